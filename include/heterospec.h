@@ -1,0 +1,183 @@
+/*
+ * heterospec.h - C ABI of the MI355X (gfx950) tree-verification library.
+ *
+ * One speculative-decoding verification step, as four asynchronous calls:
+ *
+ *   hs_draft_entropy_topk   vocabulary-wide softmax of draft logits, Top-K tokens with their
+ *                           log-probabilities, Top-K entropy          (Section 4.1 Eq. 1; Section 2.2 Expansion)
+ *   hs_tree_prune           cumulative-confidence reranking / pruning of the draft tree
+ *                                                                      (Section 2.2 Reranking; Section 4.3 Top-N Pruning)
+ *   hs_tree_attention       tree-masked attention of the kept rows over the prefix KV cache
+ *                                                                      (Section 2.2: tree-mask attention)
+ *   hs_verify_accept        greedy or stochastic accept walk           (Section 2.1 acceptance rule)
+ *
+ * Conventions that hold for every call
+ *   - Pointers are DEVICE pointers unless the parameter name starts with host_.  The caller owns
+ *     every buffer; the library allocates and frees nothing, and keeps nothing after a call.
+ *   - Scratch memory comes from the caller: `workspace` must hold at least the bytes the matching
+ *     *_workspace query returns for the same shape arguments and must be 256-byte aligned.
+ *     A smaller or NULL workspace (when the query is non-zero) gives HS_ERR_WORKSPACE.
+ *   - A call only enqueues kernels on `stream` (a hipStream_t; NULL = the default stream) and
+ *     returns.  Results are valid once the caller has synchronised that stream.  No call
+ *     synchronises the device, and none records a memset, so calls may be captured in a HIP graph.
+ *   - Host-visible arguments are validated before anything is launched; on any error nothing is
+ *     launched and hs_last_error() describes the problem.  Device-side data is trusted:
+ *     parent[i] < i, offsets non-decreasing, sibling tokens distinct, no NaN logits.
+ *   - All arrays are dense row-major.  Ragged batches are packed back to back and described by
+ *     offset arrays with B+1 entries (first 0, last the total).
+ *   - Same inputs give bit-identical outputs (no floating-point atomics).
+ *   - Trees: row 0 of each sequence is the root (the last committed token), parent[root] = -1,
+ *     parents are LOCAL indices within the sequence and parent[i] < i.
+ */
+#ifndef HETEROSPEC_H_
+#define HETEROSPEC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HS_OK = 0,
+  HS_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+  HS_ERR_SHAPE = 2,       /* a size is negative, zero where it may not be, or inconsistent */
+  HS_ERR_UNSUPPORTED = 3, /* a valid request this build has no kernel for                */
+  HS_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than the query says   */
+  HS_ERR_RUNTIME = 5      /* the HIP runtime refused a launch                            */
+} hs_status;
+
+typedef enum { HS_F32 = 0, HS_BF16 = 1 } hs_dtype;
+
+typedef enum {
+  HS_ACCEPT_GREEDY = 0,               /* temperature 0: follow the target's argmax                       */
+  HS_ACCEPT_STOCHASTIC = 1,           /* accept x with prob min(1, p(x)/p_hat(x)); residual on rejection */
+  HS_ACCEPT_STOCHASTIC_POINTMASS = 2  /* candidates treated as point-mass proposals: accept with p(x)    */
+} hs_accept_mode;
+
+typedef void* hs_stream; /* a hipStream_t */
+
+#define HS_MAX_TOPK 64
+
+/* Static description of a status code; never NULL, never freed. */
+const char* hs_status_string(hs_status st);
+/* Detail of the last error raised on the calling thread ("" if none). Valid until the next call
+ * on this thread. */
+const char* hs_last_error(void);
+/* Library version, "major.minor". */
+const char* hs_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_draft_entropy_topk  (Section 4.1, Eq. 1: the per-position term of the cumulative Top-K
+ * entropy; Section 2.2, Expansion: Top-k tokens and their confidences c_j)
+ *
+ * For each of R rows x of draft logits over V tokens, with y = x / temperature:
+ *   topk_idx [R,K]  int32  indices of the K largest logits, largest first; equal logits are
+ *                          ordered by ascending index (decided on the raw float32 values)
+ *   topk_logp[R,K]  float  log softmax(y) at those indices  (log of the confidence c)
+ *   ent_topk [R]    float  -sum_i pt_i ln pt_i over the Top-K probabilities renormalised to sum 1
+ *   ent_full [R]    float  entropy of softmax(y) over the whole vocabulary      (may be NULL)
+ *   lse      [R]    float  ln sum_v exp(y_v)                                    (may be NULL)
+ * logits: float32, row r starts at logits + r*row_stride (row_stride >= V, in elements).
+ * -inf logits are allowed (probability 0).  Natural logarithms.
+ * Requires 1 <= K <= min(V, HS_MAX_TOPK), temperature > 0, R >= 0 (R == 0 is a no-op).
+ */
+size_t hs_draft_entropy_topk_workspace(int32_t R, int32_t V, int32_t K);
+hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stride, int32_t R, int32_t V,
+                                int32_t K, float temperature,
+                                int32_t* topk_idx, float* topk_logp, float* ent_topk,
+                                float* ent_full, float* lse,
+                                void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_tree_prune  (Section 2.2: the value of node i is the product of the confidences on the path
+ * root -> i, and the best nodes by value form the verified subtree; Section 4.3: the node budget
+ * N' varies per step)
+ *
+ * B candidate trees packed by node_offsets [B+1]; NN = node_offsets[B] (passed by the caller).
+ * Per sequence s, with n = its node count and local indices:
+ *   depth[0] = 0, depth[i] = depth[parent[i]] + 1
+ *   cumlogp[0] = 0, cumlogp[i] = fl32(cumlogp[parent[i]] + min(logc[i], 0))   (one float add per node)
+ *   node i >= 1 survives iff, for i and each of its ancestors j: depth[j] <= d_max[s] and
+ *   cumlogp[j] >= theta[s]; and, when max_nodes[s] > 0 and more than max_nodes[s] nodes survive
+ *   that test, i is among the first max_nodes[s] of them ordered by (cumlogp descending, index
+ *   ascending).  The root always survives.  A filter is switched off by d_max = INT32_MAX,
+ *   theta = -inf, max_nodes = 0.
+ * Outputs: depth, cumlogp, keep (1 = survives) are indexed like the input [NN];
+ *   out_offsets [B+1] packs the surviving rows; out_src [NN'] is each surviving row's LOCAL index in
+ *   its candidate tree (ascending); out_parent [NN'] its parent as a LOCAL index among the surviving
+ *   rows (-1 for the root).  out_src / out_parent must have room for NN entries.
+ * logc[i] is the log-confidence of node i (ignored for roots).  An empty sequence (n = 0) emits nothing.
+ */
+size_t hs_tree_prune_workspace(int32_t B, int32_t NN);
+hs_status hs_tree_prune(const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                        int32_t B, int32_t NN,
+                        const int32_t* d_max, const float* theta, const int32_t* max_nodes,
+                        int32_t* depth, float* cumlogp, uint8_t* keep,
+                        int32_t* out_offsets, int32_t* out_src, int32_t* out_parent,
+                        void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_tree_attention  (Section 2.2: the pruned tree is verified in one pass with tree-mask
+ * attention)
+ *
+ * For sequence s, tree row i, query head h (KV head g = h / (Hq/Hkv)):
+ *   o[i,h,:] = softmax_j( scale * <q[i,h,:], k[j,g,:]> ) . v[j,g,:]
+ * over j = every prefix token of s, and every tree row of s on the root path of i (the root, the
+ * ancestors of i, and i itself).  One attention layer; no positional encoding is applied.
+ *   q [NN,Hq,D], o [NN,Hq,D]; k_prefix, v_prefix [total_prefix,Hkv,D]; k_tree, v_tree [NN,Hkv,D]
+ *   all of element type dt (HS_BF16: bfloat16 storage, float32 softmax state and accumulation,
+ *   output rounded once; HS_F32: float32 throughout).
+ *   parent [NN] int32 local indices; node_offsets [B+1] int32; prefix_offsets [B+1] int64 (token units).
+ *   host_node_offsets / host_prefix_offsets: HOST copies of the two offset arrays, read during the
+ *   call to size the launch; they must equal the device arrays.
+ *   lse [NN,Hq] float: ln of the softmax denominator (of the scaled scores); may be NULL.
+ * Requires Hq % Hkv == 0, D in {64, 128}, at most 1024 tree rows per sequence.
+ */
+size_t hs_tree_attention_workspace(int32_t B, int32_t NN, int64_t total_prefix,
+                                   int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt);
+hs_status hs_tree_attention(const void* q, const void* k_prefix, const void* v_prefix,
+                            const void* k_tree, const void* v_tree,
+                            const int32_t* parent, const int32_t* node_offsets,
+                            const int64_t* prefix_offsets,
+                            const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                            int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale,
+                            void* o, float* lse,
+                            void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_verify_accept  (Section 2.1: a drafted token x is accepted with probability
+ * min(1, p(x)/p_hat(x)); on rejection a token is drawn from the residual of p and later drafts are
+ * dropped.  On a tree, the children of the current node are tried in ascending row index.)
+ *
+ * target_logits [NN,V] float: row i is the target model's logits after tree row i.
+ * draft_logits  [NN,V] float: row i is the draft distribution the children of row i were proposed
+ *   from (only rows that have children are read; NULL allowed in greedy mode).
+ * token [NN] int32: the token of each row (root entry ignored).  parent / node_offsets as above.
+ * uniforms [NN + B] float in [0,1): uniforms[node] decides that node's test, uniforms[NN + s]
+ *   draws the bonus token of sequence s (NULL allowed in greedy mode).
+ * Greedy: from the root, move to the child whose token equals argmax of the target row of the
+ *   current node (ties -> lower index) until there is none; bonus = that argmax.
+ * Stochastic: p = softmax(target/T), q = softmax(draft/T) at the current node; for each child c
+ *   in order accept iff u_c < min(1, p(x_c)/q(x_c)); on rejection p <- norm(max(p - q, 0)),
+ *   q(x_c) <- 0, q <- norm(q).  If no child is accepted the bonus token is the first index whose
+ *   running sum of p exceeds u_bonus.  Point-mass variant: accept iff u_c < p(x_c); on rejection
+ *   p(x_c) <- 0, p <- norm(p).
+ * Outputs: accept_len [B] (number of accepted rows), accept_path [B,max_depth] local row indices
+ *   padded with -1, bonus_token [B] (-1 for an empty sequence).  The walk stops after max_depth
+ *   accepted rows.
+ */
+size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V);
+hs_status hs_verify_accept(const float* target_logits, const float* draft_logits,
+                           int64_t row_stride, const int32_t* token, const int32_t* parent,
+                           const int32_t* node_offsets,
+                           int32_t B, int32_t NN, int32_t V, hs_accept_mode mode, float temperature,
+                           const float* uniforms, int32_t max_depth,
+                           int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
+                           void* workspace, size_t workspace_bytes, hs_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HETEROSPEC_H_ */

@@ -1,0 +1,71 @@
+// Shared pieces of the tree-attention kernels (internal).
+//
+// Work decomposition (all kernels): grid.y = sequence, grid.x enumerates (key split, row block,
+// KV head) of that sequence; workgroups whose indices fall outside their sequence's extent exit at
+// once.  The prefix of sequence s is cut into n_sp = max(1, ceil(L_s / split_len)) splits; the last
+// split also handles the tree rows themselves (the masked part).  Rows of one KV head g are
+// r = i * G + gi for tree row i and group member gi (query head h = g * G + gi).
+//
+// Partial results (only when some sequence has more than one split): one record of D + 2 floats per
+// (node, head, split): unnormalised output o[D], running maximum m (in units of the scaled score)
+// and denominator l; slot = (node_global * Hq + h) * sp_max + split.
+#pragma once
+#include "hs_common.h"
+
+namespace hs {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __builtin_bit_cast(float, (unsigned)b << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest, ties to even
+  unsigned u = __builtin_bit_cast(unsigned, f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_elem(const T* p);
+template <>
+__device__ __forceinline__ float load_elem<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_elem<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T>
+__device__ __forceinline__ void store_elem(T* p, float v);
+template <>
+__device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_elem<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+struct AttnArgs {
+  const void* q;
+  const void* k_prefix;
+  const void* v_prefix;
+  const void* k_tree;
+  const void* v_tree;
+  const int32_t* parent;
+  const int32_t* node_offsets;
+  const int64_t* prefix_offsets;
+  int B, Hq, Hkv, G;
+  float scale;
+  int split_len;   // prefix tokens per split (multiple of 64)
+  int sp_max;      // largest split count of any sequence; 1 = results are written directly
+  int n_rb_max;    // largest row-block count of any sequence (generic kernel)
+  void* o;
+  float* lse;
+  float* part;
+};
+
+__host__ __device__ __forceinline__ int splits_of(int64_t L, int split_len) {
+  int n = (int)((L + split_len - 1) / split_len);
+  return n < 1 ? 1 : n;
+}
+
+// Is tree row j on the root path of tree row i (j == i or an ancestor)?  par: local parents.
+__device__ __forceinline__ bool on_root_path(const int* par, int i, int j) {
+  int a = i;
+  while (a > j) a = par[a];
+  return a == j;
+}
+
+}  // namespace hs

@@ -1,0 +1,94 @@
+// Internal helpers shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "heterospec.h"
+
+namespace hs {
+
+// Records the message for hs_last_error() and returns `st`.
+hs_status fail(hs_status st, const char* fmt, ...);
+void clear_error();
+
+inline hs_status launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(HS_ERR_RUNTIME, "%s: %s", what, hipGetErrorString(e));
+  return HS_OK;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Carves 256-byte aligned pieces out of the caller's workspace.
+struct Carver {
+  char* base;
+  size_t used = 0;
+  explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+  template <typename T>
+  T* take(size_t n) {
+    T* r = reinterpret_cast<T*>(base + used);
+    used += align_up(n * sizeof(T), 256);
+    return r;
+  }
+};
+
+// Row scan shared by hs_draft_entropy_topk and hs_verify_accept (defined in entropy_topk.hip).
+size_t row_topk_workspace(int R, int V, int K);
+hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
+                          int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
+                          void* workspace, hipStream_t stream);
+
+#define HS_REQUIRE(cond, st, ...) \
+  do {                            \
+    if (!(cond)) return ::hs::fail(st, __VA_ARGS__); \
+  } while (0)
+
+// ------------------------------------------------------------------ device helpers
+#define HS_INF __builtin_huge_valf()
+
+// Strict total order on (value, index): larger value first, then lower index.
+__device__ __forceinline__ bool better(float av, int ai, float bv, int bi) {
+  return av > bv || (av == bv && ai < bi);
+}
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Running softmax statistics of a set of raw logits x, with y = x * inv_t:
+//   m  = max x (raw units, so comparisons stay exact);
+//   s1 = sum exp(y - y_max) over all elements but ONE instance of the max;
+//   t  = sum exp(y - y_max) (y - y_max)   (every term <= 0).
+// Keeping the max's own unit out of s1 keeps entropy and lse accurate for nearly one-hot rows:
+//   lse = m * inv_t + log1p(s1),  entropy = log1p(s1) - t / (1 + s1).
+struct Stats {
+  float m, s1, t;
+};
+
+__device__ __forceinline__ Stats stats_empty() { return Stats{-HS_INF, 0.f, 0.f}; }
+
+__device__ __forceinline__ Stats stats_merge(Stats a, Stats b, float inv_t) {
+  if (b.m == -HS_INF) return a;
+  if (a.m == -HS_INF) return b;
+  if (b.m > a.m) {
+    Stats x = a;
+    a = b;
+    b = x;
+  }
+  float d = (b.m - a.m) * inv_t;  // <= 0
+  float e = exp2_fast(d * 1.4426950408889634f);
+  float w = 1.f + b.s1;
+  return Stats{a.m, a.s1 + e * w, a.t + e * (b.t + d * w)};
+}
+
+__device__ __forceinline__ Stats stats_shfl_xor(Stats a, int mask) {
+  return Stats{__shfl_xor(a.m, mask), __shfl_xor(a.s1, mask), __shfl_xor(a.t, mask)};
+}
+
+__device__ __forceinline__ Stats stats_wave_reduce(Stats a, float inv_t) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) a = stats_merge(a, stats_shfl_xor(a, off), inv_t);
+  return a;
+}
+
+}  // namespace hs

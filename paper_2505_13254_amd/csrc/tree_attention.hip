@@ -1,0 +1,329 @@
+// hs_tree_attention: tree-masked attention of the kept tree rows over the prefix KV cache
+// (Section 2.2: the pruned tree is verified in one pass with tree-mask attention).
+//
+// This file holds the entry point, the launch planning, the float32 / any-shape kernel
+// (k_attn_generic: vector ALU, K/V tiles staged through LDS, 16 rows per workgroup) and the
+// split combine (k_attn_combine).  bfloat16 with head dimension 128 goes to the MFMA kernel in
+// tree_attention_mfma.hip.
+#include "attn_common.h"
+
+namespace hs {
+
+hs_status attn_mfma_launch(const AttnArgs& a, const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                           hipStream_t stream);
+bool attn_mfma_supported(int D, hs_dtype dt);
+
+constexpr int GEN_THREADS = 256;
+constexpr int GEN_ROWS = 16;  // rows per workgroup (4 per wave)
+constexpr int GEN_TILE = 64;  // keys per tile (one per lane)
+constexpr int MAX_TREE_ROWS = 1024;
+
+template <typename T, int D>
+__global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
+  __shared__ float Ks[GEN_TILE][D + 1];
+  __shared__ float Vs[GEN_TILE][D];
+  __shared__ float Qs[GEN_ROWS][D];
+  __shared__ float Ps[GEN_THREADS / 64][4][GEN_TILE];
+  __shared__ int par[MAX_TREE_ROWS];
+
+  const int s = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = a.node_offsets[s];
+  const int M = a.node_offsets[s + 1] - n0;
+  const int64_t p0 = a.prefix_offsets[s];
+  const int64_t L = a.prefix_offsets[s + 1] - p0;
+  if (M <= 0) return;
+  const int G = a.G, Hkv = a.Hkv, Hq = a.Hq;
+  const int R = G * M;
+  const int n_rb = (R + GEN_ROWS - 1) / GEN_ROWS;
+  const int n_sp = splits_of(L, a.split_len);
+  int x = blockIdx.x;
+  const int g = x % Hkv;
+  x /= Hkv;
+  const int rb = x % a.n_rb_max;
+  const int sp = x / a.n_rb_max;
+  if (rb >= n_rb || sp >= n_sp) return;
+
+  const T* q = static_cast<const T*>(a.q);
+  const T* kp = static_cast<const T*>(a.k_prefix) + p0 * Hkv * D;
+  const T* vp = static_cast<const T*>(a.v_prefix) + p0 * Hkv * D;
+  const T* kt = static_cast<const T*>(a.k_tree) + (int64_t)n0 * Hkv * D;
+  const T* vt = static_cast<const T*>(a.v_tree) + (int64_t)n0 * Hkv * D;
+
+  for (int i = tid; i < M; i += GEN_THREADS) par[i] = a.parent[n0 + i];
+  const int r0 = rb * GEN_ROWS;
+  for (int e = tid; e < GEN_ROWS * D; e += GEN_THREADS) {
+    const int rr = e / D, d = e - rr * D;
+    const int r = r0 + rr;
+    float v = 0.f;
+    if (r < R) {
+      const int i = r / G, gi = r - i * G;
+      v = load_elem<T>(q + ((int64_t)(n0 + i) * Hq + g * G + gi) * D + d);
+    }
+    Qs[rr][d] = v;
+  }
+
+  constexpr int DPL = D / 64;  // output elements per lane
+  float m_run[4], l_run[4], acc[4][DPL];
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    m_run[rr] = -HS_INF;
+    l_run[rr] = 0.f;
+#pragma unroll
+    for (int dd = 0; dd < DPL; ++dd) acc[rr][dd] = 0.f;
+  }
+
+  const int64_t k_lo = (int64_t)sp * a.split_len;
+  const int64_t k_hi = (sp == n_sp - 1) ? L : k_lo + a.split_len;
+  const int n_prefix_tiles = (int)((k_hi - k_lo + GEN_TILE - 1) / GEN_TILE);
+  const int n_tree_tiles = (sp == n_sp - 1) ? (M + GEN_TILE - 1) / GEN_TILE : 0;
+
+  for (int t = 0; t < n_prefix_tiles + n_tree_tiles; ++t) {
+    const bool tree = t >= n_prefix_tiles;
+    const int64_t base = tree ? (int64_t)(t - n_prefix_tiles) * GEN_TILE : k_lo + (int64_t)t * GEN_TILE;
+    const int64_t limit = tree ? M : k_hi;
+    const T* ksrc = tree ? kt : kp;
+    const T* vsrc = tree ? vt : vp;
+    __syncthreads();  // previous tile fully consumed (and Qs / par written, first time)
+    for (int e = tid; e < GEN_TILE * D; e += GEN_THREADS) {
+      const int j = e / D, d = e - j * D;
+      const int64_t key = base + j;
+      float kv = 0.f, vv = 0.f;
+      if (key < limit) {
+        kv = load_elem<T>(ksrc + (key * Hkv + g) * D + d);
+        vv = load_elem<T>(vsrc + (key * Hkv + g) * D + d);
+      }
+      Ks[j][d] = kv;
+      Vs[j][d] = vv;
+    }
+    __syncthreads();
+
+    // scores of this wave's 4 rows against the tile's 64 keys (lane = key)
+    float sc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int d = 0; d < D; ++d) {
+      const float kv = Ks[lane][d];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) sc[rr] = fmaf(Qs[wave * 4 + rr][d], kv, sc[rr]);
+    }
+    const int64_t key = base + lane;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = r0 + wave * 4 + rr;
+      bool ok = key < limit && r < R;
+      if (ok && tree) ok = on_root_path(par, r / G, (int)key);
+      const float sv = ok ? sc[rr] * a.scale : -HS_INF;
+      float mx = sv;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      const float m_new = fmaxf(m_run[rr], mx);
+      float pj = 0.f, alpha = 1.f;
+      if (m_new != -HS_INF) {
+        pj = __expf(sv - m_new);
+        alpha = __expf(m_run[rr] - m_new);  // 0 when nothing was seen before
+      }
+      float ps = pj;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) ps += __shfl_xor(ps, off);
+      l_run[rr] = l_run[rr] * alpha + ps;
+      m_run[rr] = m_new;
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) acc[rr][dd] *= alpha;
+      Ps[wave][rr][lane] = pj;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int j = 0; j < GEN_TILE; ++j) {
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) {
+        const float vv = Vs[j][lane + 64 * dd];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) acc[rr][dd] = fmaf(Ps[wave][rr][j], vv, acc[rr][dd]);
+      }
+    }
+  }
+
+  // write the result (sp_max == 1) or this split's partial record
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int r = r0 + wave * 4 + rr;
+    if (r >= R) continue;
+    const int i = r / G, gi = r - i * G;
+    const int64_t row = (int64_t)(n0 + i) * Hq + g * G + gi;
+    if (a.sp_max == 1) {
+      T* out = static_cast<T*>(a.o) + row * D;
+      const float inv = 1.f / l_run[rr];
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) store_elem<T>(out + lane + 64 * dd, acc[rr][dd] * inv);
+      if (a.lse && lane == 0) a.lse[row] = m_run[rr] + __logf(l_run[rr]);
+    } else {
+      float* rec = a.part + (row * a.sp_max + sp) * (D + 2);
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) rec[lane + 64 * dd] = acc[rr][dd];
+      if (lane == 0) {
+        rec[D] = m_run[rr];
+        rec[D + 1] = l_run[rr];
+      }
+    }
+  }
+}
+
+// Merges the splits of one (node, head): weights exp(m_sp - max m).
+template <typename T, int D>
+__global__ __launch_bounds__(D) void k_attn_combine(AttnArgs a, int NN) {
+  const int64_t row = blockIdx.x;  // node_global * Hq + h
+  const int node = (int)(row / a.Hq);
+  // sequence of this node: last s with node_offsets[s] <= node
+  int lo = 0, hi = a.B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.node_offsets[mid] <= node) lo = mid; else hi = mid;
+  }
+  const int64_t L = a.prefix_offsets[lo + 1] - a.prefix_offsets[lo];
+  const int n_sp = splits_of(L, a.split_len);
+  const float* rec = a.part + row * a.sp_max * (D + 2);
+  float m = -HS_INF;
+  for (int sp = 0; sp < n_sp; ++sp) m = fmaxf(m, rec[sp * (D + 2) + D]);
+  float l = 0.f, o = 0.f;
+  const int d = threadIdx.x;
+  for (int sp = 0; sp < n_sp; ++sp) {
+    const float* r = rec + sp * (D + 2);
+    const float w = __expf(r[D] - m);
+    l = fmaf(r[D + 1], w, l);
+    o = fmaf(r[d], w, o);
+  }
+  store_elem<T>(static_cast<T*>(a.o) + row * D + d, o / l);
+  if (a.lse && d == 0) a.lse[row] = m + __logf(l);
+}
+
+struct AttnPlan {
+  int split_len, sp_max, n_rb_max, max_rows;
+  int64_t max_L;
+  bool ok;
+};
+
+// Chooses the split length from the host copies of the offsets: enough workgroups to fill the
+// chip, but splits long enough that partial records stay small next to the K/V they summarise.
+static AttnPlan plan_attention(const int32_t* hno, const int64_t* hpo, int B, int Hq, int Hkv, int rows_per_wg,
+                               int target_wgs) {
+  AttnPlan p{};
+  int max_M = 0;
+  int64_t max_L = 0, sum_L = 0;
+  for (int s = 0; s < B; ++s) {
+    const int M = hno[s + 1] - hno[s];
+    const int64_t L = hpo[s + 1] - hpo[s];
+    if (M > max_M) max_M = M;
+    if (M > 0) {
+      if (L > max_L) max_L = L;
+      sum_L += L;
+    }
+  }
+  p.max_rows = max_M;
+  p.max_L = max_L;
+  const int G = Hq / Hkv;
+  p.n_rb_max = rows_per_wg > 0 ? (G * max_M + rows_per_wg - 1) / rows_per_wg : 1;
+  if (p.n_rb_max < 1) p.n_rb_max = 1;
+  // workgroups without splitting: one per (sequence, head, row block); split until the target is met
+  const int64_t base_wgs = (int64_t)B * Hkv * p.n_rb_max;
+  int64_t want = base_wgs > 0 ? (target_wgs + base_wgs - 1) / base_wgs : 1;  // splits per average sequence
+  if (want < 1) want = 1;
+  const int64_t mean_L = B > 0 ? sum_L / B : 0;
+  int64_t len = (mean_L + want - 1) / want;
+  len = (len + 255) / 256 * 256;   // multiple of 256 tokens
+  if (len < 512) len = 512;        // never split finer than 512 tokens
+  p.split_len = (int)len;
+  p.sp_max = splits_of(max_L, p.split_len);
+  p.ok = true;
+  return p;
+}
+
+}  // namespace hs
+
+using namespace hs;
+
+static size_t part_bytes(int64_t NN, int Hq, int D, int sp_max) {
+  if (sp_max <= 1) return 0;
+  return align_up((size_t)NN * Hq * sp_max * (D + 2) * sizeof(float), 256);
+}
+
+extern "C" size_t hs_tree_attention_workspace(int32_t B, int32_t NN, int64_t total_prefix, int32_t Hq, int32_t Hkv,
+                                              int32_t D, hs_dtype dt) {
+  (void)dt;
+  if (B <= 0 || NN <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || total_prefix < 0) return 0;
+  // upper bound over every plan the launch may choose: splits are at least 512 tokens long
+  const int64_t sp_bound = total_prefix / 512 + 1;
+  return part_bytes(NN, Hq, D, (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound));
+}
+
+extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
+                                       const void* v_tree, const int32_t* parent, const int32_t* node_offsets,
+                                       const int64_t* prefix_offsets, const int32_t* host_node_offsets,
+                                       const int64_t* host_prefix_offsets, int32_t B, int32_t Hq, int32_t Hkv,
+                                       int32_t D, hs_dtype dt, float scale, void* o, float* lse, void* workspace,
+                                       size_t workspace_bytes, hs_stream stream) {
+  clear_error();
+  HS_REQUIRE(B >= 0, HS_ERR_SHAPE, "hs_tree_attention: B=%d", B);
+  HS_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, HS_ERR_SHAPE, "hs_tree_attention: Hq=%d must be a multiple of Hkv=%d",
+             Hq, Hkv);
+  HS_REQUIRE(D == 64 || D == 128, HS_ERR_UNSUPPORTED, "hs_tree_attention: head dimension %d (64 and 128 are built)", D);
+  HS_REQUIRE(dt == HS_F32 || dt == HS_BF16, HS_ERR_SHAPE, "hs_tree_attention: unknown dtype %d", (int)dt);
+  if (B == 0) return HS_OK;
+  HS_REQUIRE(host_node_offsets && host_prefix_offsets && node_offsets && prefix_offsets, HS_ERR_NULL,
+             "hs_tree_attention: offset arrays (device and host copies) are required");
+  HS_REQUIRE(host_node_offsets[0] == 0 && host_prefix_offsets[0] == 0, HS_ERR_SHAPE,
+             "hs_tree_attention: offsets must start at 0");
+  for (int s = 0; s < B; ++s) {
+    const int M = host_node_offsets[s + 1] - host_node_offsets[s];
+    HS_REQUIRE(M >= 0 && host_prefix_offsets[s + 1] >= host_prefix_offsets[s], HS_ERR_SHAPE,
+               "hs_tree_attention: offsets decrease at sequence %d", s);
+    HS_REQUIRE(M <= MAX_TREE_ROWS, HS_ERR_UNSUPPORTED, "hs_tree_attention: sequence %d has %d tree rows (limit %d)", s,
+               M, MAX_TREE_ROWS);
+  }
+  const int NN = host_node_offsets[B];
+  const int64_t total_prefix = host_prefix_offsets[B];
+  if (NN == 0) return HS_OK;
+  HS_REQUIRE(q && k_tree && v_tree && parent && o, HS_ERR_NULL, "hs_tree_attention: NULL tensor");
+  HS_REQUIRE(total_prefix == 0 || (k_prefix && v_prefix), HS_ERR_NULL, "hs_tree_attention: NULL prefix cache");
+
+  const bool mfma = attn_mfma_supported(D, dt);
+  AttnPlan plan = plan_attention(host_node_offsets, host_prefix_offsets, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, 1024);
+  // the workspace bound assumes at most 64 splits per sequence
+  while (plan.sp_max > 64) {
+    plan.split_len *= 2;
+    plan.sp_max = splits_of(plan.max_L, plan.split_len);
+  }
+  const size_t need = part_bytes(NN, Hq, D, plan.sp_max);
+  HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
+             HS_ERR_WORKSPACE, "hs_tree_attention: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+             workspace_bytes);
+
+  AttnArgs a;
+  a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_tree = k_tree; a.v_tree = v_tree;
+  a.parent = parent; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets;
+  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
+  a.split_len = plan.split_len; a.sp_max = plan.sp_max; a.n_rb_max = plan.n_rb_max;
+  a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  if (mfma) {
+    hs_status r = attn_mfma_launch(a, host_node_offsets, host_prefix_offsets, st);
+    if (r != HS_OK) return r;
+  } else {
+    dim3 grid((unsigned)(Hkv * plan.n_rb_max * plan.sp_max), (unsigned)B);
+    if (dt == HS_F32 && D == 64) hipLaunchKernelGGL((k_attn_generic<float, 64>), grid, dim3(GEN_THREADS), 0, st, a);
+    else if (dt == HS_F32) hipLaunchKernelGGL((k_attn_generic<float, 128>), grid, dim3(GEN_THREADS), 0, st, a);
+    else if (D == 64) hipLaunchKernelGGL((k_attn_generic<bf16_t, 64>), grid, dim3(GEN_THREADS), 0, st, a);
+    else hipLaunchKernelGGL((k_attn_generic<bf16_t, 128>), grid, dim3(GEN_THREADS), 0, st, a);
+    hs_status r = launch_status("tree attention");
+    if (r != HS_OK) return r;
+  }
+  if (plan.sp_max > 1) {
+    dim3 grid((unsigned)((int64_t)NN * Hq));
+    if (dt == HS_F32 && D == 64) hipLaunchKernelGGL((k_attn_combine<float, 64>), grid, dim3(64), 0, st, a, NN);
+    else if (dt == HS_F32) hipLaunchKernelGGL((k_attn_combine<float, 128>), grid, dim3(128), 0, st, a, NN);
+    else if (D == 64) hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, dim3(64), 0, st, a, NN);
+    else hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, dim3(128), 0, st, a, NN);
+    return launch_status("tree attention combine");
+  }
+  return HS_OK;
+}

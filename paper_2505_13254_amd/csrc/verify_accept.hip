@@ -1,0 +1,367 @@
+// hs_verify_accept: the accept walk over a verified draft tree (Section 2.1 acceptance rule, applied
+// to the children of each node in turn).
+//
+// Stage A (all rows in parallel, HBM-bound): the row scan finds every target row's argmax and
+// softmax normaliser (and every draft row's normaliser in the stochastic modes).
+// Stage B (one workgroup per sequence, latency-bound):
+//   greedy      every node checks in parallel whether its whole root path is confirmed by the
+//               target's argmax; the deepest confirmed node is the end of the accepted path.
+//   stochastic  the walk is serial by nature.  Per rejection the normaliser of the residual
+//               distribution needs one cooperative pass over the node's two vocabulary rows; the
+//               residual itself is never materialised: after j rejections at a node it is
+//               max(p(v) - beta_j q(v), 0) for every token not yet rejected (beta_j a scalar that
+//               accumulates Z_i / (1 - sum of rejected q)), and frozen at its value of the time for a
+//               rejected token.  The bonus token is an inverse-CDF search done as row sums of 64
+//               tokens, a scan of the row sums, and a scan inside the one row that is hit.
+#include <limits.h>
+
+#include "hs_common.h"
+
+namespace hs {
+
+constexpr int GR_THREADS = 256;
+constexpr int AC_THREADS = 1024;
+constexpr int AC_WAVES = AC_THREADS / 64;
+constexpr int AC_MAX_KIDS = 256;    // children tried per node
+constexpr int AC_MAX_ROWS = 8192;   // 64-token rows of the CDF search held in LDS (V <= 524288)
+
+// ----------------------------------------------------------------------------------- greedy
+__global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(const int32_t* __restrict__ arg,
+                                                              const int32_t* __restrict__ token,
+                                                              const int32_t* __restrict__ parent,
+                                                              const int32_t* __restrict__ node_offsets,
+                                                              int max_depth, int32_t* __restrict__ accept_len,
+                                                              int32_t* __restrict__ accept_path,
+                                                              int32_t* __restrict__ bonus_token) {
+  __shared__ long long red[GR_THREADS / 64];
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const int o = node_offsets[s];
+  const int n = node_offsets[s + 1] - o;
+  int32_t* path = accept_path + (int64_t)s * max_depth;
+  for (int d = tid; d < max_depth; d += GR_THREADS) path[d] = -1;
+  if (n <= 0) {
+    if (tid == 0) {
+      accept_len[s] = 0;
+      bonus_token[s] = -1;
+    }
+    return;
+  }
+  // key = depth of a fully confirmed node (higher wins), then lower index
+  long long best = ((long long)0 << 32) | (unsigned)(INT_MAX - 0);  // the root: depth 0
+  for (int i = tid; i < n; i += GR_THREADS) {
+    bool ok = true;
+    int d = 0;
+    for (int j = i; j > 0;) {
+      const int p = parent[o + j];
+      ok = ok && (token[o + j] == arg[o + p]);
+      j = p;
+      ++d;
+    }
+    if (ok && d <= max_depth) {
+      long long key = ((long long)d << 32) | (unsigned)(INT_MAX - i);
+      best = key > best ? key : best;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    long long other = __shfl_xor(best, off);
+    best = other > best ? other : best;
+  }
+  if ((tid & 63) == 0) red[tid >> 6] = best;
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < GR_THREADS / 64; ++w) best = red[w] > best ? red[w] : best;
+    const int d = (int)(best >> 32);
+    int node = INT_MAX - (int)(best & 0xffffffffll);
+    accept_len[s] = d;
+    bonus_token[s] = arg[o + node];
+    for (int k = d - 1; k >= 0; --k) {
+      path[k] = node;
+      node = parent[o + node];
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------- stochastic
+struct RowView {
+  const float* x;  // logits row
+  float m;         // its maximum
+  float lz;        // -ln(sum exp((x - m) / T))
+  float inv_t;
+  __device__ __forceinline__ float prob(int v) const { return __expf(fmaf(x[v] - m, inv_t, lz)); }
+};
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+__device__ __forceinline__ double wave_incl_scan(double v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    double o = __shfl_up(v, off);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+// Weight of token v in the current (unnormalised) distribution, ignoring frozen tokens.
+__device__ __forceinline__ double weight(const RowView& p, const RowView& q, bool use_q, double beta, int v) {
+  double w = (double)p.prob(v);
+  if (use_q) w = fmax(w - beta * (double)q.prob(v), 0.0);
+  return w;
+}
+
+__global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
+    const float* __restrict__ target, const float* __restrict__ draft, int64_t row_stride,
+    const int32_t* __restrict__ token, const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets,
+    int NN, int V, int mode, float inv_t, const float* __restrict__ uniforms, int max_depth,
+    const int32_t* __restrict__ t_arg, const float* __restrict__ t_lz, const int32_t* __restrict__ d_arg,
+    const float* __restrict__ d_lz, int32_t* __restrict__ accept_len, int32_t* __restrict__ accept_path,
+    int32_t* __restrict__ bonus_token) {
+  __shared__ int kids[AC_MAX_KIDS];
+  __shared__ int kids_sorted[AC_MAX_KIDS];
+  __shared__ int n_kids;
+  __shared__ int rej_tok[AC_MAX_KIDS];
+  __shared__ double rej_w[AC_MAX_KIDS];  // frozen weight of each rejected token
+  __shared__ double red[AC_WAVES];
+  __shared__ double rowsum[AC_MAX_ROWS];
+  __shared__ int found_row;
+  __shared__ double found_excl;
+  __shared__ int found_tok;
+
+  const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int o = node_offsets[s];
+  const int n = node_offsets[s + 1] - o;
+  int32_t* path = accept_path + (int64_t)s * max_depth;
+  for (int d = tid; d < max_depth; d += AC_THREADS) path[d] = -1;
+  if (n <= 0) {
+    if (tid == 0) {
+      accept_len[s] = 0;
+      bonus_token[s] = -1;
+    }
+    return;
+  }
+  const bool ratio_mode = mode == HS_ACCEPT_STOCHASTIC;
+  int cur = 0, len = 0;
+  for (;;) {
+    // ---- children of cur, ascending
+    if (tid == 0) n_kids = 0;
+    __syncthreads();
+    if (len < max_depth)
+      for (int i = 1 + tid; i < n; i += AC_THREADS)
+        if (parent[o + i] == cur) {
+          int pos = atomicAdd(&n_kids, 1);
+          if (pos < AC_MAX_KIDS) kids[pos] = i;
+        }
+    __syncthreads();
+    const int nk = n_kids < AC_MAX_KIDS ? n_kids : AC_MAX_KIDS;
+    if (tid < nk) {
+      int me = kids[tid], r = 0;
+      for (int j = 0; j < nk; ++j) r += kids[j] < me ? 1 : 0;
+      kids_sorted[r] = me;
+    }
+    __syncthreads();
+
+    RowView p{target + (int64_t)(o + cur) * row_stride, 0.f, t_lz[o + cur], inv_t};
+    p.m = p.x[t_arg[o + cur]];
+    RowView q = p;
+    const bool use_q = ratio_mode && nk > 0;
+    if (use_q) {
+      q.x = draft + (int64_t)(o + cur) * row_stride;
+      q.lz = d_lz[o + cur];
+      q.m = q.x[d_arg[o + cur]];
+    }
+
+    // ---- try the children in order (every thread runs the same scalar logic)
+    double beta = 0.0, Z = 1.0, sumq = 0.0, rem = 1.0;
+    int n_rej = 0, accepted = -1;
+    for (int j = 0; j < nk; ++j) {
+      const int c = kids_sorted[j];
+      const int x = token[o + c];
+      const double u = (double)uniforms[o + c];
+      const double px = (double)p.prob(x);
+      if (!ratio_mode) {
+        if (u * rem < px) {  // u < p(x) / rem
+          accepted = c;
+          break;
+        }
+        rem -= px;
+        if (tid == 0) {
+          rej_tok[n_rej] = x;
+          rej_w[n_rej] = 0.0;
+        }
+        ++n_rej;
+        __syncthreads();
+        continue;
+      }
+      const double qx = (double)q.prob(x);
+      const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
+      const double qc = qx / (1.0 - sumq);              // current q(x)
+      if (pc >= qc || u * qc < pc) {
+        accepted = c;
+        break;
+      }
+      // rejected: p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)
+      beta += Z / (1.0 - sumq);
+      sumq += qx;
+      if (tid == 0) {
+        rej_tok[n_rej] = x;
+        rej_w[n_rej] = fmax(px - beta * qx, 0.0);
+      }
+      ++n_rej;
+      double acc = 0.0;
+      for (int v = tid; v < V; v += AC_THREADS) acc += weight(p, q, true, beta, v);
+      acc = wave_sum(acc);
+      __syncthreads();  // rej_* visible; red free
+      if (lane == 0) red[wave] = acc;
+      __syncthreads();
+      double F = 0.0;
+      for (int w = 0; w < AC_WAVES; ++w) F += red[w];
+      for (int i = 0; i < n_rej; ++i) F += rej_w[i] - weight(p, q, true, beta, rej_tok[i]);
+      Z = F;
+      __syncthreads();
+    }
+    if (accepted >= 0) {
+      if (tid == 0) path[len] = accepted;
+      ++len;
+      cur = accepted;
+      continue;
+    }
+
+    // ---- no child accepted: draw the bonus token from the current distribution
+    const bool sub_q = use_q && n_rej > 0;
+    const double total = ratio_mode ? Z : rem;
+    const double goal = (double)uniforms[NN + s] * total;
+    const int n_rows = (V + 63) / 64;
+    for (int r = wave; r < n_rows; r += AC_WAVES) {
+      const int v = r * 64 + lane;
+      double w = v < V ? weight(p, q, sub_q, beta, v) : 0.0;
+      w = wave_sum(w);
+      if (lane == 0) rowsum[r] = w;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      for (int i = 0; i < n_rej; ++i)
+        rowsum[rej_tok[i] >> 6] += rej_w[i] - weight(p, q, sub_q, beta, rej_tok[i]);
+      found_row = -1;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      double carry = 0.0;
+      int row = -1, last_pos = -1;
+      double excl = 0.0;
+      for (int base = 0; base < n_rows && row < 0; base += 64) {
+        const int r = base + lane;
+        const double val = r < n_rows ? rowsum[r] : 0.0;
+        const double incl = wave_incl_scan(val, lane) + carry;
+        const unsigned long long hit = __ballot(r < n_rows && incl > goal);
+        const unsigned long long pos = __ballot(r < n_rows && val > 0.0);
+        if (hit != 0ull) {
+          const int l = __ffsll((long long)hit) - 1;
+          row = base + l;
+          excl = __shfl(incl - val, l);
+        } else {
+          if (pos != 0ull) last_pos = base + 63 - __clzll((long long)pos);
+          carry = __shfl(incl, 63);
+        }
+      }
+      double row_goal = goal - excl;
+      if (row < 0) {  // rounding left the goal at or above the total: take the last token with mass
+        row = last_pos < 0 ? 0 : last_pos;
+        row_goal = HS_INF;
+      }
+      const int v = row * 64 + lane;
+      double w = v < V ? weight(p, q, sub_q, beta, v) : 0.0;
+      for (int i = 0; i < n_rej; ++i)
+        if (rej_tok[i] == v) w = rej_w[i];
+      const double incl = wave_incl_scan(w, lane);
+      const unsigned long long hit = __ballot(incl > row_goal);
+      const unsigned long long pos = __ballot(w > 0.0);
+      int l;
+      if (hit != 0ull)
+        l = __ffsll((long long)hit) - 1;
+      else
+        l = pos != 0ull ? 63 - __clzll((long long)pos) : 0;
+      if (lane == 0) {
+        accept_len[s] = len;
+        int tok = row * 64 + l;
+        bonus_token[s] = tok < V ? tok : V - 1;
+      }
+    }
+    return;
+  }
+}
+
+}  // namespace hs
+
+extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
+  if (B <= 0 || NN <= 0 || V <= 0) return 0;
+  // per row: argmax, -ln Z and an unused Top-1 entropy, for the target and for the draft rows
+  const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
+  return 2 * per_set + hs::row_topk_workspace(NN, V, 1);
+}
+
+extern "C" hs_status hs_verify_accept(const float* target_logits, const float* draft_logits, int64_t row_stride,
+                                      const int32_t* token, const int32_t* parent, const int32_t* node_offsets,
+                                      int32_t B, int32_t NN, int32_t V, hs_accept_mode mode, float temperature,
+                                      const float* uniforms, int32_t max_depth, int32_t* accept_len,
+                                      int32_t* accept_path, int32_t* bonus_token, void* workspace,
+                                      size_t workspace_bytes, hs_stream stream) {
+  hs::clear_error();
+  HS_REQUIRE(B >= 0 && NN >= 0 && V >= 1, HS_ERR_SHAPE, "hs_verify_accept: B=%d NN=%d V=%d", B, NN, V);
+  HS_REQUIRE(max_depth >= 1, HS_ERR_SHAPE, "hs_verify_accept: max_depth=%d must be at least 1", max_depth);
+  HS_REQUIRE(row_stride >= V, HS_ERR_SHAPE, "hs_verify_accept: row_stride=%lld < V=%d", (long long)row_stride, V);
+  HS_REQUIRE(mode == HS_ACCEPT_GREEDY || mode == HS_ACCEPT_STOCHASTIC || mode == HS_ACCEPT_STOCHASTIC_POINTMASS,
+             HS_ERR_SHAPE, "hs_verify_accept: unknown mode %d", (int)mode);
+  if (B == 0) return HS_OK;
+  HS_REQUIRE(node_offsets && accept_len && accept_path && bonus_token, HS_ERR_NULL, "hs_verify_accept: NULL argument");
+  const bool stochastic = mode != HS_ACCEPT_GREEDY;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (NN > 0) {
+    HS_REQUIRE(target_logits && token && parent, HS_ERR_NULL, "hs_verify_accept: NULL node array");
+    if (stochastic) {
+      HS_REQUIRE(uniforms, HS_ERR_NULL, "hs_verify_accept: uniforms are required in the stochastic modes");
+      HS_REQUIRE(mode != HS_ACCEPT_STOCHASTIC || draft_logits, HS_ERR_NULL,
+                 "hs_verify_accept: draft_logits are required in mode HS_ACCEPT_STOCHASTIC");
+      HS_REQUIRE(temperature > 0.f, HS_ERR_SHAPE, "hs_verify_accept: temperature must be positive");
+      HS_REQUIRE((V + 63) / 64 <= hs::AC_MAX_ROWS, HS_ERR_UNSUPPORTED,
+                 "hs_verify_accept: stochastic modes support V <= %d", hs::AC_MAX_ROWS * 64);
+    }
+  }
+  const size_t need = hs_verify_accept_workspace(B, NN, V);
+  HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
+             HS_ERR_WORKSPACE, "hs_verify_accept: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+             workspace_bytes);
+  int32_t *t_arg = nullptr, *d_arg = nullptr;
+  float *t_lz = nullptr, *d_lz = nullptr;
+  if (NN > 0) {
+    hs::Carver c(workspace);
+    t_arg = c.take<int32_t>(NN);
+    t_lz = c.take<float>(NN);
+    float* t_ent = c.take<float>(NN);
+    d_arg = c.take<int32_t>(NN);
+    d_lz = c.take<float>(NN);
+    float* d_ent = c.take<float>(NN);
+    void* scan_ws = c.take<char>(0);
+    const float T = stochastic ? temperature : 1.0f;
+    hs_status r = hs::row_topk_launch(target_logits, row_stride, NN, V, 1, T, t_arg, t_lz, t_ent, nullptr, nullptr,
+                                      scan_ws, st);
+    if (r != HS_OK) return r;
+    if (mode == HS_ACCEPT_STOCHASTIC) {
+      r = hs::row_topk_launch(draft_logits, row_stride, NN, V, 1, T, d_arg, d_lz, d_ent, nullptr, nullptr, scan_ws,
+                              st);
+      if (r != HS_OK) return r;
+    }
+  }
+  if (!stochastic) {
+    hipLaunchKernelGGL(hs::k_accept_greedy, dim3(B), dim3(hs::GR_THREADS), 0, st, t_arg, token, parent, node_offsets,
+                       max_depth, accept_len, accept_path, bonus_token);
+    return hs::launch_status("accept (greedy)");
+  }
+  hipLaunchKernelGGL(hs::k_accept_walk, dim3(B), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits, row_stride,
+                     token, parent, node_offsets, NN, V, (int)mode, 1.0f / temperature, uniforms, max_depth, t_arg,
+                     t_lz, d_arg, d_lz, accept_len, accept_path, bonus_token);
+  return hs::launch_status("accept (stochastic)");
+}

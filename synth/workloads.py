@@ -205,7 +205,7 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
     vp = rng.normal(_key(w, seed, _T_VP, s), L * w.Hkv * D).reshape(L, w.Hkv, D) / np.sqrt(D)
     kt = rng.normal(_key(w, seed, _T_KT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) * sc
     vt = rng.normal(_key(w, seed, _T_VT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) / np.sqrt(D)
-    if variant == "peaky":
+    if variant == "peaky" and M > 0:
         G = w.Hq // w.Hkv
         picks = rng.randint(_key(w, seed, _T_PLANT, s), 4 * 8, 0, 1 << 30).reshape(8, 4)
         for a, b, c, d in picks:
@@ -222,7 +222,7 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
                 while parent is not None and steps > 0 and parent[j] >= 0:
                     j = int(parent[j]); steps -= 1
                 kt[j, g] = unit * amp                               # an ancestor (or the row itself)
-    elif variant not in ("config", "unit"):
+    elif variant not in ("config", "unit", "peaky"):
         raise ValueError(variant)
     return tuple(_quantise(w, t) for t in (q, kp, vp, kt, vt))
 

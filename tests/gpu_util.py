@@ -1,0 +1,71 @@
+"""Helpers for the GPU parity tests: numpy <-> device tensors and the four calls on a step."""
+import numpy as np
+import torch
+
+import paper_2505_13254_amd as hs
+
+DEV = "cuda:0"
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV)
+
+
+def dev_store(x):
+    """A stored attention tensor (float32, or uint16 bfloat16 bit patterns) as a device tensor."""
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(x).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy()
+    return t.cpu().numpy()
+
+
+def run_entropy(rows, K, T=1.0):
+    out = hs.hs_draft_entropy_topk(dev(rows), K, T)
+    return {k: host(v) for k, v in out.items()}
+
+
+def run_prune(pin):
+    out = hs.hs_tree_prune(dev(pin["parent"], torch.int32), dev(pin["logc"], torch.float32),
+                           dev(pin["node_offsets"], torch.int32), dev(pin["d_max"], torch.int32),
+                           dev(pin["theta"], torch.float32), dev(pin["max_nodes"], torch.int32))
+    r = {k: host(v) for k, v in out.items()}
+    n = int(r["out_offsets"][-1])
+    r["out_src"], r["out_parent"] = r["out_src"][:n], r["out_parent"][:n]
+    return r
+
+
+def run_attention(step, want_lse=True):
+    no = np.asarray(step["node_offsets"], np.int32)
+    po = np.asarray(step["prefix_offsets"], np.int64)
+    o, lse = hs.hs_tree_attention(dev_store(step["q"]), dev_store(step["k_prefix"]), dev_store(step["v_prefix"]),
+                                  dev_store(step["k_tree"]), dev_store(step["v_tree"]),
+                                  dev(step["parent"], torch.int32), dev(no), dev(po),
+                                  torch.from_numpy(no), torch.from_numpy(po), float(step["scale"]), want_lse=want_lse)
+    return host(o), (host(lse) if lse is not None else None)
+
+
+def run_accept(step, mode, uniforms, max_depth, temperature=None):
+    w = step["w"]
+    out = hs.hs_verify_accept(dev(step["target_logits"]), dev(step["draft_logits"]) if mode != 0 else None,
+                              dev(step["token"], torch.int32), dev(step["parent"], torch.int32),
+                              dev(step["node_offsets"], torch.int32), mode,
+                              w.temperature if temperature is None else temperature,
+                              dev(uniforms, torch.float32) if uniforms is not None else None, max_depth)
+    return {k: host(v) for k, v in out.items()}
+
+
+def entropy_err(got, want):
+    """Worst |dH| in units of the tolerance 1e-5 * max(|H|, 1e-3) (the stated float32 entropy
+    tolerance with an absolute floor); a value <= 1 passes."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    return float(np.max(np.abs(got - want) / (1e-5 * np.maximum(np.abs(want), 1e-3))))

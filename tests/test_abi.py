@@ -1,0 +1,96 @@
+"""The C-ABI library loads and exports every symbol the header declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2505_13254_amd", "libheterospec.so")
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "heterospec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hs_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import sys
+        sys.path.insert(0, ROOT)
+        from paper_2505_13254_amd.build import build
+        build(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_four_calls():
+    names = _declared()
+    for n in ("hs_draft_entropy_topk", "hs_tree_prune", "hs_tree_attention", "hs_verify_accept"):
+        assert n in names and n + "_workspace" in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for n in _declared():
+        assert hasattr(lib, n), n
+
+
+def test_binding_signatures_cover_the_header():
+    from paper_2505_13254_amd import binding
+    assert binding.exported_symbols() == _declared()
+
+
+def test_host_side_calls(lib):
+    lib.hs_version.restype = ctypes.c_char_p
+    lib.hs_status_string.restype = ctypes.c_char_p
+    lib.hs_last_error.restype = ctypes.c_char_p
+    assert lib.hs_version().decode()[0].isdigit()
+    assert b"workspace" in lib.hs_status_string(4)
+    # workspace queries are plain host arithmetic
+    f = lib.hs_draft_entropy_topk_workspace
+    f.restype, f.argtypes = ctypes.c_size_t, [ctypes.c_int32] * 3
+    assert f(61, 128256, 10) > 0 and f(61, 128256, 10) % 256 == 0 and f(0, 128256, 10) == 0
+    g = lib.hs_tree_attention_workspace
+    g.restype = ctypes.c_size_t
+    g.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                  ctypes.c_int]
+    assert g(1, 61, 2048, 32, 8, 128, 1) % 256 == 0
+
+
+def test_argument_validation_needs_no_gpu(lib):
+    # errors are found on the host before anything is launched
+    fn = lib.hs_draft_entropy_topk
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float] + \
+                  [ctypes.c_void_p] * 6 + [ctypes.c_size_t, ctypes.c_void_p]
+    lib.hs_last_error.restype = ctypes.c_char_p
+    assert fn(None, 100, 4, 100, 0, 1.0, None, None, None, None, None, None, 0, None) == 2       # K = 0
+    assert b"K=0" in lib.hs_last_error()
+    assert fn(None, 100, 4, 100, 65, 1.0, None, None, None, None, None, None, 0, None) == 3      # K > 64
+    assert fn(None, 10, 4, 100, 5, 1.0, None, None, None, None, None, None, 0, None) == 2        # stride < V
+    assert fn(None, 100, 4, 100, 5, 1.0, None, None, None, None, None, None, 0, None) == 1       # NULL logits
+    assert fn(None, 100, 0, 100, 5, 1.0, None, None, None, None, None, None, 0, None) == 0       # R = 0: no-op
+    pr = lib.hs_tree_prune
+    pr.restype = ctypes.c_int
+    pr.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int32] * 2 + [ctypes.c_void_p] * 10 + [ctypes.c_size_t, ctypes.c_void_p]
+    assert pr(None, None, None, -1, 0, *([None] * 10), 0, None) == 2
+    assert pr(None, None, None, 2, 5, *([None] * 10), 0, None) == 1
+    at = lib.hs_tree_attention
+    at.restype = ctypes.c_int
+    at.argtypes = [ctypes.c_void_p] * 10 + [ctypes.c_int32] * 4 + [ctypes.c_int, ctypes.c_float] + \
+                  [ctypes.c_void_p] * 3 + [ctypes.c_size_t, ctypes.c_void_p]
+    assert at(*([None] * 10), 1, 6, 4, 128, 1, 0.1, None, None, None, 0, None) == 2             # Hq % Hkv
+    assert at(*([None] * 10), 1, 8, 4, 96, 1, 0.1, None, None, None, 0, None) == 3              # D = 96
+    hno = (ctypes.c_int32 * 2)(0, 2000)
+    hpo = (ctypes.c_int64 * 2)(0, 10)
+    dummy = ctypes.c_void_p(256)
+    assert at(dummy, dummy, dummy, dummy, dummy, dummy, dummy, dummy, ctypes.cast(hno, ctypes.c_void_p),
+              ctypes.cast(hpo, ctypes.c_void_p), 1, 8, 4, 128, 1, 0.1, dummy, None, None, 0, None) == 3  # > 1024 rows
+    va = lib.hs_verify_accept
+    va.restype = ctypes.c_int
+    va.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int64] + [ctypes.c_void_p] * 3 + [ctypes.c_int32] * 3 + \
+                  [ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_int32] + [ctypes.c_void_p] * 4 + \
+                  [ctypes.c_size_t, ctypes.c_void_p]
+    assert va(None, None, 10, None, None, None, 1, 4, 10, 0, 1.0, None, 0, None, None, None, None, 0, None) == 2  # max_depth
+    assert va(None, None, 10, None, None, None, 1, 4, 10, 7, 1.0, None, 3, None, None, None, None, 0, None) == 2  # mode

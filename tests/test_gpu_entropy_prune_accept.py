@@ -1,0 +1,196 @@
+"""GPU parity of hs_draft_entropy_topk, hs_tree_prune and hs_verify_accept against the CPU checker:
+bit-exact indices / kept sets / paths, entropies within 1e-5 relative."""
+import math
+
+import numpy as np
+import pytest
+
+from synth import workloads as W
+from oracle import draft_entropy_topk, tree_prune, verify_accept, pipeline as P
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _check_entropy(G, rows, K, T=1.0, logp_tol=2e-5):
+    want = draft_entropy_topk(rows, K, T)
+    got = G.run_entropy(rows, K, T)
+    assert np.array_equal(got["topk_idx"], want["topk_idx"])
+    fin = np.isfinite(want["topk_logp"])
+    worst = float(np.max(np.abs(got["topk_logp"][fin] - want["topk_logp"][fin]) / np.maximum(1, np.abs(want["topk_logp"][fin]))))
+    assert worst <= logp_tol, worst
+    assert np.array_equal(np.isfinite(got["topk_logp"]), fin)
+    assert G.entropy_err(got["ent_topk"], want["ent_topk"]) <= 1.0
+    assert G.entropy_err(got["ent_full"], want["ent_full"]) <= 1.0
+    worst = float(np.max(np.abs(got["lse"] - want["lse"]) / np.maximum(1, np.abs(want["lse"]))))
+    assert worst <= 2e-6, worst
+    return got, want
+
+
+def test_entropy_workload1_rows(G):
+    w = W.WORKLOADS[1]
+    rows = W.logits_rows(w, 0, "draft", 0, range(17))
+    _check_entropy(G, rows, 10)
+    _check_entropy(G, rows, 10, T=0.7)
+
+
+@pytest.mark.parametrize("R,V,K", [(1, 5, 5), (3, 64, 1), (2, 1000, 64), (5, 4097, 7), (1, 131, 3), (7, 20000, 10),
+                                   (300, 777, 4), (2, 262147, 10)])
+def test_entropy_shapes_spanning_tiles_and_tails(G, R, V, K):
+    rs = np.random.RandomState(R * 1000 + V)
+    rows = (rs.randn(R, V) * rs.uniform(0.3, 10, size=(R, 1))).astype(np.float32)
+    _check_entropy(G, rows, K)
+
+
+def test_entropy_edge_rows(G):
+    V, K = 9000, 10
+    rs = np.random.RandomState(1)
+    rows = np.zeros((8, V), np.float32)
+    rows[0] = 2.5                                            # all equal: indices 0..K-1, ln V, ln K
+    rows[1, 4321] = 60.0                                     # one-hot
+    rows[2] = np.sort(rs.randn(V)).astype(np.float32)        # ascending: every tile raises the threshold
+    rows[3] = -np.sort(rs.randn(V)).astype(np.float32)       # descending
+    rows[4] = -np.inf
+    rows[4, [5, 77, 8000]] = [0.0, 1.0, -1.0]                # masked vocabulary, fewer live tokens than K
+    rows[5] = np.round(rs.randn(V) * 2).astype(np.float32)   # heavy ties
+    rows[6] = rs.randn(V).astype(np.float32) * 30            # nearly one-hot
+    rows[7] = rs.randn(V).astype(np.float32) * 1e-3          # nearly uniform
+    got, want = _check_entropy(G, rows, K)
+    assert list(got["topk_idx"][0]) == list(range(K))
+    assert abs(got["ent_full"][0] - math.log(V)) < 1e-4 and abs(got["ent_topk"][0] - math.log(K)) < 1e-5
+    assert got["ent_full"][1] < 1e-8 and got["ent_topk"][1] < 1e-8
+
+
+def test_entropy_row_stride_and_unaligned_rows(G):
+    import torch
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(2)
+    big = rs.randn(6, 5003).astype(np.float32) * 3
+    t = G.dev(big)
+    view = t[:, 1:4998]                                      # stride 5003, V = 4997, misaligned start
+    out = hs.hs_draft_entropy_topk(view, 8)
+    want = draft_entropy_topk(big[:, 1:4998], 8)
+    assert np.array_equal(G.host(out["topk_idx"]), want["topk_idx"])
+    assert G.entropy_err(G.host(out["ent_full"]), want["ent_full"]) <= 1.0
+
+
+def test_entropy_is_deterministic(G):
+    rs = np.random.RandomState(3)
+    rows = (rs.randn(40, 30011) * 4).astype(np.float32)
+    a, b = G.run_entropy(rows, 10), G.run_entropy(rows, 10)
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+
+
+# ------------------------------------------------------------------------------------------ prune
+def _prune_equal(got, want):
+    for k in ("depth", "keep", "out_offsets", "out_src", "out_parent"):
+        assert np.array_equal(got[k], want[k]), k
+    assert np.array_equal(got["cumlogp"].view(np.uint32), want["cumlogp"].view(np.uint32))   # bit for bit
+
+
+def test_prune_workload1_and_sweeps(G):
+    st = P.build_step(W.WORKLOADS[1], 0, with_attention=False)
+    _prune_equal(G.run_prune(st["prune_in"]), st["prune_out"])
+    w3 = W.small(W.WORKLOADS[3], V=4096)
+    for th in w3.theta:
+        st = P.build_step(w3, 0, theta=th, with_attention=False)
+        _prune_equal(G.run_prune(st["prune_in"]), st["prune_out"])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_prune_random_ragged_batches(G, seed):
+    rs = np.random.RandomState(seed)
+    sizes = [int(x) for x in rs.choice([0, 1, 2, 17, 64, 257, 511, 1000], size=rs.randint(1, 9))]
+    if sum(sizes) == 0:
+        sizes.append(5)
+    parents, logcs = [], []
+    for n in sizes:
+        if n:
+            parents.append(np.asarray([-1] + [rs.randint(max(0, i - 12), i) for i in range(1, n)], np.int32))
+            c = -rs.exponential(0.7, size=n)
+            c[rs.rand(n) < 0.1] = 1e-7                      # slightly positive: clamped
+            c = np.round(c * 4) / 4 if seed % 2 else c      # many equal sums on odd seeds
+            c[0] = 0
+            logcs.append(c)
+    B = len(sizes)
+    pin = dict(parent=np.concatenate(parents), logc=np.concatenate(logcs).astype(np.float32),
+               node_offsets=np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32),
+               d_max=rs.choice([2, 5, 9, 2 ** 31 - 1], size=B).astype(np.int32),
+               theta=rs.choice([-np.inf, -8.0, -3.0, -0.5], size=B).astype(np.float32),
+               max_nodes=rs.choice([0, 1, 7, 60, 128], size=B).astype(np.int32))
+    want = tree_prune(pin["parent"], pin["logc"], pin["node_offsets"], pin["d_max"], pin["theta"], pin["max_nodes"])
+    _prune_equal(G.run_prune(pin), want)
+
+
+def test_prune_tree_larger_than_lds(G):
+    rs = np.random.RandomState(11)
+    n = 6000
+    parent = np.asarray([-1] + [rs.randint(max(0, i - 40), i) for i in range(1, n)], np.int32)
+    logc = (-rs.exponential(0.05, size=n)).astype(np.float32)
+    pin = dict(parent=parent, logc=logc, node_offsets=np.asarray([0, n], np.int32),
+               d_max=np.asarray([2 ** 31 - 1], np.int32), theta=np.asarray([-6.0], np.float32),
+               max_nodes=np.asarray([900], np.int32))
+    want = tree_prune(parent, logc, pin["node_offsets"], pin["d_max"], pin["theta"], pin["max_nodes"])
+    _prune_equal(G.run_prune(pin), want)
+
+
+# ------------------------------------------------------------------------------------------ accept
+def _accept_equal(got, want):
+    for k in ("accept_len", "accept_path", "bonus_token"):
+        assert np.array_equal(got[k], want[k]), (k, got[k], want[k])
+
+
+def _planted(step, rs):
+    """Make the target confirm a random root-to-leaf path of every sequence (known answer)."""
+    no = step["node_offsets"]
+    for s in range(len(no) - 1):
+        o, n = int(no[s]), int(no[s + 1] - no[s])
+        if n < 2:
+            continue
+        c = o + int(rs.randint(1, n))
+        while step["parent"][c] >= 0:
+            p = o + int(step["parent"][c])
+            step["target_logits"][p, step["token"][c]] = step["target_logits"][p].max() + 2.0
+            c = p
+
+
+@pytest.mark.parametrize("wid,small", [(1, {}), (3, dict(V=4096)), (2, dict(V=8192)), (5, dict(V=2048, B=6))])
+def test_accept_greedy(G, wid, small):
+    w = W.small(W.WORKLOADS[wid], **small)
+    rs = np.random.RandomState(wid)
+    for planted in (False, True):
+        st = P.build_step(w, 0, theta=w.theta[-1], with_attention=False)   # the loosest threshold
+        if planted:
+            _planted(st, rs)
+        D = max(1, int(P.tree_depth(st["parent"], st["node_offsets"]).max()))
+        want = P.accept_out(st, P.GREEDY, None, D)
+        _accept_equal(G.run_accept(st, 0, None, D), want)
+        if planted:
+            assert want["accept_len"].max() >= 1
+    # a walk cut short by max_depth
+    want = P.accept_out(st, P.GREEDY, None, 1)
+    _accept_equal(G.run_accept(st, 0, None, 1), want)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("wid,small", [(1, {}), (2, dict(V=8192)), (4, dict(V=4099)), (5, dict(V=2048, B=5))])
+def test_accept_stochastic(G, mode, wid, small):
+    w = W.small(W.WORKLOADS[wid], **small)
+    lens = []
+    for seed in range(3):
+        st = P.build_step(w, seed, with_attention=False)
+        u, want = P.safe_uniforms(st, mode)
+        D = max(1, int(P.tree_depth(st["parent"], st["node_offsets"]).max()))
+        _accept_equal(G.run_accept(st, mode, u, D), want)
+        lens += list(want["accept_len"])
+    if wid != 1:                                             # (the tiny workload keeps 3 unlikely nodes)
+        assert max(lens) >= 1                                # some walk went below the root
