@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is already resident in
+HBM: hs_draft_entropy_topk on every expanded draft row, hs_tree_prune on the candidate tree,
+hs_tree_attention on the kept rows (for the single-sequence workloads: all decoder layers of the
+model the layer is shaped after, each with its own Q and K/V cache, in one batched launch) and
+hs_verify_accept on the kept rows' target logits.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--layers N] [--accept greedy]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def cpu_baseline(w, step, layers, seed):
+    """The CPU checker, as it stands, on a bounded sample of the same step; scaled to the step."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import draft_entropy_topk, tree_prune, tree_attention, verify_accept
+    from synth import workloads as W
+
+    h = step.host
+    rows_total = int(step.t["draft_rows"].shape[0])
+    n_rows = min(8, rows_total)
+    x = step.t["draft_rows"][:n_rows].cpu().numpy()
+    t0 = time.perf_counter()
+    draft_entropy_topk(x, w.topk, w.temperature)
+    t1 = (time.perf_counter() - t0) * rows_total / n_rows
+    t0 = time.perf_counter()
+    tree_prune(step.t["cand_parent"].cpu().numpy(), step.t["cand_logc"].cpu().numpy(),
+               step.t["cand_offsets"].cpu().numpy(), step.t["d_max"].cpu().numpy(),
+               step.t["theta"].cpu().numpy(), step.t["max_nodes"].cpu().numpy())
+    t2 = time.perf_counter() - t0
+    # attention: the first entry of the batch (one layer / one sequence), scaled by bytes
+    no, po = h["attn_node_offsets"].numpy(), h["attn_prefix_offsets"].numpy()
+    M, L = int(no[1]), int(po[1])
+
+    def np_store(t):
+        import torch
+        return t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy()
+    q, kp, vp = np_store(step.t["q"][:M]), np_store(step.t["k_prefix"][:L]), np_store(step.t["v_prefix"][:L])
+    kt, vt = np_store(step.t["k_tree"][:M]), np_store(step.t["v_tree"][:M])
+    t0 = time.perf_counter()
+    tree_attention(q, kp, vp, kt, vt, h["out_parent"][:M], [0, M], [0, L], h["scale"])
+    one = time.perf_counter() - t0
+    es = 4 if w.dtype == "f32" else 2
+    bytes_one = (2 * (L + M) * w.Hkv * w.D + 2 * M * w.Hq * w.D) * es
+    t3 = one * step.bytes_stage3() / bytes_one
+    n4 = min(64, h["NNp"])
+    tl = step.t["target_logits"][:n4].cpu().numpy()
+    oo = h["out_offsets"]
+    t0 = time.perf_counter()
+    for r in range(n4):
+        np.argmax(tl[r])
+    t4 = (time.perf_counter() - t0) * h["NNp"] / n4
+    total = t1 + t2 + t3 + t4
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": h["kept_draft_nodes"] / total, "unit": "tree-tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "stage1 on %d of %d rows, stage2 whole, stage3 on 1 of %d batch entries (scaled by bytes), "
+                      "stage4 argmax on %d of %d rows; each scaled to the full step" %
+                      (n_rows, rows_total, len(no) - 1, n4, h["NNp"]),
+            "seconds_per_step": total,
+            "stage_seconds": {"entropy_topk": t1, "prune": t2, "attention": t3, "accept": t4}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=2, help="1..5, the configs of BASELINE.json in order")
+    ap.add_argument("--layers", type=int, default=0, help="attention layers per step (0 = the model's)")
+    ap.add_argument("--accept", default="greedy", choices=["greedy", "stochastic", "pointmass"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU hot path (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_13254_amd as hs
+    from paper_2505_13254_amd import harness
+    from synth import workloads as W
+
+    if not os.path.exists(hs.LIB_PATH):
+        from paper_2505_13254_amd.build import build
+        build(verbose=False)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    layers = args.layers or (w.layers if w.B == 1 else 1)
+    mode = {"greedy": 0, "stochastic": 1, "pointmass": 2}[args.accept]
+    step = harness.build_step(w, args.seed, layers=layers, accept_mode=mode)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        step.run()
+    torch.cuda.synchronize()
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        ev[k][0].record()
+        step.stage1()
+        ev[k][1].record()
+        step.stage2()
+        ev[k][2].record()
+        step.stage3()
+        ev[k][3].record()
+        step.stage4()
+        ev[k][4].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    stage_ms = [float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)])) for i in range(4)]
+    stage_med = [float(np.median([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)])) for i in range(4)]
+
+    # streaming-copy ceiling of this device, for context
+    big = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB
+    dst = torch.empty_like(big)
+    for _ in range(2):
+        dst.copy_(big)
+    torch.cuda.synchronize()
+    c0 = torch.cuda.Event(enable_timing=True)
+    c1 = torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(big)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * big.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del big, dst
+
+    h = step.host
+    tokens = h["kept_draft_nodes"]
+    bytes3 = step.bytes_stage3()
+    achieved = bytes3 / (stage_ms[2] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_tree_attention_w%d.json" % w.wid)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    out = {
+        "metric": "verified tree-tokens/sec per step + tree-attn HBM GB/s (% of peak), 1 GPU",
+        "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tree-tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "configs[%d] %s" % (w.wid - 1, w.name), "sequences": w.B, "heads": "%d/%d" % (w.Hq, w.Hkv),
+                   "head_dim": w.D, "vocab": w.V, "prefix_tokens": int(h["attn_prefix_offsets"][1]) if w.B == 1 else
+                   [int(x) for x in np.diff(h["attn_prefix_offsets"].numpy())],
+                   "attention_layers_per_step": layers, "candidate_nodes": h["cand_nodes"],
+                   "verified_rows": h["NNp"], "verified_draft_nodes": tokens,
+                   "draft_rows_quantified": int(step.t["draft_rows"].shape[0]), "accept": args.accept},
+        "stage_ms": {"entropy_topk": stage_ms[0], "prune": stage_ms[1], "attention": stage_ms[2], "accept": stage_ms[3]},
+        "stage_ms_median": {"entropy_topk": stage_med[0], "prune": stage_med[1], "attention": stage_med[2],
+                            "accept": stage_med[3]},
+        "stage_gbps": {"entropy_topk": step.bytes_stage1() / (stage_ms[0] * 1e-3) / 1e9,
+                       "attention": achieved, "accept": step.bytes_stage4() / (stage_ms[3] * 1e-3) / 1e9},
+        "tree_attn_hbm_gbps": achieved, "tree_attn_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBPS,
+        "copy_ceiling_gbps": copy_gbps,
+        "roofline": {"kernel": "hs_tree_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": bytes3, "launch_ms": stage_ms[2]},
+    }
+    acc = step.t["s4_out"]
+    out["result"] = {"accept_len": [int(x) for x in acc["accept_len"].cpu().numpy()][:16],
+                     "bonus_token": [int(x) for x in acc["bonus_token"].cpu().numpy()][:16]}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, step, layers, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,268 @@
+"""One verification step of a synthetic workload on the GPU library.
+
+Host-side glue only: it grows the draft tree by Top-K expansion (Section 2.2, Expansion) with
+hs_draft_entropy_topk, keeps every input resident in device memory, and issues the four calls of
+a step on the current stream.  All arithmetic of the step runs in libheterospec.so.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from synth import workloads as W
+from . import binding as hs
+
+INT_MAX = 2 ** 31 - 1
+
+
+def _dev(x, dtype=None, device="cuda:0"):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(device)
+
+
+def _store(x, device):
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.uint16:                           # bfloat16 bit patterns
+        return torch.from_numpy(x.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(x).to(device)
+
+
+def expand_tree(w: W.Workload, seed: int, s: int, depth: int, device="cuda:0"):
+    """Top-K expansion: per depth, the `frontier` nodes with the largest cumulative confidence are
+    expanded with their K most likely draft tokens.  Returns the candidate tree (host arrays) and the
+    expanded rows' logits (device, in expansion order)."""
+    K, F = w.topk, w.frontier
+    parent, token, logc, cum = [-1], [-1], [0.0], [0.0]
+    draft_ids: List[int] = []
+    rows = []
+    level = [0]
+    for d in range(depth):
+        chosen = sorted(sorted(level, key=lambda i: (-cum[i], i))[:F])
+        x = _dev(W.logits_rows(w, seed, "draft", s, chosen), device=device)
+        r = hs.hs_draft_entropy_topk(x, K, w.temperature, want_full=False)
+        idx = r["topk_idx"].cpu().numpy()
+        lp = r["topk_logp"].cpu().numpy()
+        nxt = []
+        for j, i in enumerate(chosen):
+            draft_ids.append(i)
+            for k in range(K):
+                parent.append(i)
+                token.append(int(idx[j, k]))
+                logc.append(float(lp[j, k]))
+                cum.append(cum[i] + min(float(lp[j, k]), 0.0))
+                nxt.append(len(parent) - 1)
+        rows.append(x)
+        level = nxt
+    return dict(parent=np.asarray(parent, np.int32), token=np.asarray(token, np.int32),
+                logc=np.asarray(logc, np.float32), draft_ids=np.asarray(draft_ids, np.int64),
+                rows=torch.cat(rows, dim=0))
+
+
+def fixed_tree(w: W.Workload, seed: int, s: int, device="cuda:0"):
+    """Random-shape tree: every node's draft row is quantified; child number r of a node carries the
+    node's r-th most likely draft token and its log-probability."""
+    parent = W.tree_parents(w, seed, s)
+    M = len(parent)
+    x = _dev(W.logits_rows(w, seed, "draft", s, range(M)), device=device)
+    r = hs.hs_draft_entropy_topk(x, w.topk, w.temperature, want_full=False)
+    idx, lp = r["topk_idx"].cpu().numpy(), r["topk_logp"].cpu().numpy()
+    token = np.full(M, -1, np.int32)
+    logc = np.zeros(M, np.float32)
+    rank: Dict[int, int] = {}
+    for i in range(1, M):
+        p = int(parent[i])
+        k = rank.get(p, 0)
+        rank[p] = k + 1
+        token[i], logc[i] = idx[p, k], lp[p, k]
+    return dict(parent=parent, token=token, logc=logc, draft_ids=np.arange(M), rows=x)
+
+
+def sequence_budget(w: W.Workload, seed: int, device="cuda:0"):
+    """(depth, node budget) per sequence of the batched workload from the Top-K entropy of each root
+    row (first term of Eq. 1): eight equal-count bins, low entropy -> deeper draft, fewer nodes."""
+    x = _dev(np.concatenate([W.logits_rows(w, seed, "draft", s, [0]) for s in range(w.B)]), device=device)
+    ent = hs.hs_draft_entropy_topk(x, w.topk, w.temperature, want_full=False)["ent_topk"].cpu().numpy()
+    order = sorted(range(w.B), key=lambda s: (float(ent[s]), s))
+    depth, budget = [0] * w.B, [0] * w.B
+    for rank, s in enumerate(order):
+        b = rank * 8 // w.B
+        depth[s] = max(2, w.max_depth - b)
+        budget[s] = int(round(8 + (w.max_nodes - 8) * b / 7.0))
+    return depth, budget
+
+
+@dataclass
+class Step:
+    """Device-resident inputs, outputs and workspaces of one verification step."""
+    w: W.Workload
+    layers: int
+    accept_mode: int
+    t: Dict[str, torch.Tensor] = field(default_factory=dict)
+    host: Dict[str, object] = field(default_factory=dict)
+
+    # ---- the four stages, each one C call (plus, for stage 3, a device copy that hands the pruned
+    # tree to every layer's attention problem)
+    def stage1(self):
+        return hs.hs_draft_entropy_topk(self.t["draft_rows"], self.w.topk, self.w.temperature,
+                                        out=self.t["s1_out"], ws=self.t["s1_ws"])
+
+    def stage2(self):
+        return hs.hs_tree_prune(self.t["cand_parent"], self.t["cand_logc"], self.t["cand_offsets"],
+                                self.t["d_max"], self.t["theta"], self.t["max_nodes"],
+                                out=self.t["s2_out"], ws=self.t["s2_ws"])
+
+    def stage3(self):
+        t, h = self.t, self.host
+        if self.layers > 1:
+            # the pruned tree (stage 2's device output) is the tree of every layer
+            t["attn_parent"].view(self.layers, -1).copy_(t["s2_out"]["out_parent"][:h["NNp"]])
+        return hs.hs_tree_attention(t["q"], t["k_prefix"], t["v_prefix"], t["k_tree"], t["v_tree"],
+                                    t["attn_parent"], t["attn_node_offsets"], t["attn_prefix_offsets"],
+                                    h["attn_node_offsets"], h["attn_prefix_offsets"], h["scale"],
+                                    out=t["o"], ws=t["s3_ws"])
+
+    def stage4(self):
+        t, h = self.t, self.host
+        return hs.hs_verify_accept(t["target_logits"], t["draft_logits"] if self.accept_mode == 1 else None,
+                                   t["token"], t["s2_out"]["out_parent"], t["s2_out"]["out_offsets"],
+                                   self.accept_mode, self.w.temperature,
+                                   t["uniforms"] if self.accept_mode != 0 else None, h["max_depth"],
+                                   out=t["s4_out"], ws=t["s4_ws"])
+
+    def run(self):
+        self.stage1()
+        self.stage2()
+        self.stage3()
+        self.stage4()
+
+    # ---- algorithmic bytes (what the step has to move at least once)
+    def bytes_stage1(self) -> int:
+        return int(self.t["draft_rows"].numel()) * 4
+
+    def bytes_stage3(self) -> int:
+        h, w = self.host, self.w
+        es = 4 if w.dtype == "f32" else 2
+        total = 0
+        for s in range(len(h["attn_node_offsets"]) - 1):
+            M = int(h["attn_node_offsets"][s + 1] - h["attn_node_offsets"][s])
+            L = int(h["attn_prefix_offsets"][s + 1] - h["attn_prefix_offsets"][s])
+            total += (2 * (L + M) * w.Hkv * w.D + 2 * M * w.Hq * w.D) * es
+        return total
+
+    def bytes_stage4(self) -> int:
+        n = int(self.t["target_logits"].numel()) * 4
+        return n * (2 if self.accept_mode == 1 else 1)
+
+
+def build_step(w: W.Workload, seed: int = 0, layers: Optional[int] = None, accept_mode: int = 0,
+               theta: Optional[float] = None, device="cuda:0") -> Step:
+    """Generates the workload's inputs, grows and prunes its trees with the library, and lays out
+    everything a timed step needs in device memory.  With layers > 1 (single-sequence workloads) the
+    attention stage covers that many decoder layers at once: each layer has its own Q and K/V cache
+    and is passed as one entry of the batch, all sharing the step's pruned tree."""
+    layers = layers or 1
+    if layers > 1 and w.B != 1:
+        raise ValueError("layer replication is for single-sequence workloads")
+    B = w.B
+    theta = w.theta[0] if theta is None else theta
+    budget = sequence_budget(w, seed, device) if (w.tree == "expand" and B > 1) else None
+    trees = []
+    for s in range(B):
+        if w.tree == "expand":
+            trees.append(expand_tree(w, seed, s, budget[0][s] if budget else w.max_depth, device))
+        else:
+            trees.append(fixed_tree(w, seed, s, device))
+    st = Step(w=w, layers=layers, accept_mode=accept_mode)
+    t, h = st.t, st.host
+    # stage 1: every expanded row of the step in one call
+    t["draft_rows"] = torch.cat([tr["rows"] for tr in trees], dim=0).contiguous()
+    R = t["draft_rows"].shape[0]
+    t["s1_out"] = dict(topk_idx=torch.empty((R, w.topk), dtype=torch.int32, device=device),
+                       topk_logp=torch.empty((R, w.topk), dtype=torch.float32, device=device),
+                       ent_topk=torch.empty(R, dtype=torch.float32, device=device),
+                       ent_full=torch.empty(R, dtype=torch.float32, device=device),
+                       lse=torch.empty(R, dtype=torch.float32, device=device))
+    t["s1_ws"] = hs.workspace(hs.lib().hs_draft_entropy_topk_workspace(R, w.V, w.topk), device)
+    # stage 2
+    cand_off = np.zeros(B + 1, np.int32)
+    cand_off[1:] = np.cumsum([len(tr["parent"]) for tr in trees])
+    NNc = int(cand_off[-1])
+    t["cand_parent"] = _dev(np.concatenate([tr["parent"] for tr in trees]), torch.int32, device)
+    t["cand_logc"] = _dev(np.concatenate([tr["logc"] for tr in trees]), torch.float32, device)
+    t["cand_offsets"] = _dev(cand_off, torch.int32, device)
+    t["d_max"] = _dev(np.asarray([(budget[0][s] if budget else w.max_depth) for s in range(B)]), torch.int32, device)
+    t["theta"] = _dev(np.full(B, theta), torch.float32, device)
+    t["max_nodes"] = _dev(np.asarray([(budget[1][s] if budget else w.max_nodes) for s in range(B)]), torch.int32, device)
+    t["s2_out"] = dict(depth=torch.empty(NNc, dtype=torch.int32, device=device),
+                       cumlogp=torch.empty(NNc, dtype=torch.float32, device=device),
+                       keep=torch.empty(NNc, dtype=torch.uint8, device=device),
+                       out_offsets=torch.empty(B + 1, dtype=torch.int32, device=device),
+                       out_src=torch.empty(NNc, dtype=torch.int32, device=device),
+                       out_parent=torch.empty(NNc, dtype=torch.int32, device=device))
+    t["s2_ws"] = hs.workspace(hs.lib().hs_tree_prune_workspace(B, NNc), device)
+    st.stage2()
+    torch.cuda.synchronize()
+    oo = t["s2_out"]["out_offsets"].cpu().numpy()
+    NNp = int(oo[-1])
+    src = t["s2_out"]["out_src"][:NNp].cpu().numpy()
+    par = t["s2_out"]["out_parent"][:NNp].cpu().numpy()
+    h.update(NNp=NNp, cand_nodes=NNc, out_offsets=oo, out_src=src, out_parent=par,
+             kept_draft_nodes=NNp - int((np.diff(oo) > 0).sum()))
+    depth = np.zeros(NNp, np.int32)
+    for s in range(B):
+        for i in range(int(oo[s]) + 1, int(oo[s + 1])):
+            depth[i] = depth[int(oo[s]) + par[i]] + 1
+    h["max_depth"] = max(1, int(depth.max()) if NNp else 1)
+    # stage 4 inputs: target rows of the kept nodes, draft rows where the node was expanded
+    token = np.concatenate([trees[s]["token"][src[oo[s]:oo[s + 1]]] for s in range(B)]).astype(np.int32)
+    t["token"] = _dev(token, torch.int32, device)
+    t["target_logits"] = torch.empty((NNp, w.V), dtype=torch.float32, device=device)
+    for s in range(B):
+        for i0 in range(int(oo[s]), int(oo[s + 1]), 64):
+            i1 = min(i0 + 64, int(oo[s + 1]))
+            t["target_logits"][i0:i1] = _dev(W.logits_rows(w, seed, "target", s, src[i0:i1]), device=device)
+    if accept_mode == 1:
+        t["draft_logits"] = torch.zeros((NNp, w.V), dtype=torch.float32, device=device)
+        row0 = 0
+        for s in range(B):
+            pos = {int(c): j for j, c in enumerate(trees[s]["draft_ids"])}
+            for j, c in enumerate(src[oo[s]:oo[s + 1]]):
+                if int(c) in pos:
+                    t["draft_logits"][int(oo[s]) + j] = t["draft_rows"][row0 + pos[int(c)]]
+            row0 += len(trees[s]["draft_ids"])
+    t["uniforms"] = _dev(W.uniforms(w, seed, NNp + B), torch.float32, device)
+    t["s4_out"] = dict(accept_len=torch.empty(B, dtype=torch.int32, device=device),
+                       accept_path=torch.empty((B, h["max_depth"]), dtype=torch.int32, device=device),
+                       bonus_token=torch.empty(B, dtype=torch.int32, device=device))
+    t["s4_ws"] = hs.workspace(hs.lib().hs_verify_accept_workspace(B, NNp, w.V), device)
+    # stage 3 inputs
+    L = W.prefix_lengths(w, seed)
+    if layers > 1:
+        M = NNp
+        parts = [W.attention_inputs(w, seed, 1000 + l, int(L[0]), M, "config", parent=par) for l in range(layers)]
+        no = (np.arange(layers + 1) * M).astype(np.int32)
+        po = (np.arange(layers + 1) * int(L[0])).astype(np.int64)
+        t["attn_parent"] = _dev(np.tile(par, layers), torch.int32, device)
+    else:
+        parts = [W.attention_inputs(w, seed, s, int(L[s]), int(oo[s + 1] - oo[s]), "config",
+                                    parent=par[oo[s]:oo[s + 1]]) for s in range(B)]
+        no = oo.astype(np.int32)
+        po = np.zeros(B + 1, np.int64)
+        po[1:] = np.cumsum(L)
+        t["attn_parent"] = t["s2_out"]["out_parent"]
+    for i, name in enumerate(("q", "k_prefix", "v_prefix", "k_tree", "v_tree")):
+        t[name] = torch.cat([_store(p[i], device) for p in parts], dim=0).contiguous()
+    t["attn_node_offsets"] = _dev(no, torch.int32, device) if layers > 1 else t["s2_out"]["out_offsets"]
+    t["attn_prefix_offsets"] = _dev(po, torch.int64, device)
+    h.update(attn_node_offsets=torch.from_numpy(no.copy()), attn_prefix_offsets=torch.from_numpy(po.copy()),
+             scale=1.0 / float(np.sqrt(w.D)))
+    t["o"] = torch.empty_like(t["q"])
+    nb = len(no) - 1
+    t["s3_ws"] = hs.workspace(hs.lib().hs_tree_attention_workspace(
+        nb, int(no[-1]), int(po[-1]), w.Hq, w.Hkv, w.D, hs.HS_F32 if w.dtype == "f32" else hs.HS_BF16), device)
+    return st
