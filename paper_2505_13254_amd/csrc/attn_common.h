@@ -6,15 +6,19 @@
 // split also handles the tree rows themselves (the masked part).  Rows of one KV head g are
 // r = i * G + gi for tree row i and group member gi (query head h = g * G + gi).
 //
-// Partial results (only when some sequence has more than one split): one record of D + 2 floats per
-// (node, head, split): unnormalised output o[D], running maximum m (in units of the scaled score)
-// and denominator l; slot = (node_global * Hq + h) * sp_max + split.
+// Partial results (only when some sequence has more than one split): one record of D + 4 floats per
+// (node, head, split): unnormalised output o[D], reference maximum m (in units of the scaled score),
+// denominator l (relative to m) and two pad floats (records stay 16-byte aligned);
+// slot = (node_global * Hq + h) * sp_max + split.
 #pragma once
 #include "hs_common.h"
 
 namespace hs {
 
 typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+constexpr int ATTN_REC_PAD = 4;  // floats after o[D] in a partial record: m, l, pad, pad
+#define ATTN_REC (128 + ATTN_REC_PAD)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __builtin_bit_cast(float, (unsigned)b << 16); }
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest, ties to even

@@ -5,13 +5,14 @@
 // (k_attn_generic: vector ALU, K/V tiles staged through LDS, 16 rows per workgroup) and the
 // split combine (k_attn_combine).  bfloat16 with head dimension 128 goes to the MFMA kernel in
 // tree_attention_mfma.hip.
+#include <algorithm>
+
 #include "attn_common.h"
 
 namespace hs {
 
-hs_status attn_mfma_launch(const AttnArgs& a, const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
-                           hipStream_t stream);
-bool attn_mfma_supported(int D, hs_dtype dt);
+hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream);
+bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale);
 
 constexpr int GEN_THREADS = 256;
 constexpr int GEN_ROWS = 16;  // rows per workgroup (4 per wave)
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
       for (int dd = 0; dd < DPL; ++dd) store_elem<T>(out + lane + 64 * dd, acc[rr][dd] * inv);
       if (a.lse && lane == 0) a.lse[row] = m_run[rr] + __logf(l_run[rr]);
     } else {
-      float* rec = a.part + (row * a.sp_max + sp) * (D + 2);
+      float* rec = a.part + (row * a.sp_max + sp) * (D + ATTN_REC_PAD);
 #pragma unroll
       for (int dd = 0; dd < DPL; ++dd) rec[lane + 64 * dd] = acc[rr][dd];
       if (lane == 0) {
@@ -181,13 +182,13 @@ __global__ __launch_bounds__(D) void k_attn_combine(AttnArgs a, int NN) {
   }
   const int64_t L = a.prefix_offsets[lo + 1] - a.prefix_offsets[lo];
   const int n_sp = splits_of(L, a.split_len);
-  const float* rec = a.part + row * a.sp_max * (D + 2);
+  const float* rec = a.part + row * a.sp_max * (D + ATTN_REC_PAD);
   float m = -HS_INF;
-  for (int sp = 0; sp < n_sp; ++sp) m = fmaxf(m, rec[sp * (D + 2) + D]);
+  for (int sp = 0; sp < n_sp; ++sp) m = fmaxf(m, rec[sp * (D + ATTN_REC_PAD) + D]);
   float l = 0.f, o = 0.f;
   const int d = threadIdx.x;
   for (int sp = 0; sp < n_sp; ++sp) {
-    const float* r = rec + sp * (D + 2);
+    const float* r = rec + sp * (D + ATTN_REC_PAD);
     const float w = __expf(r[D] - m);
     l = fmaf(r[D + 1], w, l);
     o = fmaf(r[d], w, o);
@@ -243,7 +244,7 @@ using namespace hs;
 
 static size_t part_bytes(int64_t NN, int Hq, int D, int sp_max) {
   if (sp_max <= 1) return 0;
-  return align_up((size_t)NN * Hq * sp_max * (D + 2) * sizeof(float), 256);
+  return align_up((size_t)NN * Hq * sp_max * (D + ATTN_REC_PAD) * sizeof(float), 256);
 }
 
 extern "C" size_t hs_tree_attention_workspace(int32_t B, int32_t NN, int64_t total_prefix, int32_t Hq, int32_t Hkv,
@@ -285,7 +286,11 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
   HS_REQUIRE(q && k_tree && v_tree && parent && o, HS_ERR_NULL, "hs_tree_attention: NULL tensor");
   HS_REQUIRE(total_prefix == 0 || (k_prefix && v_prefix), HS_ERR_NULL, "hs_tree_attention: NULL prefix cache");
 
-  const bool mfma = attn_mfma_supported(D, dt);
+  int max_M = 0;
+  for (int s = 0; s < B; ++s) max_M = std::max(max_M, host_node_offsets[s + 1] - host_node_offsets[s]);
+  auto aligned16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && aligned16(q) && aligned16(k_prefix) &&
+                    aligned16(v_prefix) && aligned16(k_tree) && aligned16(v_tree) && aligned16(o);
   AttnPlan plan = plan_attention(host_node_offsets, host_prefix_offsets, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, 1024);
   // the workspace bound assumes at most 64 splits per sequence
   while (plan.sp_max > 64) {
@@ -306,7 +311,7 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   if (mfma) {
-    hs_status r = attn_mfma_launch(a, host_node_offsets, host_prefix_offsets, st);
+    hs_status r = attn_mfma_launch(a, max_M, st);
     if (r != HS_OK) return r;
   } else {
     dim3 grid((unsigned)(Hkv * plan.n_rb_max * plan.sp_max), (unsigned)B);
