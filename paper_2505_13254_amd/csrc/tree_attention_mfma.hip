@@ -20,6 +20,13 @@
 // rescaled when a new score exceeds the reference by more than 2^8, which is exact after the final
 // division by the (equally referenced) denominator.
 // The tree part (ancestor mask) is a bit table built in LDS from the parent pointers.
+//
+// K/V tiles go from HBM straight into LDS (global_load_lds_dwordx4, 16 bytes per lane, no staging
+// registers) through a ring of four tile buffers, three tiles ahead of the one being multiplied, so
+// about 96 KB per compute unit are in flight.  The XOR swizzle that keeps LDS reads conflict-free
+// is applied on the global side: the lane that fills LDS slot c of a row fetches chunk c ^ (row & 7).
+// Waits are explicit (s_waitcnt vmcnt(n) counts this wave's younger tile loads) and the workgroup
+// barrier carries no memory fence, so outstanding loads survive it.
 #include "attn_common.h"
 
 namespace hs {
@@ -28,10 +35,15 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* glb_ptr;
 
-constexpr int MF_THREADS = 256;
+#ifndef HS_ABL
+#define HS_ABL 9
+#endif
 constexpr int MF_ROWS = 256;     // query rows per workgroup (64 per wave)
 constexpr int MF_TILE = 64;      // keys per LDS tile
+constexpr int MF_NBUF = 4;       // LDS ring: one tile being multiplied, three on their way from HBM
 constexpr int MF_MAX_M = 256;    // tree rows per sequence (ancestor bit table: M x 8 words)
 constexpr int MF_ROW_BYTES = 256;  // one K or V row of a head: 128 bf16
 constexpr int MF_TILE_BYTES = MF_TILE * MF_ROW_BYTES;
@@ -47,6 +59,18 @@ bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale) {
 // row-per-lane K reads and the row-per-half-wave V reads.
 __device__ __forceinline__ int swz(int row, int chunk) { return row * MF_ROW_BYTES + ((chunk ^ (row & 7)) << 4); }
 
+// 16 bytes per lane from global memory straight into LDS: lane i lands at lds_addr + 16 i.
+// lds_addr is a wave-uniform LDS byte address (placed in M0).
+__device__ __forceinline__ void lds_dma16(const char* gptr, unsigned lds_addr) {
+  const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
+  unsigned saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "s"(m), "v"(gptr)
+      : "memory");
+}
+
 struct TileSrc {
   const char* k;
   const char* v;
@@ -55,9 +79,14 @@ struct TileSrc {
   bool tree;
 };
 
-__global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_max) {
-  __shared__ __attribute__((aligned(16))) char lds_k[2][MF_TILE_BYTES];
-  __shared__ __attribute__((aligned(16))) char lds_v[2][MF_TILE_BYTES];
+// QT = 32-row blocks per wave: 2 -> 4 waves of 64 rows, 1 -> 8 waves of 32 rows (two waves per SIMD,
+// so one wave's softmax arithmetic overlaps the other's matrix instructions).
+template <int QT>
+__global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max) {
+  constexpr int THREADS = 512 / QT;
+  constexpr int LOADS = 1024 / THREADS;  // 16-byte chunks of K (and of V) per thread per tile
+  __shared__ __attribute__((aligned(16))) char lds_k[MF_NBUF][MF_TILE_BYTES];
+  __shared__ __attribute__((aligned(16))) char lds_v[MF_NBUF][MF_TILE_BYTES];
   __shared__ unsigned anc[MF_MAX_M * 8];
 
   const int s = blockIdx.y;
@@ -115,12 +144,12 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   }
 
   // ---- this wave's rows and their Q fragments (B operand of the first product)
-  const int row_base = rg * MF_ROWS + wave * 64;
+  const int row_base = rg * MF_ROWS + wave * (32 * QT);
   const bool wave_active = row_base < R;
-  bf16x8 qf[2][8];
-  int tree_row[2];
+  bf16x8 qf[QT][8];
+  int tree_row[QT];
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
+  for (int qt = 0; qt < QT; ++qt) {
     const int r = row_base + qt * 32 + col;
     const int rc = r < R ? r : R - 1;
     const int i = rc / G, gi = rc - i * G;
@@ -133,84 +162,86 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     }
   }
 
-  floatx16 acc[2][4];
+  floatx16 acc[QT][4];
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
+  for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[qt][t][v] = 0.f;
-  float m_ref[2] = {-HS_INF, -HS_INF};  // log2 domain
-  float l_sum[2] = {0.f, 0.f};          // this lane's share of the denominator
+  float m_ref[QT], l_sum[QT];  // log2-domain reference maximum; this lane's share of the denominator
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    m_ref[qt] = -HS_INF;
+    l_sum[qt] = 0.f;
+  }
   const float c2 = a.scale * MF_LOG2E;
 
-  // ---- staging: 64 rows x 16 chunks for K and for V, four chunks of each per thread
-  uint4 kreg[4], vreg[4];
-  auto fetch = [&](const TileSrc& ts) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = tid + MF_THREADS * j;
-      const int row = c >> 4, ch = c & 15;
-      const int64_t key = ts.base + row;
-      uint4 z = {0u, 0u, 0u, 0u};
-      if (key < ts.limit) {
-        kreg[j] = *reinterpret_cast<const uint4*>(ts.k + key * tok_stride + ch * 16);
-        vreg[j] = *reinterpret_cast<const uint4*>(ts.v + key * tok_stride + ch * 16);
-      } else {
-        kreg[j] = z;
-        vreg[j] = z;
-      }
-    }
-  };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = tid + MF_THREADS * j;
-      const int row = c >> 4, ch = c & 15;
-      *reinterpret_cast<uint4*>(&lds_k[buf][swz(row, ch)]) = kreg[j];
-      *reinterpret_cast<uint4*>(&lds_v[buf][swz(row, ch)]) = vreg[j];
-    }
-  };
-
-  {
-    TileSrc ts = tile_src(0);
-    fetch(ts);
-    stash(0);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
+  // ---- tile loads: 64 rows x 16 chunks for K and for V; wave w issues rows 4(4j+w) .. +3 of both.
+  // Issued as inline assembly: the compiler then neither tracks them in its own wait counters nor
+  // orders LDS reads of other ring slots behind them.
+  const unsigned lds_k_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_k[0][0];
+  const unsigned lds_v_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_v[0][0];
+  auto issue = [&](int t) {
     const TileSrc ts = tile_src(t);
-    if (t + 1 < n_tiles) {
-      TileSrc nx = tile_src(t + 1);
-      fetch(nx);
+    const unsigned ring = (unsigned)(t % MF_NBUF) * MF_TILE_BYTES;
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+      const int c = j * THREADS + tid;  // LDS slot (16-byte units) this lane fills
+      const int row = c >> 4, slot = c & 15;
+      int64_t key = ts.base + row;
+      key = key < ts.limit ? key : ts.limit - 1;  // rows past the end repeat the last row (masked later)
+      const int64_t off = key * tok_stride + ((slot ^ (row & 7)) << 4);
+      const unsigned wave_slot = ring + (unsigned)((j * THREADS + wave * 64) << 4);  // wave-uniform
+      lds_dma16(ts.k + off, lds_k_addr + wave_slot);
+      lds_dma16(ts.v + off, lds_v_addr + wave_slot);
     }
-    if (wave_active) {
-      const char* kb_base = lds_k[buf];
-      const char* vb_base = lds_v[buf];
+  };
+  if (n_tiles > 0) issue(0);
+  if (n_tiles > 1) issue(1);
+  if (n_tiles > 2) issue(2);
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the ancestor table is complete
+
+  // iteration t: wait for tile t, barrier, start the load of tile t+3 into the slot that tile t-1
+  // just left, multiply tile t
+  for (int t = 0; t < n_tiles; ++t) {
+    const TileSrc ts = tile_src(t);
+    const char* kb_base = lds_k[t % MF_NBUF];
+    const char* vb_base = lds_v[t % MF_NBUF];
+    // this wave's loads of tile t are done once at most the 2 x 2 LOADS loads of tiles t+1, t+2 are pending
+    if (t + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * LOADS) : "memory");
+    else if (t + 1 < n_tiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#ifndef HS_NODMA
+    if (t + 3 < n_tiles) issue(t + 3);
+#endif
+    if (wave_active && HS_ABL >= 1) {
       const bool partial_tile = ts.base + MF_TILE > ts.limit;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         if (ts.base + kb * 32 >= ts.limit) break;  // whole key block beyond the end
         // ---- S^T = K Q^T for 32 keys x 64 rows
-        floatx16 sc[2];
+        floatx16 sc[QT];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          sc[0][v] = 0.f;
-          sc[1][v] = 0.f;
-        }
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sc[qt][v] = 0.f;
         const int krow = kb * 32 + col;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
           const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb_base + swz(krow, 2 * kk + half));
-          sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][kk], sc[0], 0, 0, 0);
-          sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][kk], sc[1], 0, 0, 0);
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt)
+            sc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][kk], sc[qt], 0, 0, 0);
         }
+#if HS_ABL == 1
+        for (int qt = 0; qt < QT; ++qt) acc[qt][0] += sc[qt];
+        continue;
+#endif
         // ---- masks: keys past the end of the split; tree keys off the row's root path
         if (ts.tree) {
 #pragma unroll
-          for (int qt = 0; qt < 2; ++qt) {
+          for (int qt = 0; qt < QT; ++qt) {
             const unsigned word = anc[tree_row[qt] * 8 + (int)((ts.base >> 5) + kb)];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -224,15 +255,15 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
           for (int v = 0; v < 16; ++v) {
             const int key = 8 * (v >> 2) + 4 * half + (v & 3);
             if (key >= valid) {
-              sc[0][v] = -HS_INF;
-              sc[1][v] = -HS_INF;
+#pragma unroll
+              for (int qt = 0; qt < QT; ++qt) sc[qt][v] = -HS_INF;
             }
           }
         }
         // ---- softmax numerators in the log2 domain, lazily referenced maximum
-        bf16x8 pf[2][2];
+        bf16x8 pf[QT][2];
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
+        for (int qt = 0; qt < QT; ++qt) {
           float mx = sc[qt][0];
 #pragma unroll
           for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[qt][v]);
@@ -269,40 +300,43 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
             }
           }
         }
+#if HS_ABL == 2
+        for (int qt = 0; qt < QT; ++qt) acc[qt][0][0] += (float)pf[qt][0][0] + (float)pf[qt][1][3];
+        continue;
+#endif
         // ---- O^T += V^T P^T
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
-          uint2 vr[8];
+          uint2 vfr[8];
 #pragma unroll
           for (int idx = 0; idx < 8; ++idx) {
             const int key = kb * 32 + 8 * (2 * k2 + (idx >> 2)) + 4 * half + (idx & 3);
-            vr[idx] = *reinterpret_cast<const uint2*>(vb_base + swz(key, col >> 1) + (col & 1) * 8);
+            vfr[idx] = *reinterpret_cast<const uint2*>(vb_base + swz(key, col >> 1) + (col & 1) * 8);
           }
 #pragma unroll
           for (int tt = 0; tt < 4; ++tt) {
             unsigned w4[4];
 #pragma unroll
             for (int pp = 0; pp < 4; ++pp) {
-              const unsigned lo = (tt < 2) ? vr[2 * pp].x : vr[2 * pp].y;
-              const unsigned hi = (tt < 2) ? vr[2 * pp + 1].x : vr[2 * pp + 1].y;
+              const unsigned lo = (tt < 2) ? vfr[2 * pp].x : vfr[2 * pp].y;
+              const unsigned hi = (tt < 2) ? vfr[2 * pp + 1].x : vfr[2 * pp + 1].y;
               w4[pp] = __builtin_amdgcn_perm(hi, lo, (tt & 1) ? 0x07060302u : 0x05040100u);
             }
             uint4 packed = {w4[0], w4[1], w4[2], w4[3]};
             const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
-            acc[0][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][k2], acc[0][tt], 0, 0, 0);
-            acc[1][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][k2], acc[1][tt], 0, 0, 0);
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+              acc[qt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][k2], acc[qt][tt], 0, 0, 0);
           }
         }
       }
     }
-    if (t + 1 < n_tiles) stash(buf ^ 1);
-    __syncthreads();
   }
 
   // ---- results: direct (single split everywhere) or this split's partial record
   if (!wave_active) return;
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
+  for (int qt = 0; qt < QT; ++qt) {
     const int r = row_base + qt * 32 + col;
     const float l_tot = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
     if (r >= R) continue;
@@ -338,10 +372,13 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   }
 }
 
+#ifndef HS_QT
+#define HS_QT 1
+#endif
 hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream) {
   const int n_rg_max = (a.G * max_tree_rows + MF_ROWS - 1) / MF_ROWS;
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);
-  hipLaunchKernelGGL(k_attn_mfma, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
+  hipLaunchKernelGGL(k_attn_mfma<HS_QT>, grid, dim3(512 / HS_QT), 0, stream, a, n_rg_max);
   return launch_status("tree attention (mfma)");
 }
 
