@@ -1,9 +1,9 @@
 // bfloat16 tree attention on the matrix cores (head dimension 128).
 //
-// One workgroup = 4 waves = up to 256 query rows of one (sequence, KV head, key split); every wave
-// owns 64 rows (two 32-row MFMA column blocks) and keeps their output accumulators in registers for
-// the whole pass, so K and V are read from HBM once per workgroup and shared through LDS by all
-// G x M rows of the KV head (Section 2.2: every tree row attends to the same prefix).
+// One workgroup = up to 256 query rows of one (sequence, KV head, key split); every wave owns
+// 32 * QT rows and keeps their output accumulators in registers for the whole pass, so K and V are
+// read from HBM once per workgroup and shared through LDS by all G x M rows of the KV head
+// (Section 2.2: every tree row attends to the same prefix).
 //
 // Both products are computed transposed with v_mfma_f32_32x32x16_bf16:
 //     S^T[key, row] = K[key, :] . Q[row, :]      A = K fragment (LDS), B = Q fragment (registers)
@@ -11,20 +11,25 @@
 // In the S^T accumulator a lane holds 16 keys of ONE row, so the softmax maximum and sum are
 // in-lane reductions plus one exchange between the two half-waves, and P^T is already laid out as
 // the B operand of the second product: no transposition of P through LDS.  The contraction order of
-// the keys inside a 16-key MFMA step is permuted to match that layout; V fragments are fetched with
-// the same permutation.  The output dimension is permuted as d = 4 * i + t (t = 32-row block of
-// O^T, i = row inside it) so that a lane fetches the four blocks' values of one key with a single
-// 8-byte LDS read and writes 4 consecutive output elements at the end.
+// the keys inside a 16-key MFMA step is permuted to match that layout, and the V^T fragments are
+// fetched from the row-major V tile with the transposing LDS read (ds_read_b64_tr_b16), which hands
+// each lane four keys of one output column.
 //
-// Softmax runs in the log2 domain with a lazily updated reference maximum: accumulators are only
-// rescaled when a new score exceeds the reference by more than 2^8, which is exact after the final
-// division by the (equally referenced) denominator.
+// Softmax runs in the log2 domain.  Q is pre-multiplied by scale * log2(e), and the first MFMA of a
+// score block starts from an accumulator holding minus the row's reference maximum, so the matrix
+// core delivers x - m directly and the only per-score vector work is exp2, the row sum and the
+// conversion to bf16.  The reference maximum is updated lazily: accumulators are rescaled only when
+// a score exceeds the reference by more than 2^8 (exact after the final division by the equally
+// referenced denominator).  That check runs one block ahead, next to the second product's MFMAs,
+// and the first product of block b+1 is issued together with the exponentials of block b, so matrix
+// and vector instructions of independent blocks sit in the same scheduling region.
+//
 // The tree part (ancestor mask) is a bit table built in LDS from the parent pointers.
 //
 // K/V tiles go from HBM straight into LDS (global_load_lds_dwordx4, 16 bytes per lane, no staging
-// registers) through a ring of four tile buffers, three tiles ahead of the one being multiplied, so
-// about 96 KB per compute unit are in flight.  The XOR swizzle that keeps LDS reads conflict-free
-// is applied on the global side: the lane that fills LDS slot c of a row fetches chunk c ^ (row & 7).
+// registers) through a ring of four tile buffers: while one tile is multiplied and the next one is
+// already being read for its scores, two more are on their way (64 KB per compute unit in flight).
+// The XOR swizzle that keeps LDS reads conflict-free is applied on the global side: the lane that fills LDS slot c of a row fetches chunk c ^ swz_key(row).
 // Waits are explicit (s_waitcnt vmcnt(n) counts this wave's younger tile loads) and the workgroup
 // barrier carries no memory fence, so outstanding loads survive it.
 #include "attn_common.h"
@@ -32,35 +37,41 @@
 namespace hs {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
-typedef const __attribute__((address_space(1))) void* glb_ptr;
+typedef __attribute__((address_space(3))) shortx4* lds_s4_ptr;
 
-#ifndef HS_ABL
-#define HS_ABL 9
-#endif
-constexpr int MF_ROWS = 256;     // query rows per workgroup (64 per wave)
-constexpr int MF_TILE = 64;      // keys per LDS tile
-constexpr int MF_NBUF = 4;       // LDS ring: one tile being multiplied, three on their way from HBM
-constexpr int MF_MAX_M = 256;    // tree rows per sequence (ancestor bit table: M x 8 words)
+constexpr int MF_ROWS = 256;       // query rows per workgroup
+constexpr int MF_TILE = 64;        // keys per LDS tile (two 32-key blocks)
+constexpr int MF_NBUF = 4;         // LDS ring: two tiles in use, two on their way from HBM
+constexpr int MF_MAX_M = 256;      // tree rows per sequence (ancestor bit table: M x 8 words)
 constexpr int MF_ROW_BYTES = 256;  // one K or V row of a head: 128 bf16
 constexpr int MF_TILE_BYTES = MF_TILE * MF_ROW_BYTES;
 constexpr float MF_LOG2E = 1.4426950408889634f;
 constexpr float MF_LN2 = 0.6931471805599453f;
-constexpr float MF_LAZY = 8.0f;  // rescale only when the reference maximum is exceeded by 2^8
+constexpr float MF_LAZY = 8.0f;    // rescale only when the reference maximum is exceeded by 2^8
+
+#ifndef HS_QT
+#define HS_QT 1
+#endif
 
 bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale) {
   return D == 128 && dt == HS_BF16 && max_tree_rows <= MF_MAX_M && scale > 0.f;
 }
 
-// 16-byte chunk c (0..15) of row r lives at chunk position c ^ (r & 7): conflict-free for both the
-// row-per-lane K reads and the row-per-half-wave V reads.
-__device__ __forceinline__ int swz(int row, int chunk) { return row * MF_ROW_BYTES + ((chunk ^ (row & 7)) << 4); }
+// 16-byte chunk c (0..15) of row r lives at chunk position c ^ swz_key(r).  The key takes 16
+// different values over 16 consecutive rows (one K row per lane: conflict-free 16-byte reads) and
+// its bits 1-2 are the row's low two bits (the four rows that a 16-lane group of the transposing V
+// read touches land in four different 32-byte bank ranges).
+__device__ __forceinline__ int swz_key(int row) { return ((row & 3) << 1) | ((row >> 2) & 1) | (row & 8); }
+__device__ __forceinline__ int swz(int row, int chunk) { return row * MF_ROW_BYTES + ((chunk ^ swz_key(row)) << 4); }
 
 // 16 bytes per lane from global memory straight into LDS: lane i lands at lds_addr + 16 i.
-// lds_addr is a wave-uniform LDS byte address (placed in M0).
+// lds_addr is a wave-uniform LDS byte address (placed in M0, which is saved and restored).
 __device__ __forceinline__ void lds_dma16(const char* gptr, unsigned lds_addr) {
   const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
   unsigned saved;
@@ -79,8 +90,7 @@ struct TileSrc {
   bool tree;
 };
 
-// QT = 32-row blocks per wave: 2 -> 4 waves of 64 rows, 1 -> 8 waves of 32 rows (two waves per SIMD,
-// so one wave's softmax arithmetic overlaps the other's matrix instructions).
+// QT = 32-row blocks per wave: 2 -> 4 waves of 64 rows, 1 -> 8 waves of 32 rows (two waves per SIMD).
 template <int QT>
 __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max) {
   constexpr int THREADS = 512 / QT;
@@ -119,7 +129,7 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
   const int64_t k_hi = last_split ? L : k_lo + a.split_len;
   const int n_ptiles = (int)((k_hi - k_lo + MF_TILE - 1) / MF_TILE);
   const int n_ttiles = last_split ? (M + MF_TILE - 1) / MF_TILE : 0;
-  const int n_tiles = n_ptiles + n_ttiles;
+  const int n_tiles = n_ptiles + n_ttiles;  // >= 1: a split holds prefix keys, or it is the last one
 
   auto tile_src = [&](int t) {
     TileSrc ts;
@@ -143,7 +153,9 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
     for (int q = 0; q < 8; ++q) anc[tid * 8 + q] = w[q];
   }
 
-  // ---- this wave's rows and their Q fragments (B operand of the first product)
+  // ---- this wave's rows; Q fragments (B operand of the first product), pre-multiplied by
+  // scale * log2(e) so that the scores come out of the MFMA in the log2 domain
+  const float c2 = a.scale * MF_LOG2E;
   const int row_base = rg * MF_ROWS + wave * (32 * QT);
   const bool wave_active = row_base < R;
   bf16x8 qf[QT][8];
@@ -157,29 +169,35 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
     const char* qrow = static_cast<const char*>(a.q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[qt][kk] = (r < R && wave_active) ? *reinterpret_cast<const bf16x8*>(qrow + (2 * kk + half) * 16) : z;
+      bf16x8 raw = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (r < R && wave_active) raw = *reinterpret_cast<const bf16x8*>(qrow + (2 * kk + half) * 16);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        floatx2 f = {(float)raw[2 * e] * c2, (float)raw[2 * e + 1] * c2};
+        bf16x2 hb = __builtin_convertvector(f, bf16x2);
+        qf[qt][kk][2 * e] = hb[0];
+        qf[qt][kk][2 * e + 1] = hb[1];
+      }
     }
   }
 
-  floatx16 acc[QT][4];
+  floatx16 acc[QT][4];   // O^T: [d block of 32][16 values]: d = 32 tt + 8 (v / 4) + 4 half + v % 4
+  floatx16 negm[QT];     // minus the reference maximum in all 16 slots: start value of a score block
+  float m_ref[QT], l_sum[QT];
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt)
+  for (int qt = 0; qt < QT; ++qt) {
+    m_ref[qt] = 0.f;
+    l_sum[qt] = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negm[qt][v] = 0.f;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[qt][t][v] = 0.f;
-  float m_ref[QT], l_sum[QT];  // log2-domain reference maximum; this lane's share of the denominator
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    m_ref[qt] = -HS_INF;
-    l_sum[qt] = 0.f;
   }
-  const float c2 = a.scale * MF_LOG2E;
 
-  // ---- tile loads: 64 rows x 16 chunks for K and for V; wave w issues rows 4(4j+w) .. +3 of both.
-  // Issued as inline assembly: the compiler then neither tracks them in its own wait counters nor
-  // orders LDS reads of other ring slots behind them.
+  // ---- tile loads.  Issued as inline assembly: the compiler then neither tracks them in its own
+  // wait counters nor orders LDS reads of other ring slots behind them.
   const unsigned lds_k_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_k[0][0];
   const unsigned lds_v_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_v[0][0];
   auto issue = [&](int t) {
@@ -191,146 +209,165 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
       const int row = c >> 4, slot = c & 15;
       int64_t key = ts.base + row;
       key = key < ts.limit ? key : ts.limit - 1;  // rows past the end repeat the last row (masked later)
-      const int64_t off = key * tok_stride + ((slot ^ (row & 7)) << 4);
+      const int64_t off = key * tok_stride + ((slot ^ swz_key(row)) << 4);
       const unsigned wave_slot = ring + (unsigned)((j * THREADS + wave * 64) << 4);  // wave-uniform
       lds_dma16(ts.k + off, lds_k_addr + wave_slot);
       lds_dma16(ts.v + off, lds_v_addr + wave_slot);
     }
   };
-  if (n_tiles > 0) issue(0);
-  if (n_tiles > 1) issue(1);
-  if (n_tiles > 2) issue(2);
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the ancestor table is complete
-
-  // iteration t: wait for tile t, barrier, start the load of tile t+3 into the slot that tile t-1
-  // just left, multiply tile t
-  for (int t = 0; t < n_tiles; ++t) {
-    const TileSrc ts = tile_src(t);
-    const char* kb_base = lds_k[t % MF_NBUF];
-    const char* vb_base = lds_v[t % MF_NBUF];
-    // this wave's loads of tile t are done once at most the 2 x 2 LOADS loads of tiles t+1, t+2 are pending
-    if (t + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * LOADS) : "memory");
-    else if (t + 1 < n_tiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
+  // Wait until this wave's loads of tile t have landed (only the loads of tile t+1 may still be
+  // pending), then meet the other waves.  It is called while tile t-1 is still being multiplied, so
+  // the slot that is free for a new load is the one of tile t-2: tile t+2 goes there.
+  auto arrive = [&](int t) {
+    if (t + 1 < n_tiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
     else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#ifndef HS_NODMA
-    if (t + 3 < n_tiles) issue(t + 3);
-#endif
-    if (wave_active && HS_ABL >= 1) {
-      const bool partial_tile = ts.base + MF_TILE > ts.limit;
+    if (t + 2 < n_tiles) issue(t + 2);
+  };
+
+  // ---- S^T block = K[32 keys] Q^T, started from -m_ref
+  auto qk = [&](int blk, floatx16 (&S)[QT]) {
+    const char* kbuf = lds_k[(blk >> 1) % MF_NBUF];
+    const int krow = (blk & 1) * 32 + col;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        if (ts.base + kb * 32 >= ts.limit) break;  // whole key block beyond the end
-        // ---- S^T = K Q^T for 32 keys x 64 rows
-        floatx16 sc[QT];
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kbuf + swz(krow, 2 * kk + half));
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
+      for (int qt = 0; qt < QT; ++qt)
+        S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][kk], kk == 0 ? negm[qt] : S[qt], 0, 0, 0);
+    }
+  };
+  // ---- masks (tree keys off the row's root path, keys past the end), block maximum, lazy update of
+  // the reference.  S holds x - m_ref on entry and on exit.
+  auto settle = [&](int blk, floatx16 (&S)[QT], bool force) {
+    const TileSrc ts = tile_src(blk >> 1);
+    const int64_t bbase = ts.base + (blk & 1) * 32;
+    if (ts.tree) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) sc[qt][v] = 0.f;
-        const int krow = kb * 32 + col;
+      for (int qt = 0; qt < QT; ++qt) {
+        const unsigned word = bbase < ts.limit ? anc[tree_row[qt] * 8 + (int)(bbase >> 5)] : 0u;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb_base + swz(krow, 2 * kk + half));
-#pragma unroll
-          for (int qt = 0; qt < QT; ++qt)
-            sc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][kk], sc[qt], 0, 0, 0);
+        for (int v = 0; v < 16; ++v) {
+          const int bit = 8 * (v >> 2) + 4 * half + (v & 3);
+          S[qt][v] = ((word >> bit) & 1u) ? S[qt][v] : -HS_INF;
         }
-#if HS_ABL == 1
-        for (int qt = 0; qt < QT; ++qt) acc[qt][0] += sc[qt];
-        continue;
-#endif
-        // ---- masks: keys past the end of the split; tree keys off the row's root path
-        if (ts.tree) {
+      }
+    } else if (bbase + 32 > ts.limit) {
+      const int valid = (int)(ts.limit - bbase);  // may be <= 0: the whole block is past the end
 #pragma unroll
-          for (int qt = 0; qt < QT; ++qt) {
-            const unsigned word = anc[tree_row[qt] * 8 + (int)((ts.base >> 5) + kb)];
+      for (int v = 0; v < 16; ++v) {
+        const int key = 8 * (v >> 2) + 4 * half + (v & 3);
+        if (key >= valid) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int bit = 8 * (v >> 2) + 4 * half + (v & 3);
-              sc[qt][v] = ((word >> bit) & 1u) ? sc[qt][v] : -HS_INF;
-            }
-          }
-        } else if (partial_tile) {
-          const int valid = (int)(ts.limit - ts.base) - kb * 32;  // keys of this block that exist
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = 8 * (v >> 2) + 4 * half + (v & 3);
-            if (key >= valid) {
-#pragma unroll
-              for (int qt = 0; qt < QT; ++qt) sc[qt][v] = -HS_INF;
-            }
-          }
-        }
-        // ---- softmax numerators in the log2 domain, lazily referenced maximum
-        bf16x8 pf[QT][2];
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-          float mx = sc[qt][0];
-#pragma unroll
-          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[qt][v]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
-          const float cand = mx * c2;
-          const bool grow = cand > m_ref[qt] + MF_LAZY;
-          if (__ballot(grow) != 0ull) {
-            const float m_new = grow ? cand : m_ref[qt];
-            const float alpha = (m_ref[qt] == -HS_INF) ? (grow ? 0.f : 1.f) : exp2_fast(m_ref[qt] - m_new);
-            l_sum[qt] *= alpha;
-#pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) acc[qt][tt][v] *= alpha;
-            m_ref[qt] = m_new;
-          }
-          float p[16];
-          float ps = 0.f;
-          const float mr = (m_ref[qt] == -HS_INF) ? 0.f : m_ref[qt];  // (every key masked so far: p = 0)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            p[v] = exp2_fast(fmaf(sc[qt][v], c2, -mr));
-            ps += p[v];
-          }
-          l_sum[qt] += ps;
-#pragma unroll
-          for (int k2 = 0; k2 < 2; ++k2) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              floatx2 f = {p[8 * k2 + 2 * e], p[8 * k2 + 2 * e + 1]};
-              bf16x2 hbits = __builtin_convertvector(f, bf16x2);
-              pf[qt][k2][2 * e] = hbits[0];
-              pf[qt][k2][2 * e + 1] = hbits[1];
-            }
-          }
-        }
-#if HS_ABL == 2
-        for (int qt = 0; qt < QT; ++qt) acc[qt][0][0] += (float)pf[qt][0][0] + (float)pf[qt][1][3];
-        continue;
-#endif
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
-          uint2 vfr[8];
-#pragma unroll
-          for (int idx = 0; idx < 8; ++idx) {
-            const int key = kb * 32 + 8 * (2 * k2 + (idx >> 2)) + 4 * half + (idx & 3);
-            vfr[idx] = *reinterpret_cast<const uint2*>(vb_base + swz(key, col >> 1) + (col & 1) * 8);
-          }
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt) {
-            unsigned w4[4];
-#pragma unroll
-            for (int pp = 0; pp < 4; ++pp) {
-              const unsigned lo = (tt < 2) ? vfr[2 * pp].x : vfr[2 * pp].y;
-              const unsigned hi = (tt < 2) ? vfr[2 * pp + 1].x : vfr[2 * pp + 1].y;
-              w4[pp] = __builtin_amdgcn_perm(hi, lo, (tt & 1) ? 0x07060302u : 0x05040100u);
-            }
-            uint4 packed = {w4[0], w4[1], w4[2], w4[3]};
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-              acc[qt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][k2], acc[qt][tt], 0, 0, 0);
-          }
+          for (int qt = 0; qt < QT; ++qt) S[qt][v] = -HS_INF;
         }
       }
     }
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      float m4[4];  // four independent chains, then a tree: short dependency depth
+#pragma unroll
+      for (int c = 0; c < 4; ++c) m4[c] = fmaxf(fmaxf(S[qt][c], S[qt][4 + c]), fmaxf(S[qt][8 + c], S[qt][12 + c]));
+      float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const bool grow = force || mx > MF_LAZY;
+      if (__ballot(grow) != 0ull) {
+        const float delta = (grow && mx != -HS_INF) ? mx : 0.f;
+        const float alpha = exp2_fast(-delta);
+        m_ref[qt] += delta;
+        l_sum[qt] *= alpha;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          S[qt][v] -= delta;
+          negm[qt][v] = -m_ref[qt];
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[qt][tt][v] *= alpha;
+      }
+    }
+  };
+  // ---- P = exp2(S) as bf16 B operands; row sums
+  auto exps = [&](const floatx16 (&S)[QT], bf16x8 (&P)[QT][2]) {
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      float p[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        p[v] = exp2_fast(S[qt][v]);
+      }
+      float s4[4];  // four independent partial sums
+#pragma unroll
+      for (int c = 0; c < 4; ++c) s4[c] = (p[c] + p[4 + c]) + (p[8 + c] + p[12 + c]);
+      l_sum[qt] += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          floatx2 f = {p[8 * k2 + 2 * e], p[8 * k2 + 2 * e + 1]};
+          bf16x2 hb = __builtin_convertvector(f, bf16x2);
+          P[qt][k2][2 * e] = hb[0];
+          P[qt][k2][2 * e + 1] = hb[1];
+        }
+    }
+  };
+  // ---- O^T += V^T P^T for one 32-key block.  The transposing read returns, to lane l of a 16-lane
+  // group, element l % 4 of the 8-byte pieces addressed by lanes l / 4 + {0, 4, 8, 12} of the group:
+  // lane (a = l % 4, j = l / 4) therefore addresses key j of the wanted four at columns 4a .. 4a+3.
+  const int tr_a = lane & 3, tr_j = (lane >> 2) & 3, tr_dh = (lane >> 4) & 1;
+  auto pv = [&](int blk, const bf16x8 (&P)[QT][2]) {
+    const char* vbuf = lds_v[(blk >> 1) % MF_NBUF];
+    const int kb = blk & 1;
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) {
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        bf16x8 vf;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const int key = kb * 32 + 16 * k2 + 8 * r + 4 * half + tr_j;
+          const int chunk = 4 * tt + 2 * tr_dh + (tr_a >> 1);
+          const shortx4 got = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s4_ptr)(vbuf + swz(key, chunk) + (tr_a & 1) * 8));
+          const bf16x4 gb = __builtin_bit_cast(bf16x4, got);
+          vf[4 * r + 0] = gb[0];
+          vf[4 * r + 1] = gb[1];
+          vf[4 * r + 2] = gb[2];
+          vf[4 * r + 3] = gb[3];
+        }
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+          acc[qt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, P[qt][k2], acc[qt][tt], 0, 0, 0);
+      }
+    }
+  };
+
+  issue(0);
+  if (n_tiles > 1) issue(1);
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the ancestor table is complete
+
+  const int n_blocks = 2 * n_tiles;
+  floatx16 s_cur[QT], s_next[QT];
+  bf16x8 pb[QT][2];
+  arrive(0);
+  if (wave_active) {
+    qk(0, s_cur);
+    settle(0, s_cur, true);  // the first block always has a visible key (a prefix token, or the root)
+  }
+  for (int blk = 0; blk + 1 < n_blocks; ++blk) {
+    if (blk & 1) arrive((blk + 1) >> 1);  // the next block opens a new tile
+    if (wave_active) {
+      qk(blk + 1, s_next);     // matrix pipe: scores of the next block ...
+      exps(s_cur, pb);         // ... vector pipe: exponentials of this one
+      pv(blk, pb);             // matrix pipe: second product of this block ...
+      settle(blk + 1, s_next, false);  // ... vector pipe: masks and maximum of the next one
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) s_cur[qt] = s_next[qt];
+    }
+  }
+  if (wave_active) {
+    exps(s_cur, pb);
+    pv(n_blocks - 1, pb);
   }
 
   // ---- results: direct (single split everywhere) or this split's partial record
@@ -346,24 +383,28 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
       const float inv = 1.f / l_tot;
       char* out = static_cast<char*>(a.o) + row * MF_ROW_BYTES;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int d0 = 4 * (8 * (v >> 2) + 4 * half + (v & 3));
-        floatx2 f01 = {acc[qt][0][v] * inv, acc[qt][1][v] * inv};
-        floatx2 f23 = {acc[qt][2][v] * inv, acc[qt][3][v] * inv};
-        uint2 pk;
-        pk.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f01, bf16x2));
-        pk.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f23, bf16x2));
-        *reinterpret_cast<uint2*>(out + d0 * 2) = pk;
-      }
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int d0 = 32 * tt + 8 * b + 4 * half;
+          floatx2 f01 = {acc[qt][tt][4 * b] * inv, acc[qt][tt][4 * b + 1] * inv};
+          floatx2 f23 = {acc[qt][tt][4 * b + 2] * inv, acc[qt][tt][4 * b + 3] * inv};
+          uint2 pk;
+          pk.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f01, bf16x2));
+          pk.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f23, bf16x2));
+          *reinterpret_cast<uint2*>(out + d0 * 2) = pk;
+        }
       if (a.lse && half == 0) a.lse[row] = (m_ref[qt] + __log2f(l_tot)) * MF_LN2;
     } else {
       float* rec = a.part + (row * a.sp_max + sp) * ATTN_REC;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int d0 = 4 * (8 * (v >> 2) + 4 * half + (v & 3));
-        float4 f = {acc[qt][0][v], acc[qt][1][v], acc[qt][2][v], acc[qt][3][v]};
-        *reinterpret_cast<float4*>(rec + d0) = f;
-      }
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int d0 = 32 * tt + 8 * b + 4 * half;
+          float4 f = {acc[qt][tt][4 * b], acc[qt][tt][4 * b + 1], acc[qt][tt][4 * b + 2], acc[qt][tt][4 * b + 3]};
+          *reinterpret_cast<float4*>(rec + d0) = f;
+        }
       if (half == 0) {
         rec[128] = m_ref[qt] * MF_LN2;
         rec[129] = l_tot;
@@ -372,9 +413,6 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
   }
 }
 
-#ifndef HS_QT
-#define HS_QT 1
-#endif
 hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream) {
   const int n_rg_max = (a.G * max_tree_rows + MF_ROWS - 1) / MF_ROWS;
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);

@@ -37,7 +37,10 @@ def _compare(G, step, dtype):
     got_o, got_lse = G.run_attention(step)
     err = np.abs(got_o.astype(np.float64) - want_o).max()
     assert err <= TOL[dtype], err
-    assert np.abs(got_lse - want_lse).max() <= (1e-4 if dtype == "f32" else 1e-3)
+    # bf16: the kernel folds scale * log2(e) into Q and rounds it to bf16 again, which perturbs each
+    # score by at most 2^-9 * sum_d |q_d k_d| * scale (about 1.4e-2 for unit-variance inputs); with
+    # few keys the log-sum-exp moves by as much, so it gets the same 2e-2 bound as the outputs
+    assert np.abs(got_lse - want_lse).max() <= (1e-4 if dtype == "f32" else 2e-2)
     # besides the stated bound: the error should be rounding-sized relative to the output scale
     scale = np.abs(want_o).max()
     assert err <= (1e-5 if dtype == "f32" else 6e-3) * max(scale, 1e-6) + 1e-7, (err, scale)
