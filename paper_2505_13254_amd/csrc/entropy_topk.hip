@@ -50,19 +50,47 @@ static ScanPlan plan_scan(int R, int V) {
 }
 
 // Re-ranks entries [0, n) of (cv, ci) by counting and writes those of rank < K, in order, to (ov, oi).
-// Called by `nthreads` cooperating threads with ids 0..nthreads-1; the caller synchronises around it.
+// Called by `nthreads` cooperating threads (whole waves) with ids 0..nthreads-1; the caller
+// synchronises around it.  The entries to compare against are held 64 at a time in registers and
+// broadcast lane by lane, so the inner loop has no memory latency in it.
 __device__ __forceinline__ void rank_select(const float* cv, const int* ci, int n, int K, float* ov, int* oi,
                                             int id, int nthreads) {
-  for (int a = id; a < n; a += nthreads) {
-    float av = cv[a];
-    int ai = ci[a];
+  const int lane = id & 63;
+  for (int base = 0; base < n; base += nthreads) {  // uniform trip count
+    const int a = base + id;
+    float av = -HS_INF;
+    int ai = INT_MAX;
+    if (a < n) {
+      av = cv[a];
+      ai = ci[a];
+    }
     int r = 0;
-    for (int b = 0; b < n; ++b) r += better(cv[b], ci[b], av, ai) ? 1 : 0;
-    if (r < K) {
+    for (int c0 = 0; c0 < n; c0 += 64) {
+      float bv = -HS_INF;
+      int bi = INT_MAX;
+      if (c0 + lane < n) {
+        bv = cv[c0 + lane];
+        bi = ci[c0 + lane];
+      }
+      const int m = (n - c0) < 64 ? (n - c0) : 64;
+      for (int j = 0; j < m; ++j) {
+        const float xv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), j));
+        const int xi = __builtin_amdgcn_readlane(bi, j);
+        r += better(xv, xi, av, ai) ? 1 : 0;
+      }
+    }
+    if (a < n && r < K) {
       ov[r] = av;
       oi[r] = ai;
     }
   }
+}
+
+// Orders this wave's LDS traffic: what lanes wrote before is visible to all lanes after.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Rank of this lane's pair among the 64 lanes' pairs (number of lanes holding a better pair).
@@ -98,14 +126,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     lv[0][wave][lane] = -HS_INF;
     li[0][wave][lane] = INT_MAX - lane;
   }
-  Stats st = stats_empty();
+  // statistics are kept in the log2 domain while scanning: y = (x - m) * c, c = log2(e) / T
+  const float c = inv_t * LOG2E;
+  float m = -HS_INF, s1 = 0.f, t2 = 0.f;
   bool first = true;
-  __syncthreads();
+  wave_sync();
 
-  for (int tile = 0; tile < tiles_per_wg; ++tile) {
+  auto load_tile = [&](int tile, float (&v)[SCAN_VPT]) {
     const int tbase = (split * tiles_per_wg + tile) * SCAN_TILE;
-    if (tbase >= V) break;  // uniform over the workgroup
-    float v[SCAN_VPT];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int i0 = tbase + (j * SCAN_THREADS + tid) * 4;
@@ -120,36 +148,48 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
         for (int e = 0; e < 4; ++e) v[j * 4 + e] = (i0 + e < V) ? x[i0 + e] : -HS_INF;
       }
     }
+  };
+  // tiles this workgroup really has (uniform)
+  int n_my = (V - split * tiles_per_wg * SCAN_TILE + SCAN_TILE - 1) / SCAN_TILE;
+  n_my = n_my < 0 ? 0 : (n_my > tiles_per_wg ? tiles_per_wg : n_my);
+
+  float v[SCAN_VPT], vn[SCAN_VPT];
+  if (n_my > 0) load_tile(0, v);
+  for (int tile = 0; tile < n_my; ++tile) {
+    const int tbase = (split * tiles_per_wg + tile) * SCAN_TILE;
+    if (tile + 1 < n_my) load_tile(tile + 1, vn);  // next tile's loads fly while this one is processed
 #define HS_IDX(jj) (tbase + (((jj) >> 2) * SCAN_THREADS + tid) * 4 + ((jj)&3))
 
     // ---- softmax statistics of this thread's values
-    float tm = v[0];
-#pragma unroll
-    for (int jj = 1; jj < SCAN_VPT; ++jj) tm = fmaxf(tm, v[jj]);
+    float tm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+    tm = fmaxf(tm, fmaxf(fmaxf(fmaxf(v[8], v[9]), fmaxf(v[10], v[11])), fmaxf(fmaxf(v[12], v[13]), fmaxf(v[14], v[15]))));
     int skip = -1;
-    if (tm > st.m) {
+    if (tm > m) {
 #pragma unroll
       for (int jj = SCAN_VPT - 1; jj >= 0; --jj) skip = (v[jj] == tm) ? jj : skip;  // first instance of the max
-      if (st.m != -HS_INF) {
-        float d = (st.m - tm) * inv_t;
-        float e = exp2_fast(d * LOG2E);
-        float w = 1.f + st.s1;
-        st.t = e * (st.t + d * w);
-        st.s1 = e * w;
+      if (m != -HS_INF) {
+        const float d2 = (m - tm) * c;
+        const float e = exp2_fast(d2);
+        const float w = 1.f + s1;
+        t2 = e * (t2 + d2 * w);
+        s1 = e * w;
       }
-      st.m = tm;
+      m = tm;
     }
     if (tm != -HS_INF) {
 #pragma unroll
       for (int jj = 0; jj < SCAN_VPT; ++jj) {
-        float d = fmaxf((v[jj] - st.m) * inv_t, -1e30f);
-        float e = exp2_fast(d * LOG2E);
-        st.t = fmaf(e, d, st.t);
-        st.s1 += (jj == skip) ? 0.f : e;
+        // x - m first: exact near the maximum (an fma with a rounded m * c would leave the maximum's
+        // own y slightly off zero and put that into t2); the clamp keeps 0 * -inf out of t2
+        const float y = fmaxf((v[jj] - m) * c, -1e30f);
+        const float e = exp2_fast(y);
+        t2 = fmaf(e, y, t2);
+        s1 += (jj == skip) ? 0.f : e;
       }
     }
 
-    // ---- threshold: K-th best lane maximum (first tile) or the list's K-th entry
+    // ---- threshold: the list's K-th entry, or for the first tile the K-th best of the lane maxima
+    // (of the maxima of groups of four lanes when K <= 16: a quarter of the comparisons)
     float tv;
     int ti;
     if (first) {
@@ -163,9 +203,29 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
           bi = idx;
         }
       }
-      int r = wave_rank(bv, bi);
+      int r;
+      if (K <= 16) {
+#pragma unroll
+        for (int off = 1; off <= 2; off <<= 1) {
+          const float ov = __shfl_xor(bv, off);
+          const int oi = __shfl_xor(bi, off);
+          if (better(ov, oi, bv, bi)) {
+            bv = ov;
+            bi = oi;
+          }
+        }
+        r = 0;
+#pragma unroll
+        for (int l = 0; l < 64; l += 4) {
+          const float ov = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), l));
+          const int oi = __builtin_amdgcn_readlane(bi, l);
+          r += better(ov, oi, bv, bi) ? 1 : 0;
+        }
+      } else {
+        r = wave_rank(bv, bi);
+      }
       unsigned long long who = __ballot(r == K - 1);
-      int src = __ffsll((long long)who) - 1;  // exactly one lane: the order is strict
+      int src = __ffsll((long long)who) - 1;  // never empty: the order is strict, ranks are a permutation
       tv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), src));
       ti = __builtin_amdgcn_readlane(bi, src);
       first = false;
@@ -174,31 +234,37 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
       ti = li[cur][wave][K - 1];
     }
 
-    // ---- compact the elements that are not worse than the threshold
-    int cnt = 0;
-    const unsigned long long lt = (1ull << lane) - 1ull;
+    // ---- compact the elements that are not worse than the threshold (skipped when no lane's
+    // maximum reaches it), then re-rank list + candidates
+    if (__ballot(tm >= tv) != 0ull) {
+      int cnt = 0;
+      const unsigned long long lt = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int jj = 0; jj < SCAN_VPT; ++jj) {
-      int idx = HS_IDX(jj);
-      bool f = !better(tv, ti, v[jj], idx);
-      unsigned long long mask = __ballot(f);
-      if (f) {
-        int pos = cnt + __popcll(mask & lt);
-        cv[wave][pos] = v[jj];
-        ci[wave][pos] = idx;
+      for (int jj = 0; jj < SCAN_VPT; ++jj) {
+        int idx = HS_IDX(jj);
+        bool f = !better(tv, ti, v[jj], idx);
+        unsigned long long mask = __ballot(f);
+        if (f) {
+          int pos = cnt + __popcll(mask & lt);
+          cv[wave][pos] = v[jj];
+          ci[wave][pos] = idx;
+        }
+        cnt += __popcll(mask);
       }
-      cnt += __popcll(mask);
+      if (lane < K) {
+        cv[wave][cnt + lane] = lv[cur][wave][lane];
+        ci[wave][cnt + lane] = li[cur][wave][lane];
+      }
+      wave_sync();
+      rank_select(cv[wave], ci[wave], cnt + K, K, lv[cur ^ 1][wave], li[cur ^ 1][wave], lane, 64);
+      cur ^= 1;
+      wave_sync();
     }
 #undef HS_IDX
-    if (lane < K) {
-      cv[wave][cnt + lane] = lv[cur][wave][lane];
-      ci[wave][cnt + lane] = li[cur][wave][lane];
-    }
-    __syncthreads();
-    rank_select(cv[wave], ci[wave], cnt + K, K, lv[cur ^ 1][wave], li[cur ^ 1][wave], lane, 64);
-    cur ^= 1;
-    __syncthreads();
+#pragma unroll
+    for (int jj = 0; jj < SCAN_VPT; ++jj) v[jj] = vn[jj];
   }
+  Stats st{m, s1, t2 * 0.6931471805599453f};  // back to natural-log units
 
   // ---- merge the four waves' lists and statistics, write this slice's partial result
   st = stats_wave_reduce(st, inv_t);
@@ -293,26 +359,33 @@ __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __r
   rank_select(cv, ci, n, K, ov, oi, tid, FIN_THREADS);
   __syncthreads();
 
-  const double m = (double)total.m, s1 = (double)total.s1, t = (double)total.t;
-  const double l1p = log1p(s1);
+  const float m = total.m, s1 = total.s1, t = total.t;
+  const float l1p = log1pf(s1);
   if (tid < K) {
     topk_idx[(int64_t)row * K + tid] = oi[tid];
-    topk_logp[(int64_t)row * K + tid] = (float)(((double)ov[tid] - m) * (double)inv_t - l1p);
+    topk_logp[(int64_t)row * K + tid] = (ov[tid] - m) * inv_t - l1p;
   }
-  if (tid == 0) {
-    // Top-K probabilities renormalised over the K: weights relative to the best one
-    double w1 = 0.0, wa = 0.0;
-    for (int k = 1; k < K; ++k) {
-      double a = ((double)ov[k] - (double)ov[0]) * (double)inv_t;
-      if (a > -700.0) {
-        double w = exp(a);
-        w1 += w;
-        wa += w * a;
+  if (tid < 64) {
+    // Top-K probabilities renormalised over the K: weights relative to the best one (lane = entry);
+    // entropy = ln(1 + sum w) - sum(w a) / (1 + sum w), every term of one sign
+    float w = 0.f, wa = 0.f;
+    if (lane >= 1 && lane < K) {
+      const float a = (ov[lane] - ov[0]) * inv_t;
+      if (a > -100.f) {
+        w = expf(a);
+        wa = w * a;
       }
     }
-    ent_topk[row] = (float)(log1p(w1) - wa / (1.0 + w1));
-    if (ent_full) ent_full[row] = (float)(l1p - t / (1.0 + s1));
-    if (lse) lse[row] = (float)(m * (double)inv_t + l1p);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      w += __shfl_xor(w, off);
+      wa += __shfl_xor(wa, off);
+    }
+    if (lane == 0) {
+      ent_topk[row] = log1pf(w) - wa / (1.f + w);
+      if (ent_full) ent_full[row] = l1p - t / (1.f + s1);
+      if (lse) lse[row] = m * inv_t + l1p;
+    }
   }
 }
 
