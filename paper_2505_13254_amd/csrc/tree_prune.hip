@@ -39,37 +39,25 @@ __device__ __forceinline__ int block_reduce_sum(int v, int* red) {
   return r;
 }
 
-__global__ __launch_bounds__(PR_THREADS) void k_prune_select(
-    const int32_t* __restrict__ parent, const float* __restrict__ logc, const int32_t* __restrict__ node_offsets,
-    const int32_t* __restrict__ d_max, const float* __restrict__ theta, const int32_t* __restrict__ max_nodes,
-    int32_t* __restrict__ depth, float* __restrict__ cumlogp, uint8_t* __restrict__ keep,
-    int32_t* __restrict__ ws_pos, int32_t* __restrict__ ws_count, int32_t* __restrict__ ws_flag) {
-  __shared__ int l_par[PR_LDS_NODES];
-  __shared__ int l_dep[PR_LDS_NODES];
-  __shared__ float l_sum[PR_LDS_NODES];
-  __shared__ int l_ok[PR_LDS_NODES];
-  __shared__ int l_new[PR_LDS_NODES];
-  __shared__ int red[PR_THREADS / 64];
-  __shared__ int chunk_sum[PR_THREADS];
+// (value, index) as one 45-bit key, index < 8192: larger key = better (larger value, then lower
+// index); never 0.
+constexpr int KEY_BITS = 45;
+__device__ __forceinline__ unsigned long long order_key(float v, int i) {
+  unsigned u = __builtin_bit_cast(unsigned, v);
+  u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;  // monotone map of float order onto unsigned order
+  return ((unsigned long long)u << 13) | (unsigned)(8191 - i);
+}
 
-  const int s = blockIdx.x, tid = threadIdx.x;
-  const int o = node_offsets[s];
-  const int n = node_offsets[s + 1] - o;
-  if (n <= 0) {
-    if (tid == 0) ws_count[s] = 0;
-    return;
-  }
-  const bool in_lds = n <= PR_LDS_NODES;
-  // large trees use the output arrays and the workspace as their scratch
-  int* par = in_lds ? l_par : const_cast<int*>(parent + o);
-  int* dep = in_lds ? l_dep : depth + o;
-  float* sum = in_lds ? l_sum : cumlogp + o;
-  int* ok = in_lds ? l_ok : ws_flag + o;
-
-  if (in_lds)
-    for (int i = tid; i < n; i += PR_THREADS) par[i] = parent[o + i];
-  __syncthreads();
-
+// The whole selection for one sequence; called once with LDS arrays and once with global scratch so
+// that each copy is compiled for its own address space.
+template <typename IP, typename FP>
+__device__ __forceinline__ void prune_sequence(
+    IP par, IP dep, FP sum, IP ok, IP nxt, unsigned long long* keys, int* bit_count, int* red, int* chunk_sum, int n,
+    int o,
+    bool copy_out, FP lc, int dcap, float th, int budget, int32_t* __restrict__ depth,
+    float* __restrict__ cumlogp, uint8_t* __restrict__ keep, int32_t* __restrict__ ws_pos,
+    int32_t* __restrict__ ws_count, int s) {
+  const int tid = threadIdx.x, lane = tid & 63;
   // depth: walk to the root
   int my_max = 0;
   for (int i = tid; i < n; i += PR_THREADS) {
@@ -85,13 +73,11 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
   const int max_depth = block_reduce_max(my_max, red);
 
   // cumulative log-confidence and the path filter, one level at a time (parents are final first)
-  const int dcap = d_max[s];
-  const float th = theta[s];
   for (int level = 1; level <= max_depth; ++level) {
     for (int i = tid; i < n; i += PR_THREADS) {
       if (dep[i] == level) {
         const int p = par[i];
-        const float v = sum[p] + fminf(logc[o + i], 0.f);
+        const float v = sum[p] + fminf(lc[i], 0.f);
         sum[i] = v;
         ok[i] = (ok[p] != 0 && level <= dcap && v >= th) ? 1 : 0;
       }
@@ -100,21 +86,41 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
   }
 
   // node budget: keep the first max_nodes candidates under (sum descending, index ascending)
-  const int budget = max_nodes[s];
   int mine = 0;
   for (int i = tid; i < n; i += PR_THREADS) mine += (i >= 1 && ok[i]) ? 1 : 0;
   const int n_cand = block_reduce_sum(mine, red);
   if (budget > 0 && n_cand > budget) {
-    int* nxt = in_lds ? l_new : ws_pos + o;  // ws_pos is not written before the last phase
-    for (int i = tid; i < n; i += PR_THREADS) {
-      int flag = ok[i];
-      if (i >= 1 && flag) {
-        const float v = sum[i];
-        int r = 0;
-        for (int j = 1; j < n; ++j) r += (ok[j] && better(sum[j], j, v, i)) ? 1 : 0;
-        flag = r < budget ? 1 : 0;
+    if (keys != nullptr) {
+      // The budget-th best key, bit by bit from the top: x grows while at least `budget` keys are
+      // >= x.  Keys are distinct, so exactly `budget` candidates end up >= x.  One count (wave
+      // popcounts added in LDS) and one barrier per bit; non-candidates carry key 0.
+      for (int i = tid; i < n; i += PR_THREADS) keys[i] = (i >= 1 && ok[i]) ? order_key(sum[i], i) : 0ull;
+      for (int b = tid; b < 64; b += PR_THREADS) bit_count[b] = 0;
+      __syncthreads();
+      unsigned long long x = 0ull;
+      for (int bit = KEY_BITS - 1; bit >= 0; --bit) {
+        const unsigned long long cand = x | (1ull << bit);
+        int c = 0;  // wave-wide count: ballots and scalar popcounts, no cross-lane data movement
+        for (int base = 0; base < n; base += PR_THREADS) {
+          const int i = base + tid;
+          c += __popcll(__ballot(i < n && keys[i] >= cand));
+        }
+        if (lane == 0 && c != 0) atomicAdd(&bit_count[bit], c);
+        __syncthreads();
+        if (bit_count[bit] >= budget) x = cand;
       }
-      nxt[i] = flag;
+      for (int i = tid; i < n; i += PR_THREADS) nxt[i] = (i == 0) ? 1 : ((keys[i] != 0ull && keys[i] >= x) ? 1 : 0);
+    } else {
+      for (int i = tid; i < n; i += PR_THREADS) {
+        int flag = ok[i];
+        if (i >= 1 && flag) {
+          const float v = sum[i];
+          int r = 0;
+          for (int j = 1; j < n; ++j) r += (ok[j] && better(sum[j], j, v, i)) ? 1 : 0;
+          flag = r < budget ? 1 : 0;
+        }
+        nxt[i] = flag;
+      }
     }
     __syncthreads();
     for (int i = tid; i < n; i += PR_THREADS) ok[i] = nxt[i];
@@ -128,14 +134,25 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
   for (int i = lo; i < hi; ++i) c += ok[i] ? 1 : 0;
   chunk_sum[tid] = c;
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int t = 0; t < PR_THREADS; ++t) {
-      int x = chunk_sum[t];
-      chunk_sum[t] = run;
-      run += x;
+  if (tid < 64) {
+    // exclusive scan of the PR_THREADS chunk totals by one wave: PR_THREADS / 64 per lane
+    constexpr int PER = PR_THREADS / 64;
+    int loc[PER], tot = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      loc[q] = tot;
+      tot += chunk_sum[tid * PER + q];
     }
-    ws_count[s] = run;
+    int incl = tot;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    const int excl = incl - tot;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) chunk_sum[tid * PER + q] = excl + loc[q];
+    if (tid == 63) ws_count[s] = incl;
   }
   __syncthreads();
   int pos = chunk_sum[tid];
@@ -144,10 +161,52 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
     ws_pos[o + i] = k ? pos : -1;
     keep[o + i] = (uint8_t)k;
     pos += k;
-    if (in_lds) {
+    if (copy_out) {
       depth[o + i] = dep[i];
       cumlogp[o + i] = sum[i];
     }
+  }
+}
+
+__global__ __launch_bounds__(PR_THREADS) void k_prune_select(
+    const int32_t* __restrict__ parent, const float* __restrict__ logc, const int32_t* __restrict__ node_offsets,
+    const int32_t* __restrict__ d_max, const float* __restrict__ theta, const int32_t* __restrict__ max_nodes,
+    int32_t* __restrict__ depth, float* __restrict__ cumlogp, uint8_t* __restrict__ keep,
+    int32_t* __restrict__ ws_pos, int32_t* __restrict__ ws_count, int32_t* __restrict__ ws_flag) {
+  __shared__ int l_par[PR_LDS_NODES];
+  __shared__ int l_dep[PR_LDS_NODES];
+  __shared__ float l_sum[PR_LDS_NODES];
+  __shared__ int l_ok[PR_LDS_NODES];
+  __shared__ int l_new[PR_LDS_NODES];
+  __shared__ unsigned long long l_keys[PR_LDS_NODES];
+  __shared__ int bit_count[64];
+  __shared__ float l_logc[PR_LDS_NODES];
+  __shared__ int red[PR_THREADS / 64];
+  __shared__ int chunk_sum[PR_THREADS];
+
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const int o = node_offsets[s];
+  const int n = node_offsets[s + 1] - o;
+  if (n <= 0) {
+    if (tid == 0) ws_count[s] = 0;
+    return;
+  }
+  if (n <= PR_LDS_NODES) {
+    // one round trip to global memory for the whole tree; everything after runs out of LDS
+    const int dcap = d_max[s], budget = max_nodes[s];
+    const float th = theta[s];
+    for (int i = tid; i < n; i += PR_THREADS) {
+      l_par[i] = parent[o + i];
+      l_logc[i] = logc[o + i];
+    }
+    __syncthreads();
+    prune_sequence(l_par, l_dep, l_sum, l_ok, l_new, l_keys, bit_count, red, chunk_sum, n, o, true, l_logc, dcap, th, budget, depth, cumlogp, keep, ws_pos, ws_count, s);
+  } else {
+    // very large trees: the output arrays and the workspace are the scratch (ws_pos is not written
+    // before the last phase, so it can hold the budget flags meanwhile)
+    prune_sequence(const_cast<int32_t*>(parent + o), depth + o, cumlogp + o, ws_flag + o, ws_pos + o, (unsigned long long*)nullptr, bit_count, red,
+                   chunk_sum, n, o, false, const_cast<float*>(logc + o), d_max[s], theta[s], max_nodes[s], depth, cumlogp,
+                   keep, ws_pos, ws_count, s);
   }
 }
 
