@@ -265,6 +265,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     for (int jj = 0; jj < SCAN_VPT; ++jj) v[jj] = vn[jj];
   }
   Stats st{m, s1, t2 * 0.6931471805599453f};  // back to natural-log units
+  // waves flip their list buffers independently (tiles without candidates are skipped per wave):
+  // bring every wave's final list to buffer 0 before the lists are merged
+  if (cur == 1 && lane < K) {
+    lv[0][wave][lane] = lv[1][wave][lane];
+    li[0][wave][lane] = li[1][wave][lane];
+  }
 
   // ---- merge the four waves' lists and statistics, write this slice's partial result
   st = stats_wave_reduce(st, inv_t);
@@ -274,8 +280,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
   int* mi = &ci[1][0];
   if (tid < SCAN_WAVES * K) {
     int w = tid / K, k = tid - w * K;
-    mv[tid] = lv[cur][w][k];
-    mi[tid] = li[cur][w][k];
+    mv[tid] = lv[0][w][k];
+    mi[tid] = li[0][w][k];
   }
   __syncthreads();
   const int64_t pbase = ((int64_t)row * S + split) * K;

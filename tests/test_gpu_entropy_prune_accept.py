@@ -43,7 +43,7 @@ def test_entropy_workload1_rows(G):
 
 
 @pytest.mark.parametrize("R,V,K", [(1, 5, 5), (3, 64, 1), (2, 1000, 64), (5, 4097, 7), (1, 131, 3), (7, 20000, 10),
-                                   (300, 777, 4), (2, 262147, 10)])
+                                   (300, 777, 4), (2, 262147, 10), (1200, 20000, 10), (700, 40000, 1)])
 def test_entropy_shapes_spanning_tiles_and_tails(G, R, V, K):
     rs = np.random.RandomState(R * 1000 + V)
     rows = (rs.randn(R, V) * rs.uniform(0.3, 10, size=(R, 1))).astype(np.float32)

@@ -1,0 +1,108 @@
+"""Parity at the workloads' full sizes, in the launch configuration bench.py times: the step is built
+and run by the GPU harness, then every stage's device inputs are pulled back and checked against the
+CPU checker: whole outputs where that is cheap, sampled rows / heads where it is not."""
+import numpy as np
+import pytest
+
+from synth import workloads as W
+from oracle import draft_entropy_topk, tree_prune, tree_attention, verify_accept
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_13254_amd import harness
+    return harness
+
+
+def _np(t):
+    torch.cuda.synchronize()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def _check_step(st, rs, n_rows=6, n_heads=3, accept_mode=0):
+    w, t, h = st.w, st.t, st.host
+    st.run()
+    torch.cuda.synchronize()
+    # ---- stage 1 on sampled rows: indices bit-exact, entropies 1e-5
+    R = t["draft_rows"].shape[0]
+    rows = sorted(set(int(x) for x in rs.randint(0, R, size=n_rows)) | {0, R - 1})
+    want = draft_entropy_topk(_np(t["draft_rows"][rows]), w.topk, w.temperature)
+    got = {k: _np(v)[rows] for k, v in t["s1_out"].items()}
+    assert np.array_equal(got["topk_idx"], want["topk_idx"])
+    for k in ("ent_topk", "ent_full"):
+        assert np.all(np.abs(got[k] - want[k]) <= 1e-5 * np.maximum(np.abs(want[k]), 1e-3)), k
+    # ---- stage 2, whole: same float32 confidences on both sides
+    pr = tree_prune(_np(t["cand_parent"]), _np(t["cand_logc"]), _np(t["cand_offsets"]), _np(t["d_max"]),
+                    _np(t["theta"]), _np(t["max_nodes"]))
+    s2 = {k: _np(v) for k, v in t["s2_out"].items()}
+    n = int(pr["out_offsets"][-1])
+    assert np.array_equal(s2["keep"], pr["keep"]) and np.array_equal(s2["out_offsets"], pr["out_offsets"])
+    assert np.array_equal(s2["out_src"][:n], pr["out_src"]) and np.array_equal(s2["out_parent"][:n], pr["out_parent"])
+    assert np.array_equal(s2["cumlogp"].view(np.uint32), pr["cumlogp"].view(np.uint32))
+    # ---- stage 3 on sampled (batch entry, query head): all rows of that head
+    no, po = h["attn_node_offsets"].numpy(), h["attn_prefix_offsets"].numpy()
+    parent = _np(t["attn_parent"])
+    o = t["o"].float().cpu().numpy()
+    G = w.Hq // w.Hkv
+    for _ in range(n_heads):
+        b = int(rs.randint(0, len(no) - 1))
+        hq = int(rs.randint(0, w.Hq))
+        g = hq // G
+        n0, n1, p0, p1 = int(no[b]), int(no[b + 1]), int(po[b]), int(po[b + 1])
+        if n1 == n0:
+            continue
+        wo, _ = tree_attention(_np(t["q"][n0:n1, hq:hq + 1]), _np(t["k_prefix"][p0:p1, g:g + 1]),
+                               _np(t["v_prefix"][p0:p1, g:g + 1]), _np(t["k_tree"][n0:n1, g:g + 1]),
+                               _np(t["v_tree"][n0:n1, g:g + 1]), parent[n0:n1], [0, n1 - n0], [0, p1 - p0], h["scale"])
+        err = np.abs(o[n0:n1, hq] - wo[:, 0]).max()
+        assert err <= (2e-2 if w.dtype == "bf16" else 1e-4), (b, hq, err)
+        assert err <= 6e-3 * np.abs(wo).max() + 1e-6, (b, hq, err, np.abs(wo).max())
+    # ---- stage 4, whole walk (argmax rows are cheap; the stochastic modes read only visited rows)
+    tl = _np(t["target_logits"])
+    dl = _np(t["draft_logits"]) if accept_mode == 1 else None
+    wa = verify_accept(tl, dl, _np(t["token"]), s2["out_parent"][:n], s2["out_offsets"], accept_mode, w.temperature,
+                       _np(t["uniforms"]) if accept_mode else None, h["max_depth"])
+    ga = {k: _np(v) for k, v in t["s4_out"].items()}
+    for k in wa:
+        assert np.array_equal(ga[k], wa[k]), (k, ga[k], wa[k])
+    return wa
+
+
+def test_workload2_bench_configuration(H):
+    w = W.WORKLOADS[2]
+    st = H.build_step(w, 0, layers=w.layers, accept_mode=0)
+    assert st.host["NNp"] == 61 and st.host["cand_nodes"] == 511 and st.t["q"].shape[0] == 61 * 32
+    _check_step(st, np.random.RandomState(0), n_heads=6)
+
+
+def test_workload3_threshold_sweep(H):
+    w = W.WORKLOADS[3]
+    kept = []
+    for th in w.theta:
+        st = H.build_step(w, 0, layers=1, accept_mode=0, theta=th)
+        _check_step(st, np.random.RandomState(1), n_rows=3, n_heads=2)
+        kept.append(set(st.host["out_src"].tolist()))
+    assert kept[0] <= kept[1] <= kept[2]
+
+
+def test_workload4_single_layer(H):
+    w = W.WORKLOADS[4]
+    st = H.build_step(w, 0, layers=1, accept_mode=0)
+    assert st.host["NNp"] == 97
+    _check_step(st, np.random.RandomState(2), n_rows=3, n_heads=3)
+
+
+def test_workload5_ragged_batch(H):
+    w = W.WORKLOADS[5]
+    st = H.build_step(w, 0, layers=1, accept_mode=0)
+    sizes = np.diff(st.host["out_offsets"])
+    assert len(sizes) == 16 and sizes.min() >= 2 and sizes.max() <= 129
+    res = _check_step(st, np.random.RandomState(3), n_rows=4, n_heads=5)
+    assert res["accept_len"].shape == (16,)
