@@ -20,9 +20,10 @@
 // core delivers x - m directly and the only per-score vector work is exp2, the row sum and the
 // conversion to bf16.  The reference maximum is updated lazily: accumulators are rescaled only when
 // a score exceeds the reference by more than 2^8 (exact after the final division by the equally
-// referenced denominator).  That check runs one block ahead, next to the second product's MFMAs,
-// and the first product of block b+1 is issued together with the exponentials of block b, so matrix
-// and vector instructions of independent blocks sit in the same scheduling region.
+// referenced denominator).  The check costs one compare per block: it rides on the row sum of the
+// exponentials, which exceeds 2^8 whenever a score does, and only then is the exact maximum taken.
+// The first product of block b+1 is issued together with the exponentials of block b, so matrix and
+// vector instructions of independent blocks sit in the same scheduling region.
 //
 // The tree part (ancestor mask) is a bit table built in LDS from the parent pointers.
 //
@@ -200,19 +201,38 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
   // wait counters nor orders LDS reads of other ring slots behind them.
   const unsigned lds_k_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_k[0][0];
   const unsigned lds_v_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_v[0][0];
+  // per-lane byte offsets inside a full prefix tile: fixed for the whole pass
+  int64_t lane_off[LOADS];
+  unsigned lane_lds[LOADS];
+#pragma unroll
+  for (int j = 0; j < LOADS; ++j) {
+    const int c = j * THREADS + tid;  // LDS slot (16-byte units) this lane fills
+    const int row = c >> 4, slot = c & 15;
+    lane_off[j] = (int64_t)row * tok_stride + ((slot ^ swz_key(row)) << 4);
+    lane_lds[j] = (unsigned)((j * THREADS + wave * 64) << 4);  // wave-uniform LDS byte offset
+  }
   auto issue = [&](int t) {
-    const TileSrc ts = tile_src(t);
     const unsigned ring = (unsigned)(t % MF_NBUF) * MF_TILE_BYTES;
+    if (t < n_ptiles && k_lo + (int64_t)(t + 1) * MF_TILE <= k_hi) {
+      // a full tile of prefix keys: one scalar base plus the fixed lane offsets
+      const int64_t tile_off = (k_lo + (int64_t)t * MF_TILE) * tok_stride;
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        lds_dma16(kp + tile_off + lane_off[j], lds_k_addr + ring + lane_lds[j]);
+        lds_dma16(vp + tile_off + lane_off[j], lds_v_addr + ring + lane_lds[j]);
+      }
+      return;
+    }
+    const TileSrc ts = tile_src(t);
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
-      const int c = j * THREADS + tid;  // LDS slot (16-byte units) this lane fills
+      const int c = j * THREADS + tid;
       const int row = c >> 4, slot = c & 15;
       int64_t key = ts.base + row;
       key = key < ts.limit ? key : ts.limit - 1;  // rows past the end repeat the last row (masked later)
       const int64_t off = key * tok_stride + ((slot ^ swz_key(row)) << 4);
-      const unsigned wave_slot = ring + (unsigned)((j * THREADS + wave * 64) << 4);  // wave-uniform
-      lds_dma16(ts.k + off, lds_k_addr + wave_slot);
-      lds_dma16(ts.v + off, lds_v_addr + wave_slot);
+      lds_dma16(ts.k + off, lds_k_addr + ring + lane_lds[j]);
+      lds_dma16(ts.v + off, lds_v_addr + ring + lane_lds[j]);
     }
   };
   // Wait until this wave's loads of tile t have landed (only the loads of tile t+1 may still be
@@ -236,9 +256,10 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
         S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][kk], kk == 0 ? negm[qt] : S[qt], 0, 0, 0);
     }
   };
-  // ---- masks (tree keys off the row's root path, keys past the end), block maximum, lazy update of
-  // the reference.  S holds x - m_ref on entry and on exit.
-  auto settle = [&](int blk, floatx16 (&S)[QT], bool force) {
+  // ---- masks of a block's scores: tree keys off the row's root path, keys past the end of the
+  // split.  Only the blocks from n_plain on need it (the partial prefix tail and the tree part).
+  const int n_plain = (int)((k_hi - k_lo) >> 5);
+  auto mask_block = [&](int blk, floatx16 (&S)[QT]) {
     const TileSrc ts = tile_src(blk >> 1);
     const int64_t bbase = ts.base + (blk & 1) * 32;
     if (ts.tree) {
@@ -262,44 +283,56 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
         }
       }
     }
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      float m4[4];  // four independent chains, then a tree: short dependency depth
-#pragma unroll
-      for (int c = 0; c < 4; ++c) m4[c] = fmaxf(fmaxf(S[qt][c], S[qt][4 + c]), fmaxf(S[qt][8 + c], S[qt][12 + c]));
-      float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const bool grow = force || mx > MF_LAZY;
-      if (__ballot(grow) != 0ull) {
-        const float delta = (grow && mx != -HS_INF) ? mx : 0.f;
-        const float alpha = exp2_fast(-delta);
-        m_ref[qt] += delta;
-        l_sum[qt] *= alpha;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          S[qt][v] -= delta;
-          negm[qt][v] = -m_ref[qt];
-        }
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[qt][tt][v] *= alpha;
-      }
-    }
   };
-  // ---- P = exp2(S) as bf16 B operands; row sums
-  auto exps = [&](const floatx16 (&S)[QT], bf16x8 (&P)[QT][2]) {
+  // exact maximum of a row's 32 scores of a block (both half-waves)
+  auto row_max = [&](const floatx16& S) {
+    float m4[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) m4[c] = fmaxf(fmaxf(S[c], S[4 + c]), fmaxf(S[8 + c], S[12 + c]));
+    const float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+    return fmaxf(mx, __shfl_xor(mx, 32));
+  };
+  // moves the reference maximum of row block qt up by delta (>= 0 except at the very first block)
+  auto move_reference = [&](int qt, float delta) {
+    const float alpha = exp2_fast(-delta);
+    m_ref[qt] += delta;
+    l_sum[qt] *= alpha;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negm[qt][v] = -m_ref[qt];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[qt][tt][v] *= alpha;
+  };
+  // ---- P = exp2(S) as bf16 B operands; row sums.  The lazy reference check rides on the row sum:
+  // a score above the reference by more than 2^8 makes the sum exceed 2^8 (so does an overflow), and
+  // only then the exact maximum is taken, the reference moved and the block redone.  S_next (scores
+  // of the following block, already started from the old reference) moves along.
+  auto exps = [&](floatx16 (&S)[QT], bf16x8 (&P)[QT][2], floatx16 (&S_next)[QT], bool have_next) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
       float p[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        p[v] = exp2_fast(S[qt][v]);
-      }
+      for (int v = 0; v < 16; ++v) p[v] = exp2_fast(S[qt][v]);
       float s4[4];  // four independent partial sums
 #pragma unroll
       for (int c = 0; c < 4; ++c) s4[c] = (p[c] + p[4 + c]) + (p[8 + c] + p[12 + c]);
-      l_sum[qt] += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+      float ps = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+      if (__ballot(!(ps <= 256.f)) != 0ull) {  // rare
+        const float mx = row_max(S[qt]);
+        const float delta = mx > 0.f ? mx : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          S[qt][v] -= delta;
+          p[v] = exp2_fast(S[qt][v]);
+          if (have_next) S_next[qt][v] -= delta;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) s4[c] = (p[c] + p[4 + c]) + (p[8 + c] + p[12 + c]);
+        ps = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+        move_reference(qt, delta);
+      }
+      l_sum[qt] += ps;
 #pragma unroll
       for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
@@ -352,21 +385,30 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
   arrive(0);
   if (wave_active) {
     qk(0, s_cur);
-    settle(0, s_cur, true);  // the first block always has a visible key (a prefix token, or the root)
+    mask_block(0, s_cur);
+    // the first block always has a visible key (a prefix token, or the root): its exact maximum
+    // becomes the first reference
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      const float mx = row_max(s_cur[qt]);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_cur[qt][v] -= mx;
+      move_reference(qt, mx);
+    }
   }
   for (int blk = 0; blk + 1 < n_blocks; ++blk) {
     if (blk & 1) arrive((blk + 1) >> 1);  // the next block opens a new tile
     if (wave_active) {
-      qk(blk + 1, s_next);     // matrix pipe: scores of the next block ...
-      exps(s_cur, pb);         // ... vector pipe: exponentials of this one
-      pv(blk, pb);             // matrix pipe: second product of this block ...
-      settle(blk + 1, s_next, false);  // ... vector pipe: masks and maximum of the next one
+      qk(blk + 1, s_next);              // matrix pipe: scores of the next block ...
+      exps(s_cur, pb, s_next, true);    // ... vector pipe: exponentials of this one
+      pv(blk, pb);                      // matrix pipe: second product of this block
+      if (blk + 1 >= n_plain) mask_block(blk + 1, s_next);
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) s_cur[qt] = s_next[qt];
     }
   }
   if (wave_active) {
-    exps(s_cur, pb);
+    exps(s_cur, pb, s_next, false);
     pv(n_blocks - 1, pb);
   }
 
