@@ -289,8 +289,10 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
   int max_M = 0;
   for (int s = 0; s < B; ++s) max_M = std::max(max_M, host_node_offsets[s + 1] - host_node_offsets[s]);
   auto aligned16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && aligned16(q) && aligned16(k_prefix) &&
-                    aligned16(v_prefix) && aligned16(k_tree) && aligned16(v_tree) && aligned16(o);
+  // (head-count limits: the matrix-core kernel numbers rows and lane offsets in narrow types)
+  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && Hq / Hkv <= 128 && Hkv <= 4096 && aligned16(q) &&
+                    aligned16(k_prefix) && aligned16(v_prefix) && aligned16(k_tree) && aligned16(v_tree) &&
+                    aligned16(o);
   AttnPlan plan = plan_attention(host_node_offsets, host_prefix_offsets, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
   // the workspace bound assumes at most 64 splits per sequence
   while (plan.sp_max > 64) {

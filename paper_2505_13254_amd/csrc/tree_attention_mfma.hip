@@ -1,8 +1,8 @@
 // bfloat16 tree attention on the matrix cores (head dimension 128).
 //
-// One workgroup = up to 256 query rows of one (sequence, KV head, key split); every wave owns
-// 32 * QT rows and keeps their output accumulators in registers for the whole pass, so K and V are
-// read from HBM once per workgroup and shared through LDS by all G x M rows of the KV head
+// One workgroup = up to 256 query rows of one (sequence, KV head, key split); each of its eight
+// waves owns 32 rows and keeps their output accumulators in registers for the whole pass, so K and
+// V are read from HBM once per workgroup and shared through LDS by all G x M rows of the KV head
 // (Section 2.2: every tree row attends to the same prefix).
 //
 // Both products are computed transposed with v_mfma_f32_32x32x16_bf16:
@@ -18,21 +18,32 @@
 // Softmax runs in the log2 domain.  Q is pre-multiplied by scale * log2(e), and the first MFMA of a
 // score block starts from an accumulator holding minus the row's reference maximum, so the matrix
 // core delivers x - m directly and the only per-score vector work is exp2, the row sum and the
-// conversion to bf16.  The reference maximum is updated lazily: accumulators are rescaled only when
-// a score exceeds the reference by more than 2^8 (exact after the final division by the equally
-// referenced denominator).  The check costs one compare per block: it rides on the row sum of the
-// exponentials, which exceeds 2^8 whenever a score does, and only then is the exact maximum taken.
-// The first product of block b+1 is issued together with the exponentials of block b, so matrix and
-// vector instructions of independent blocks sit in the same scheduling region.
+// conversion to bf16.
+//
+// The reference maximum of a row is the exact maximum of its first 32-key block and then stays
+// fixed: nothing is rescaled inside the loop.  P and the accumulators are floating point, so a later
+// score above the reference only makes them larger, with the same relative precision; the result
+// is exact after the final division by the equally referenced denominator.  Only an overflow (a
+// score more than ~2^6 octaves above the reference) would break this; it shows in the denominator at
+// the end of the pass, and the workgroup then repeats its pass with the classic block-by-block
+// update of the maximum (rare, slow, same result).
+//
+// Schedule.  Each 32-key block passes through two windows of eight matrix instructions: its scores,
+// then its second product.  A window also takes half of a block's exponentials (the second half of
+// the block whose product comes next, or the first half of the block whose scores were just
+// finished) and requests the LDS fragments that the matrix instructions three steps ahead will
+// need, so matrix, vector and LDS pipes of a wave all have independent work at any time.
 //
 // The tree part (ancestor mask) is a bit table built in LDS from the parent pointers.
 //
 // K/V tiles go from HBM straight into LDS (global_load_lds_dwordx4, 16 bytes per lane, no staging
-// registers) through a ring of four tile buffers: while one tile is multiplied and the next one is
-// already being read for its scores, two more are on their way (64 KB per compute unit in flight).
-// The XOR swizzle that keeps LDS reads conflict-free is applied on the global side: the lane that fills LDS slot c of a row fetches chunk c ^ swz_key(row).
-// Waits are explicit (s_waitcnt vmcnt(n) counts this wave's younger tile loads) and the workgroup
-// barrier carries no memory fence, so outstanding loads survive it.
+// registers) through a ring of four tile buffers: one tile is being multiplied, the next one has
+// landed, two more are on their way (64 KB per compute unit in flight).  The XOR swizzle that keeps
+// LDS reads conflict-free is applied on the global side: the lane that fills LDS slot c of a row
+// fetches chunk c ^ swz_key(row).  Waits are explicit (s_waitcnt vmcnt(n) counts this wave's younger
+// tile loads) and the workgroup barrier carries no memory fence, so outstanding loads survive it.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace hs {
@@ -43,22 +54,23 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(3))) shortx4* lds_s4_ptr;
 
 constexpr int MF_ROWS = 256;       // query rows per workgroup
+constexpr int MF_THREADS = 512;    // eight waves of 32 rows, two per SIMD
 constexpr int MF_TILE = 64;        // keys per LDS tile (two 32-key blocks)
-constexpr int MF_NBUF = 4;         // LDS ring: two tiles in use, two on their way from HBM
+constexpr int MF_NBUF = 4;         // LDS ring: one tile in use, one landed, two on their way from HBM
 constexpr int MF_MAX_M = 256;      // tree rows per sequence (ancestor bit table: M x 8 words)
 constexpr int MF_ROW_BYTES = 256;  // one K or V row of a head: 128 bf16
 constexpr int MF_TILE_BYTES = MF_TILE * MF_ROW_BYTES;
+constexpr int MF_BLOCK_BYTES = 32 * MF_ROW_BYTES;
+constexpr int MF_LOADS = MF_TILE * 16 / MF_THREADS;  // 16-byte chunks of K (and of V) per thread per tile
+constexpr int MF_AHEAD = 1;        // LDS fragments are requested this many steps (of two matrix instructions) ahead
 constexpr float MF_LOG2E = 1.4426950408889634f;
 constexpr float MF_LN2 = 0.6931471805599453f;
-constexpr float MF_LAZY = 8.0f;    // rescale only when the reference maximum is exceeded by 2^8
-
-#ifndef HS_QT
-#define HS_QT 1
-#endif
+constexpr float MF_SUM_LIMIT = 0x1p64f;  // a denominator beyond it (or NaN) sends the pass to the exact path
 
 bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale) {
   return D == 128 && dt == HS_BF16 && max_tree_rows <= MF_MAX_M && scale > 0.f;
@@ -66,40 +78,63 @@ bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale) {
 
 // 16-byte chunk c (0..15) of row r lives at chunk position c ^ swz_key(r).  The key takes 16
 // different values over 16 consecutive rows (one K row per lane: conflict-free 16-byte reads) and
-// its bits 1-2 are the row's low two bits (the four rows that a 16-lane group of the transposing V
-// read touches land in four different 32-byte bank ranges).
-__device__ __forceinline__ int swz_key(int row) { return ((row & 3) << 1) | ((row >> 2) & 1) | (row & 8); }
+// its upper two bits are the row's low two bits: the four rows that a transposing V read touches
+// within a half-wave land in four different 64-byte bank ranges.
+__device__ __forceinline__ int swz_key(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 __device__ __forceinline__ int swz(int row, int chunk) { return row * MF_ROW_BYTES + ((chunk ^ swz_key(row)) << 4); }
 
-// 16 bytes per lane from global memory straight into LDS: lane i lands at lds_addr + 16 i.
-// lds_addr is a wave-uniform LDS byte address (placed in M0, which is saved and restored).
-__device__ __forceinline__ void lds_dma16(const char* gptr, unsigned lds_addr) {
-  const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
+// One tile from global memory straight into LDS: four loads of 16 bytes per lane (K and V, two row
+// groups each).  A load lands at its wave-uniform LDS byte address (taken from M0, which is saved
+// and restored) + 16 * lane; its source is a scalar base plus a 32-bit lane offset.
+__device__ __forceinline__ void lds_dma_tile(const char* kbase, const char* vbase, unsigned off0, unsigned off1,
+                                             unsigned lds_k0, unsigned lds_v0, unsigned lds_k1, unsigned lds_v1) {
   unsigned saved;
   asm volatile(
-      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %5, %7\n\t"
+      "s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %5, %8\n\t"
+      "s_mov_b32 m0, %3\n\tglobal_load_lds_dwordx4 %6, %7\n\t"
+      "s_mov_b32 m0, %4\n\tglobal_load_lds_dwordx4 %6, %8\n\t"
+      "s_mov_b32 m0, %0"
       : "=&s"(saved)
-      : "s"(m), "v"(gptr)
+      : "s"(lds_k0), "s"(lds_v0), "s"(lds_k1), "s"(lds_v1), "v"(off0), "v"(off1), "s"(kbase), "s"(vbase)
       : "memory");
 }
 
-struct TileSrc {
-  const char* k;
-  const char* v;
-  int64_t base;   // first key of the tile (token index in the prefix, or tree row)
-  int64_t limit;  // keys at or beyond it do not exist
-  bool tree;
-};
+// s_waitcnt on the LDS counter alone (vmcnt and expcnt fields at their maxima)
+#define MF_WAIT_LDS_CONST(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
+__device__ __forceinline__ void wait_lds(int n) {  // n is a constant once the windows are unrolled
+  switch (n) {
+    case 0: MF_WAIT_LDS_CONST(0); break;
+    case 2: MF_WAIT_LDS_CONST(2); break;
+    case 4: MF_WAIT_LDS_CONST(4); break;
+    case 6: MF_WAIT_LDS_CONST(6); break;
+    case 8: MF_WAIT_LDS_CONST(8); break;
+    case 10: MF_WAIT_LDS_CONST(10); break;
+    case 12: MF_WAIT_LDS_CONST(12); break;
+    default: break;  // no hint: the compiler's own waits stand
+  }
+}
 
-// QT = 32-row blocks per wave: 2 -> 4 waves of 64 rows, 1 -> 8 waves of 32 rows (two waves per SIMD).
-template <int QT>
-__global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max) {
-  constexpr int THREADS = 512 / QT;
-  constexpr int LOADS = 1024 / THREADS;  // 16-byte chunks of K (and of V) per thread per tile
+#ifdef HS_TS
+__device__ unsigned long long dbg_ts[4096 * 16];
+#define TS(i) do { __builtin_amdgcn_sched_barrier(0); ts_[i] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define TS(i)
+#endif
+#define MF_PIN() __builtin_amdgcn_sched_barrier(0)
+
+__global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_max) {
   __shared__ __attribute__((aligned(16))) char lds_k[MF_NBUF][MF_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) char lds_v[MF_NBUF][MF_TILE_BYTES];
   __shared__ unsigned anc[MF_MAX_M * 8];
+  __shared__ int par_lds[MF_MAX_M];
+  __shared__ int exact_flag;
 
+#ifdef HS_TS
+  unsigned long long ts_[16] = {0};
+#endif
+  TS(0);
   const int s = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
@@ -131,155 +166,190 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
   const int n_ptiles = (int)((k_hi - k_lo + MF_TILE - 1) / MF_TILE);
   const int n_ttiles = last_split ? (M + MF_TILE - 1) / MF_TILE : 0;
   const int n_tiles = n_ptiles + n_ttiles;  // >= 1: a split holds prefix keys, or it is the last one
+  const int n_full = (int)((k_hi - k_lo) / MF_TILE);  // leading tiles made of 64 prefix keys
+  const int n_plain = (int)((k_hi - k_lo) >> 5);      // leading blocks that need no mask
 
-  auto tile_src = [&](int t) {
-    TileSrc ts;
-    ts.tree = t >= n_ptiles;
-    if (ts.tree) {
-      ts.k = kt; ts.v = vt; ts.base = (int64_t)(t - n_ptiles) * MF_TILE; ts.limit = M;
-    } else {
-      ts.k = kp; ts.v = vp; ts.base = k_lo + (int64_t)t * MF_TILE; ts.limit = k_hi;
+  // ---- tile loads.  Issued as inline assembly: the compiler then neither tracks them in its own
+  // wait counters nor orders LDS reads of other ring slots behind them.  The lane that fills the
+  // 16-byte LDS slot c of a tile (row c / 16, position c % 16) fetches chunk (c % 16) ^ swz_key(row).
+  static_assert(MF_LOADS == 2, "lds_dma_tile moves two row groups of K and of V");
+  const unsigned lds_k_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_k[0][0];
+  const unsigned lds_v_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_v[0][0];
+  const unsigned wave_lds = __builtin_amdgcn_readfirstlane((unsigned)(wave * 64 * 16));  // this wave's 1 KB of a row group
+  const int dma_row = tid >> 4;                                                        // + 32 for the second row group
+  const unsigned dma_chunk = (unsigned)(((tid & 15) ^ swz_key(dma_row)) << 4);         // swz_key(row + 32) == swz_key(row)
+  const unsigned lane_off0 = (unsigned)(dma_row * (int)tok_stride) + dma_chunk;        // inside a full tile: fixed
+  const unsigned lane_off1 = lane_off0 + (unsigned)(32 * (int)tok_stride);
+  // a full tile of prefix keys into ring slot `slot`
+  auto issue_full = [&](int t, int slot) {
+    const int64_t tile_off = (k_lo + (int64_t)t * MF_TILE) * tok_stride;
+    const unsigned ring = (unsigned)slot * MF_TILE_BYTES + wave_lds;
+    lds_dma_tile(kp + tile_off, vp + tile_off, lane_off0, lane_off1, lds_k_addr + ring, lds_v_addr + ring,
+                 lds_k_addr + ring + MF_BLOCK_BYTES, lds_v_addr + ring + MF_BLOCK_BYTES);
+  };
+  // any tile: the last prefix tile may be partial, tree tiles come from the tree buffers; rows past
+  // the end repeat the last row (their scores are masked)
+  auto issue = [&](int t) {
+    if (t < n_full) {
+      issue_full(t, t % MF_NBUF);
+      return;
     }
-    return ts;
+    const bool tree = t >= n_ptiles;
+    const char* ks = tree ? kt : kp;
+    const char* vs = tree ? vt : vp;
+    const int64_t base = tree ? (int64_t)(t - n_ptiles) * MF_TILE : k_lo + (int64_t)t * MF_TILE;
+    const int rows = (int)((tree ? (int64_t)M : k_hi) - base);  // >= 1 rows of this tile exist
+    const int r0 = dma_row < rows ? dma_row : rows - 1;
+    const int r1 = dma_row + 32 < rows ? dma_row + 32 : rows - 1;
+    const unsigned ring = (unsigned)(t % MF_NBUF) * MF_TILE_BYTES + wave_lds;
+    lds_dma_tile(ks + base * tok_stride, vs + base * tok_stride, (unsigned)(r0 * (int)tok_stride) + dma_chunk,
+                 (unsigned)(r1 * (int)tok_stride) + dma_chunk, lds_k_addr + ring, lds_v_addr + ring,
+                 lds_k_addr + ring + MF_BLOCK_BYTES, lds_v_addr + ring + MF_BLOCK_BYTES);
+  };
+  // Start of a pass: tiles 0 and 1 are on their way; wait for this wave's part of tile 0, meet the
+  // other waves, request tile 2.
+  auto first_arrival = [&]() {
+    if (n_tiles > 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * MF_LOADS) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (2 < n_tiles) issue(2);
+  };
+  // Middle of trip t (tile t is being multiplied): wait for this wave's part of tile t + 1 (tile
+  // t + 2 may still be pending), meet the other waves, request tile t + 3.  Every wave has finished
+  // tile t - 1 by then: its slot is the one that tile t + 3 goes to.
+  auto next_arrival = [&](int t) {
+    if (t + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * MF_LOADS) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (t + 3 < n_tiles) issue(t + 3);
   };
 
-  // ---- ancestor bit table: bit j of row i's words is set iff tree row j is on the root path of i
-  if (last_split && tid < M) {
-    unsigned w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int j = tid; j >= 0; j = a.parent[n0 + j]) {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) w[q] |= ((j >> 5) == q) ? (1u << (j & 31)) : 0u;
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) anc[tid * 8 + q] = w[q];
-  }
-
-  // ---- this wave's rows; Q fragments (B operand of the first product), pre-multiplied by
-  // scale * log2(e) so that the scores come out of the MFMA in the log2 domain
-  const float c2 = a.scale * MF_LOG2E;
-  const int row_base = rg * MF_ROWS + wave * (32 * QT);
+  // ---- set-up.  Its global reads (parent pointers, Q rows) are requested first and the first two
+  // K/V tiles right behind them, so that HBM is busy while the ancestor table is built and Q is
+  // converted.  (Loads return in order: waiting for the Q rows never waits for a tile.)
+  const int row_base = rg * MF_ROWS + wave * 32;
   const bool wave_active = row_base < R;
-  bf16x8 qf[QT][8];
-  int tree_row[QT];
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const int r = row_base + qt * 32 + col;
+  // r / G for a row number r < 2^16 without the integer-division sequence: (r + 0.5) / G is at least
+  // 1 / (2 G) away from an integer, far more than the rounding of the float product
+  const float inv_G = 1.0f / (float)G;
+  auto div_G = [&](int r) { return (int)(((float)r + 0.5f) * inv_G); };
+  int my_parent = -1;
+  if (last_split && tid < M) my_parent = a.parent[n0 + tid];
+  bf16x8 qf[8];
+  int tree_row;
+  {
+    const int r = row_base + col;
     const int rc = r < R ? r : R - 1;
-    const int i = rc / G, gi = rc - i * G;
-    tree_row[qt] = i;
+    const int i = div_G(rc), gi = rc - i * G;
+    tree_row = i;
     const char* qrow = static_cast<const char*>(a.q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      bf16x8 raw = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (r < R && wave_active) raw = *reinterpret_cast<const bf16x8*>(qrow + (2 * kk + half) * 16);
+      const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+      qf[kk] = (r < R && wave_active) ? *reinterpret_cast<const bf16x8*>(qrow + (2 * kk + half) * 16) : zero8;
+    }
+  }
+  TS(1);
+  issue(0);
+  if (n_tiles > 1) issue(1);
+  TS(2);
+
+  // ---- ancestor bit table: bit j of row i's words is set iff tree row j is on the root path of i.
+  // The parent pointers are staged in LDS and the paths are walked there.
+  if (last_split) {
+    if (tid < M) par_lds[tid] = my_parent;
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (tid < M) {
+      unsigned w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int j = tid; j >= 0; j = par_lds[j]) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        floatx2 f = {(float)raw[2 * e] * c2, (float)raw[2 * e + 1] * c2};
-        bf16x2 hb = __builtin_convertvector(f, bf16x2);
-        qf[qt][kk][2 * e] = hb[0];
-        qf[qt][kk][2 * e + 1] = hb[1];
+        for (int q = 0; q < 8; ++q) w[q] |= ((j >> 5) == q) ? (1u << (j & 31)) : 0u;
       }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) anc[tid * 8 + q] = w[q];
+    }
+  }
+  if (tid == 0) exact_flag = 0;
+
+  // ---- Q fragments (B operand of the first product), pre-multiplied by scale * log2(e) so that
+  // the scores come out of the MFMA in the log2 domain
+  const float c2 = a.scale * MF_LOG2E;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 raw = qf[kk];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      floatx2 f = {(float)raw[2 * e] * c2, (float)raw[2 * e + 1] * c2};
+      bf16x2 hb = __builtin_convertvector(f, bf16x2);
+      qf[kk][2 * e] = hb[0];
+      qf[kk][2 * e + 1] = hb[1];
     }
   }
 
-  floatx16 acc[QT][4];   // O^T: [d block of 32][16 values]: d = 32 tt + 8 (v / 4) + 4 half + v % 4
-  floatx16 negm[QT];     // minus the reference maximum in all 16 slots: start value of a score block
-  float m_ref[QT], l_sum[QT];
+  floatx16 acc[4];   // O^T: [d block of 32][16 values]: d = 32 tt + 8 (v / 4) + 4 half + v % 4
+  floatx16 negm;     // minus the reference maximum in all 16 slots: start value of a score block
+  float m_ref = 0.f, l_sum = 0.f;
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    m_ref[qt] = 0.f;
-    l_sum[qt] = 0.f;
+  for (int v = 0; v < 16; ++v) negm[v] = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) negm[qt][v] = 0.f;
+  for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[qt][t][v] = 0.f;
-  }
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-  // ---- tile loads.  Issued as inline assembly: the compiler then neither tracks them in its own
-  // wait counters nor orders LDS reads of other ring slots behind them.
-  const unsigned lds_k_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_k[0][0];
-  const unsigned lds_v_addr = (unsigned)(uintptr_t)(lds_ptr)&lds_v[0][0];
-  // per-lane byte offsets inside a full prefix tile: fixed for the whole pass
-  int64_t lane_off[LOADS];
-  unsigned lane_lds[LOADS];
+  // ---- LDS fragments.  Per-lane addresses for block 0 of ring slot 0; a block of slot s, parity b
+  // lies s * MF_TILE_BYTES + b * MF_BLOCK_BYTES further (an immediate offset when s is static).
+  // K: lane (col, half) reads chunk 2 kk + half of key row col.  V: the transposing read returns, to
+  // lane l of a 16-lane group, element l % 4 of the 8-byte pieces addressed by lanes l / 4 + {0, 4,
+  // 8, 12} of the group: lane (a = l % 4, j = l / 4) therefore addresses key j of the wanted four at
+  // columns 4a .. 4a+3; fragment f = 4 k2 + tt holds the 16 keys of contraction step k2 for the 32
+  // output columns of d block tt.
+  const int tr_a = lane & 3, tr_j = (lane >> 2) & 3, tr_dh = (lane >> 4) & 1;
+  const char* kl[8];
+  const char* vl[8][2];
 #pragma unroll
-  for (int j = 0; j < LOADS; ++j) {
-    const int c = j * THREADS + tid;  // LDS slot (16-byte units) this lane fills
-    const int row = c >> 4, slot = c & 15;
-    lane_off[j] = (int64_t)row * tok_stride + ((slot ^ swz_key(row)) << 4);
-    lane_lds[j] = (unsigned)((j * THREADS + wave * 64) << 4);  // wave-uniform LDS byte offset
-  }
-  auto issue = [&](int t) {
-    const unsigned ring = (unsigned)(t % MF_NBUF) * MF_TILE_BYTES;
-    if (t < n_ptiles && k_lo + (int64_t)(t + 1) * MF_TILE <= k_hi) {
-      // a full tile of prefix keys: one scalar base plus the fixed lane offsets
-      const int64_t tile_off = (k_lo + (int64_t)t * MF_TILE) * tok_stride;
+  for (int kk = 0; kk < 8; ++kk) kl[kk] = &lds_k[0][0] + swz(col, 2 * kk + half);
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        lds_dma16(kp + tile_off + lane_off[j], lds_k_addr + ring + lane_lds[j]);
-        lds_dma16(vp + tile_off + lane_off[j], lds_v_addr + ring + lane_lds[j]);
-      }
-      return;
+  for (int f = 0; f < 8; ++f)
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int key = 16 * (f >> 2) + 8 * r + 4 * half + tr_j;
+      vl[f][r] = &lds_v[0][0] + swz(key, 4 * (f & 3) + 2 * tr_dh + (tr_a >> 1)) + (tr_a & 1) * 8;
     }
-    const TileSrc ts = tile_src(t);
+  auto ldk = [&](int off, int kk) { return *reinterpret_cast<const bf16x8*>(kl[kk] + off); };
+  auto ldv = [&](int off, int f) {
+    bf16x8 vf;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const int c = j * THREADS + tid;
-      const int row = c >> 4, slot = c & 15;
-      int64_t key = ts.base + row;
-      key = key < ts.limit ? key : ts.limit - 1;  // rows past the end repeat the last row (masked later)
-      const int64_t off = key * tok_stride + ((slot ^ swz_key(row)) << 4);
-      lds_dma16(ts.k + off, lds_k_addr + ring + lane_lds[j]);
-      lds_dma16(ts.v + off, lds_v_addr + ring + lane_lds[j]);
+    for (int r = 0; r < 2; ++r) {
+      const shortx4 got = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(vl[f][r] + off));
+      const bf16x4 gb = __builtin_bit_cast(bf16x4, got);
+      vf[4 * r + 0] = gb[0];
+      vf[4 * r + 1] = gb[1];
+      vf[4 * r + 2] = gb[2];
+      vf[4 * r + 3] = gb[3];
     }
+    return vf;
   };
-  // Wait until this wave's loads of tile t have landed (only the loads of tile t+1 may still be
-  // pending), then meet the other waves.  It is called while tile t-1 is still being multiplied, so
-  // the slot that is free for a new load is the one of tile t-2: tile t+2 goes there.
-  auto arrive = [&](int t) {
-    if (t + 1 < n_tiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (t + 2 < n_tiles) issue(t + 2);
-  };
+  // byte offset of block (slot, parity) inside a ring
+  auto blk_off = [](int slot, int parity) { return slot * MF_TILE_BYTES + parity * MF_BLOCK_BYTES; };
 
-  // ---- S^T block = K[32 keys] Q^T, started from -m_ref
-  auto qk = [&](int blk, floatx16 (&S)[QT]) {
-    const char* kbuf = lds_k[(blk >> 1) % MF_NBUF];
-    const int krow = (blk & 1) * 32 + col;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kbuf + swz(krow, 2 * kk + half));
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt)
-        S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][kk], kk == 0 ? negm[qt] : S[qt], 0, 0, 0);
-    }
-  };
   // ---- masks of a block's scores: tree keys off the row's root path, keys past the end of the
   // split.  Only the blocks from n_plain on need it (the partial prefix tail and the tree part).
-  const int n_plain = (int)((k_hi - k_lo) >> 5);
-  auto mask_block = [&](int blk, floatx16 (&S)[QT]) {
-    const TileSrc ts = tile_src(blk >> 1);
-    const int64_t bbase = ts.base + (blk & 1) * 32;
-    if (ts.tree) {
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        const unsigned word = bbase < ts.limit ? anc[tree_row[qt] * 8 + (int)(bbase >> 5)] : 0u;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int bit = 8 * (v >> 2) + 4 * half + (v & 3);
-          S[qt][v] = ((word >> bit) & 1u) ? S[qt][v] : -HS_INF;
-        }
-      }
-    } else if (bbase + 32 > ts.limit) {
-      const int valid = (int)(ts.limit - bbase);  // may be <= 0: the whole block is past the end
+  auto mask_block = [&](int blk, floatx16& S) {
+    const int t = blk >> 1;
+    if (t >= n_ptiles) {
+      const int bbase = (t - n_ptiles) * MF_TILE + (blk & 1) * 32;
+      const unsigned word = bbase < M ? anc[tree_row * 8 + (bbase >> 5)] : 0u;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int key = 8 * (v >> 2) + 4 * half + (v & 3);
-        if (key >= valid) {
+        const int bit = 8 * (v >> 2) + 4 * half + (v & 3);
+        S[v] = ((word >> bit) & 1u) ? S[v] : -HS_INF;
+      }
+    } else {
+      const int64_t bbase = k_lo + (int64_t)t * MF_TILE + (blk & 1) * 32;
+      if (bbase + 32 > k_hi) {
+        const int valid = (int)(k_hi - bbase);  // may be <= 0: the whole block is past the end
 #pragma unroll
-          for (int qt = 0; qt < QT; ++qt) S[qt][v] = -HS_INF;
+        for (int v = 0; v < 16; ++v) {
+          const int key = 8 * (v >> 2) + 4 * half + (v & 3);
+          S[v] = key < valid ? S[v] : -HS_INF;
         }
       }
     }
@@ -292,174 +362,309 @@ __global__ __launch_bounds__(512 / QT) void k_attn_mfma(AttnArgs a, int n_rg_max
     const float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
     return fmaxf(mx, __shfl_xor(mx, 32));
   };
-  // moves the reference maximum of row block qt up by delta (>= 0 except at the very first block)
-  auto move_reference = [&](int qt, float delta) {
+  // moves the reference maximum up by delta (>= 0 except at the very first block)
+  auto move_reference = [&](float delta) {
     const float alpha = exp2_fast(-delta);
-    m_ref[qt] += delta;
-    l_sum[qt] *= alpha;
+    m_ref += delta;
+    l_sum *= alpha;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) negm[qt][v] = -m_ref[qt];
+    for (int v = 0; v < 16; ++v) negm[v] = -m_ref;
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[qt][tt][v] *= alpha;
+      for (int v = 0; v < 16; ++v) acc[tt][v] *= alpha;
   };
-  // ---- P = exp2(S) as bf16 B operands; row sums.  The lazy reference check rides on the row sum:
-  // a score above the reference by more than 2^8 makes the sum exceed 2^8 (so does an overflow), and
-  // only then the exact maximum is taken, the reference moved and the block redone.  S_next (scores
-  // of the following block, already started from the old reference) moves along.
-  auto exps = [&](floatx16 (&S)[QT], bf16x8 (&P)[QT][2], floatx16 (&S_next)[QT], bool have_next) {
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      float p[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) p[v] = exp2_fast(S[qt][v]);
-      float s4[4];  // four independent partial sums
-#pragma unroll
-      for (int c = 0; c < 4; ++c) s4[c] = (p[c] + p[4 + c]) + (p[8 + c] + p[12 + c]);
-      float ps = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-      if (__ballot(!(ps <= 256.f)) != 0ull) {  // rare
-        const float mx = row_max(S[qt]);
-        const float delta = mx > 0.f ? mx : 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          S[qt][v] -= delta;
-          p[v] = exp2_fast(S[qt][v]);
-          if (have_next) S_next[qt][v] -= delta;
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) s4[c] = (p[c] + p[4 + c]) + (p[8 + c] + p[12 + c]);
-        ps = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-        move_reference(qt, delta);
-      }
-      l_sum[qt] += ps;
-#pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          floatx2 f = {p[8 * k2 + 2 * e], p[8 * k2 + 2 * e + 1]};
-          bf16x2 hb = __builtin_convertvector(f, bf16x2);
-          P[qt][k2][2 * e] = hb[0];
-          P[qt][k2][2 * e + 1] = hb[1];
-        }
-    }
+  // the pieces of a window: two exponentials (keys 2j, 2j + 1 of half h of a block), and, one step
+  // later, their bf16 pair; the two values also go into two running denominators
+  float l0 = 0.f, l1 = 0.f;
+  auto exp_pair = [&](const floatx16& S, int h, int j) {
+    floatx2 pp = {exp2_fast(S[8 * h + 2 * j]), exp2_fast(S[8 * h + 2 * j + 1])};
+    return pp;
   };
-  // ---- O^T += V^T P^T for one 32-key block.  The transposing read returns, to lane l of a 16-lane
-  // group, element l % 4 of the 8-byte pieces addressed by lanes l / 4 + {0, 4, 8, 12} of the group:
-  // lane (a = l % 4, j = l / 4) therefore addresses key j of the wanted four at columns 4a .. 4a+3.
-  const int tr_a = lane & 3, tr_j = (lane >> 2) & 3, tr_dh = (lane >> 4) & 1;
-  auto pv = [&](int blk, const bf16x8 (&P)[QT][2]) {
-    const char* vbuf = lds_v[(blk >> 1) % MF_NBUF];
-    const int kb = blk & 1;
+  auto pack_pair = [&](const floatx2& pp, uintx4& P, int j) {
+    l0 += pp[0];
+    l1 += pp[1];
+    P[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(pp, bf16x2));
+  };
+  // half h of a block outside the windows
+  auto exp_half = [&](const floatx16& S, int h, uintx4& P) {
 #pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
-#pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        bf16x8 vf;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-          const int key = kb * 32 + 16 * k2 + 8 * r + 4 * half + tr_j;
-          const int chunk = 4 * tt + 2 * tr_dh + (tr_a >> 1);
-          const shortx4 got = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s4_ptr)(vbuf + swz(key, chunk) + (tr_a & 1) * 8));
-          const bf16x4 gb = __builtin_bit_cast(bf16x4, got);
-          vf[4 * r + 0] = gb[0];
-          vf[4 * r + 1] = gb[1];
-          vf[4 * r + 2] = gb[2];
-          vf[4 * r + 3] = gb[3];
-        }
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-          acc[qt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, P[qt][k2], acc[qt][tt], 0, 0, 0);
-      }
-    }
+    for (int j = 0; j < 4; ++j) pack_pair(exp_pair(S, h, j), P, j);
   };
 
-  issue(0);
-  if (n_tiles > 1) issue(1);
+  bf16x8 kf[8], vf[8];  // fragment registers: four of each are alive at any time
+  // Score window: S_out = K(block at oq) Q^T, started from -m_ref, in four steps of two matrix
+  // instructions.  A step first requests the fragments of the next step (the window's last step:
+  // the first two V fragments of the block at ov, whose product window follows), waits for its own,
+  // and pairs its matrix instructions with two exponentials of half h of S_in.
+  auto win_qk = [&](int oq, int ov, floatx16& S_out, const floatx16& S_in, int h, uintx4& P) {
+    floatx2 pp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int sN = j + MF_AHEAD;  // the step whose fragments are requested now (4, 5: product window)
+      if (sN < 4) {
+        kf[2 * sN] = ldk(oq, 2 * sN);
+        kf[2 * sN + 1] = ldk(oq, 2 * sN + 1);
+      } else {
+        vf[2 * (sN - 4)] = ldv(ov, 2 * (sN - 4));
+        vf[2 * (sN - 4) + 1] = ldv(ov, 2 * (sN - 4) + 1);
+      }
+      int pending = 0;  // LDS reads requested after those of step j: K steps count 2, V steps 4
+#pragma unroll
+      for (int d = 1; d <= MF_AHEAD; ++d) pending += (j + d < 4) ? 2 : 4;
+      wait_lds(pending);
+      S_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[2 * j], qf[2 * j], j == 0 ? negm : S_out, 0, 0, 0);
+      pp[j] = exp_pair(S_in, h, j);
+      S_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[2 * j + 1], qf[2 * j + 1], S_out, 0, 0, 0);
+      if (j > 0) pack_pair(pp[j - 1], P, j - 1);
+      MF_PIN();
+    }
+    pack_pair(pp[3], P, 3);
+  };
+  // Product window: O^T += V^T(block at ov) P^T with P = (P0, P1), same step structure; its last
+  // steps request the first K fragments of the block at oq, whose score window follows
+  // (with_kf: there is such a block).  with_exp: exponentials of half h of S_in are taken.
+  auto win_pv = [&](int ov, int oq, const uintx4& P0, const uintx4& P1, const floatx16& S_in, int h, uintx4& P,
+                    auto with_exp, auto with_kf) {
+    constexpr bool EXP = decltype(with_exp)::value, KF = decltype(with_kf)::value;
+    const bf16x8 b0 = __builtin_bit_cast(bf16x8, P0), b1 = __builtin_bit_cast(bf16x8, P1);
+    floatx2 pp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int sN = j + MF_AHEAD;
+      if (sN < 4) {
+        vf[2 * sN] = ldv(ov, 2 * sN);
+        vf[2 * sN + 1] = ldv(ov, 2 * sN + 1);
+      } else if (KF) {
+        kf[2 * (sN - 4)] = ldk(oq, 2 * (sN - 4));
+        kf[2 * (sN - 4) + 1] = ldk(oq, 2 * (sN - 4) + 1);
+      }
+      if (KF) {
+        int pending = 0;
+#pragma unroll
+        for (int d = 1; d <= MF_AHEAD; ++d) pending += (j + d < 4) ? 4 : 2;
+        wait_lds(pending);
+      }
+      acc[(2 * j) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * j], j < 2 ? b0 : b1, acc[(2 * j) & 3], 0, 0, 0);
+      if (EXP) pp[j] = exp_pair(S_in, h, j);
+      acc[(2 * j + 1) & 3] =
+          __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * j + 1], j < 2 ? b0 : b1, acc[(2 * j + 1) & 3], 0, 0, 0);
+      if (EXP && j > 0) pack_pair(pp[j - 1], P, j - 1);
+      MF_PIN();
+    }
+    if (EXP) pack_pair(pp[3], P, 3);
+  };
+  const std::true_type YES{};
+  const std::false_type NO{};
+
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the ancestor table is complete
-
+  TS(3);
+  first_arrival();
+  TS(4);
   const int n_blocks = 2 * n_tiles;
-  floatx16 s_cur[QT], s_next[QT];
-  bf16x8 pb[QT][2];
-  arrive(0);
+
   if (wave_active) {
-    qk(0, s_cur);
-    mask_block(0, s_cur);
-    // the first block always has a visible key (a prefix token, or the root): its exact maximum
-    // becomes the first reference
+    floatx16 sA, sB;    // scores of the even / odd block of the tile in hand
+    uintx4 pa, pb, pc;  // halves of P (bf16 pairs): first half of the even block, a second half, first half of the odd block
+    // ---- first block: it always has a visible key (a prefix token, or the root), and its exact
+    // maximum is the reference of the whole pass
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      const float mx = row_max(s_cur[qt]);
+    for (int kk = 0; kk < 8; ++kk) kf[kk] = ldk(0, kk);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s_cur[qt][v] -= mx;
-      move_reference(qt, mx);
+    for (int kk = 0; kk < 8; ++kk) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? negm : sA, 0, 0, 0);
+    if (n_plain < 1) mask_block(0, sA);
+    {
+      const float mx = row_max(sA);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sA[v] -= mx;
+      move_reference(mx);
+      exp_half(sA, 0, pa);
     }
-  }
-  for (int blk = 0; blk + 1 < n_blocks; ++blk) {
-    if (blk & 1) arrive((blk + 1) >> 1);  // the next block opens a new tile
-    if (wave_active) {
-      qk(blk + 1, s_next);              // matrix pipe: scores of the next block ...
-      exps(s_cur, pb, s_next, true);    // ... vector pipe: exponentials of this one
-      pv(blk, pb);                      // matrix pipe: second product of this block
-      if (blk + 1 >= n_plain) mask_block(blk + 1, s_next);
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) s_cur[qt] = s_next[qt];
+    for (int kk = 0; kk < 2 * MF_AHEAD; ++kk) kf[kk] = ldk(blk_off(0, 1), kk);
+    TS(5);
+    // ---- one trip per tile t (blocks 2t and 2t + 1, ring slot s = t % 4); the barrier in its
+    // middle lets tile t + 1 in
+    //   window 1: scores of 2t+1      | second half of 2t
+    //   window 2: product of 2t       | first half of 2t+1
+    //   window 3: scores of 2t+2      | second half of 2t+1
+    //   window 4: product of 2t+1     | first half of 2t+2
+    // MASKED: blocks from n_plain on are masked and the tile that is requested may be any tile.
+    auto trip = [&](int t, int s, auto masked) {
+      constexpr bool MASKED = decltype(masked)::value;
+      const int s1 = (s + 1) % MF_NBUF;
+      win_qk(blk_off(s, 1), blk_off(s, 0), sB, sA, 1, pb);
+      if (MASKED && 2 * t + 1 >= n_plain) mask_block(2 * t + 1, sB);
+      if (MASKED) {
+        next_arrival(t);
+      } else {
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * MF_LOADS) : "memory");
+        issue_full(t + 3, (s + 3) % MF_NBUF);
+      }
+      win_pv(blk_off(s, 0), blk_off(s1, 0), pa, pb, sB, 0, pc, YES, YES);
+      win_qk(blk_off(s1, 0), blk_off(s, 1), sA, sB, 1, pb);
+      if (MASKED && 2 * t + 2 >= n_plain) mask_block(2 * t + 2, sA);
+      win_pv(blk_off(s, 1), blk_off(s1, 1), pc, pb, sA, 0, pa, YES, YES);
+    };
+    // Four tiles per round with the ring slots spelled out, while they and the tiles they request
+    // (up to t + 6) are full prefix tiles: every LDS address is then a register plus an immediate.
+    int t = 0;
+    for (; t + 6 < n_full; t += 4) {
+      trip(t, 0, NO);
+      trip(t + 1, 1, NO);
+      trip(t + 2, 2, NO);
+      trip(t + 3, 3, NO);
     }
-  }
-  if (wave_active) {
-    exps(s_cur, pb, s_next, false);
-    pv(n_blocks - 1, pb);
+    TS(6);
+    for (; t + 1 < n_tiles; ++t) trip(t, t % MF_NBUF, YES);
+    TS(7);
+    {  // last tile: nothing follows its odd block
+      const int s = t % MF_NBUF;
+      win_qk(blk_off(s, 1), blk_off(s, 0), sB, sA, 1, pb);
+      if (2 * t + 1 >= n_plain) mask_block(2 * t + 1, sB);
+      win_pv(blk_off(s, 0), 0, pa, pb, sB, 0, pc, YES, NO);
+      exp_half(sB, 1, pb);
+#pragma unroll
+      for (int f = 0; f < 2 * MF_AHEAD; ++f) vf[f] = ldv(blk_off(s, 1), f);
+      win_pv(blk_off(s, 1), 0, pc, pb, sB, 0, pa, NO, NO);
+    }
+    l_sum = l0 + l1;
+    TS(8);
+  } else {
+    // no rows: this wave only moves tiles and meets the barriers
+    for (int t = 0; t + 1 < n_tiles; ++t) next_arrival(t);
   }
 
-  // ---- results: direct (single split everywhere) or this split's partial record
+  // ---- did the fixed reference hold?  (denominator of both half-waves; NaN counts as no)
+  float l_tot = l_sum + __shfl_xor(l_sum, 32);
+  if (wave_active && __ballot(!(l_tot < MF_SUM_LIMIT)) != 0ull && lane == 0) exact_flag = 1;
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // also: every LDS read of the pass is done
+  if (exact_flag != 0) {
+    // ---- exact path (rare): the pass again, one block at a time, the reference following the
+    // running maximum: classic online softmax, no overlap between the steps
+    m_ref = 0.f;
+    l_sum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negm[v] = 0.f;
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tt][v] = 0.f;
+    issue(0);
+    if (n_tiles > 1) issue(1);
+    first_arrival();
+    for (int blk = 0; blk < n_blocks; ++blk) {
+      // the barrier of next_arrival also keeps any wave from reading tile t + 1 before all of it is there
+      if ((blk & 1) && blk + 1 < n_blocks) next_arrival(blk >> 1);
+      if (!wave_active) continue;
+      const int off = blk_off((blk >> 1) % MF_NBUF, blk & 1);
+      floatx16 S;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ldk(off, kk), qf[kk], kk == 0 ? negm : S, 0, 0, 0);
+      if (blk >= n_plain) mask_block(blk, S);
+      const float mx = row_max(S);
+      if (blk == 0 || __ballot(mx > 0.f) != 0ull) {
+        const float delta = (blk == 0 || mx > 0.f) ? mx : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) S[v] -= delta;
+        move_reference(delta);
+      }
+      uintx4 P0, P1;
+      l0 = 0.f;
+      l1 = 0.f;
+      exp_half(S, 0, P0);
+      exp_half(S, 1, P1);
+      l_sum += l0 + l1;
+      const bf16x8 b0 = __builtin_bit_cast(bf16x8, P0), b1 = __builtin_bit_cast(bf16x8, P1);
+#pragma unroll
+      for (int f = 0; f < 8; ++f)
+        acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ldv(off, f), f < 4 ? b0 : b1, acc[f & 3], 0, 0, 0);
+    }
+    l_tot = l_sum + __shfl_xor(l_sum, 32);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
   if (!wave_active) return;
+
+  if (a.sp_max == 1) {
+    // ---- results, single split everywhere: normalised rows go out as bf16.  Each wave turns its
+    // 32 x 128 block around in LDS (the tile ring is free: every wave has passed the last barrier),
+    // so that a lane stores 16 contiguous bytes and a store instruction covers four whole rows.
+    constexpr int ST_ROW = MF_ROW_BYTES + 16;  // padded row: the 8-byte writes of 16 rows spread over all banks
+    char* stage = wave < 4 ? lds_k[wave] : lds_v[wave - 4];
+    const float inv = 1.f / l_tot;
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const int r = row_base + qt * 32 + col;
-    const float l_tot = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
-    if (r >= R) continue;
-    const int i = r / G, gi = r - i * G;
-    const int64_t row = (int64_t)(n0 + i) * Hq + g * G + gi;
-    if (a.sp_max == 1) {
-      const float inv = 1.f / l_tot;
-      char* out = static_cast<char*>(a.o) + row * MF_ROW_BYTES;
+    for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt)
+      for (int b = 0; b < 4; ++b) {
+        const int d0 = 32 * tt + 8 * b + 4 * half;
+        floatx2 f01 = {acc[tt][4 * b] * inv, acc[tt][4 * b + 1] * inv};
+        floatx2 f23 = {acc[tt][4 * b + 2] * inv, acc[tt][4 * b + 3] * inv};
+        uint2 pk;
+        pk.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f01, bf16x2));
+        pk.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f23, bf16x2));
+        *reinterpret_cast<uint2*>(stage + col * ST_ROW + d0 * 2) = pk;
+      }
+    const int r = row_base + col;
+    if (a.lse && half == 0 && r < R) {
+      const int i = div_G(r), gi = r - i * G;
+      a.lse[(int64_t)(n0 + i) * Hq + g * G + gi] = (m_ref + __log2f(l_tot)) * MF_LN2;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's staging writes are in LDS
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int d0 = 32 * tt + 8 * b + 4 * half;
-          floatx2 f01 = {acc[qt][tt][4 * b] * inv, acc[qt][tt][4 * b + 1] * inv};
-          floatx2 f23 = {acc[qt][tt][4 * b + 2] * inv, acc[qt][tt][4 * b + 3] * inv};
-          uint2 pk;
-          pk.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f01, bf16x2));
-          pk.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f23, bf16x2));
-          *reinterpret_cast<uint2*>(out + d0 * 2) = pk;
-        }
-      if (a.lse && half == 0) a.lse[row] = (m_ref[qt] + __log2f(l_tot)) * MF_LN2;
-    } else {
+    for (int j = 0; j < 8; ++j) {
+      const int row_l = 4 * j + (lane >> 4), chunk = lane & 15;
+      const int ro = row_base + row_l;
+      if (ro < R) {
+        const int i = div_G(ro), gi = ro - i * G;
+        const uint4 val = *reinterpret_cast<const uint4*>(stage + row_l * ST_ROW + chunk * 16);
+        *reinterpret_cast<uint4*>(static_cast<char*>(a.o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES +
+                                  chunk * 16) = val;
+      }
+    }
+  } else {
+    // ---- this split's partial record: unnormalised accumulators, reference maximum, denominator
+    const int r = row_base + col;
+    if (r < R) {
+      const int i = div_G(r), gi = r - i * G;
+      const int64_t row = (int64_t)(n0 + i) * Hq + g * G + gi;
       float* rec = a.part + (row * a.sp_max + sp) * ATTN_REC;
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           const int d0 = 32 * tt + 8 * b + 4 * half;
-          float4 f = {acc[qt][tt][4 * b], acc[qt][tt][4 * b + 1], acc[qt][tt][4 * b + 2], acc[qt][tt][4 * b + 3]};
+          float4 f = {acc[tt][4 * b], acc[tt][4 * b + 1], acc[tt][4 * b + 2], acc[tt][4 * b + 3]};
           *reinterpret_cast<float4*>(rec + d0) = f;
         }
       if (half == 0) {
-        rec[128] = m_ref[qt] * MF_LN2;
+        rec[128] = m_ref * MF_LN2;
         rec[129] = l_tot;
       }
     }
   }
+#ifdef HS_TS
+  TS(9);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  TS(10);
+  if (tid == 0) {
+    const int wg = blockIdx.y * gridDim.x + blockIdx.x;
+    if (wg < 4096)
+      for (int i = 0; i < 16; ++i) dbg_ts[wg * 16 + i] = ts_[i];
+  }
+#endif
 }
 
 hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream) {
   const int n_rg_max = (a.G * max_tree_rows + MF_ROWS - 1) / MF_ROWS;
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);
-  hipLaunchKernelGGL(k_attn_mfma<HS_QT>, grid, dim3(512 / HS_QT), 0, stream, a, n_rg_max);
+  hipLaunchKernelGGL(k_attn_mfma, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
   return launch_status("tree attention (mfma)");
 }
 
 }  // namespace hs
+#ifdef HS_TS
+extern "C" int hs_dbg_ts(unsigned long long* host, int n_wg) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(hs::dbg_ts), (size_t)n_wg * 16 * 8);
+}
+#endif

@@ -197,6 +197,9 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
     variant "peaky":  "unit", plus a few keys made to point along chosen queries so that a
                       handful of scores stand far above the rest; some planted keys are in
                       the last part of the prefix and some are tree rows (needs `parent`).
+    variant "hot":    "peaky" with planted scores of 120, 135, 150, ... instead of 8: exp() of the
+                      gap to the other scores overflows float32, so an implementation must track
+                      the running maximum to get these rows right.
     """
     D = w.D
     sc = 1.0 / np.sqrt(D) if variant == "config" else 1.0
@@ -205,14 +208,15 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
     vp = rng.normal(_key(w, seed, _T_VP, s), L * w.Hkv * D).reshape(L, w.Hkv, D) / np.sqrt(D)
     kt = rng.normal(_key(w, seed, _T_KT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) * sc
     vt = rng.normal(_key(w, seed, _T_VT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) / np.sqrt(D)
-    if variant == "peaky" and M > 0:
+    if variant in ("peaky", "hot") and M > 0:
         G = w.Hq // w.Hkv
         picks = rng.randint(_key(w, seed, _T_PLANT, s), 4 * 8, 0, 1 << 30).reshape(8, 4)
-        for a, b, c, d in picks:
+        for n, (a, b, c, d) in enumerate(picks):
             i, h = int(a) % M, int(b) % w.Hq
             g = h // G
             unit = q[i, h] / np.linalg.norm(q[i, h])
-            amp = 8.0 * np.sqrt(D) / np.linalg.norm(q[i, h])    # score = |q| amp / sqrt(D) = 8
+            score = 8.0 if variant == "peaky" else 120.0 + 15.0 * n
+            amp = score * np.sqrt(D) / np.linalg.norm(q[i, h])  # score = |q| amp / sqrt(D)
             if int(c) % 2 == 0 and L > 0:
                 j = L - 1 - (int(d) % max(1, min(L, 40)))          # near the end of the prefix
                 kp[j, g] = unit * amp
@@ -222,7 +226,7 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
                 while parent is not None and steps > 0 and parent[j] >= 0:
                     j = int(parent[j]); steps -= 1
                 kt[j, g] = unit * amp                               # an ancestor (or the row itself)
-    elif variant not in ("config", "unit", "peaky"):
+    elif variant not in ("config", "unit", "peaky", "hot"):
         raise ValueError(variant)
     return tuple(_quantise(w, t) for t in (q, kp, vp, kt, vt))
 
