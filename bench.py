@@ -112,7 +112,9 @@ def main():
         step.run()
     torch.cuda.synchronize()
     K = args.steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+    # events on the stream the kernels are launched on (torch's current stream); the attention launch
+    # gets a pair of its own, apart from the small copy that hands stage 2's tree to every layer
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(K):
@@ -121,15 +123,30 @@ def main():
         ev[k][1].record()
         step.stage2()
         ev[k][2].record()
-        step.stage3()
+        step.stage3_tree()
         ev[k][3].record()
-        step.stage4()
+        step.stage3()
         ev[k][4].record()
+        step.stage4()
+        ev[k][5].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
-    stage_ms = [float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)])) for i in range(4)]
-    stage_med = [float(np.median([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)])) for i in range(4)]
+    gaps = [[ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)] for i in range(5)]
+    order = (0, 1, 3, 4)                                     # entropy_topk, prune, attention, accept
+    stage_ms = [float(np.mean(gaps[i])) for i in order]
+    stage_med = [float(np.median(gaps[i])) for i in order]
+    tree_copy_ms = float(np.mean(gaps[2]))
+
+    # what a pair of events costs by itself on the busy stream (it is inside every figure above)
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 20)]
+    step.run()
+    for i in range(20):
+        pe[2 * i].record()
+        pe[2 * i + 1].record()
+        step.stage3_tree()
+    torch.cuda.synchronize()
+    event_pair_ms = float(np.median([pe[2 * i].elapsed_time(pe[2 * i + 1]) for i in range(20)]))
 
     # streaming-copy ceiling of this device, for context
     big = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB
@@ -168,7 +185,8 @@ def main():
                    "attention_layers_per_step": layers, "candidate_nodes": h["cand_nodes"],
                    "verified_rows": h["NNp"], "verified_draft_nodes": tokens,
                    "draft_rows_quantified": int(step.t["draft_rows"].shape[0]), "accept": args.accept},
-        "stage_ms": {"entropy_topk": stage_ms[0], "prune": stage_ms[1], "attention": stage_ms[2], "accept": stage_ms[3]},
+        "stage_ms": {"entropy_topk": stage_ms[0], "prune": stage_ms[1], "attention": stage_ms[2], "accept": stage_ms[3],
+                     "tree_to_layers_copy": tree_copy_ms, "empty_event_pair": event_pair_ms},
         "stage_ms_median": {"entropy_topk": stage_med[0], "prune": stage_med[1], "attention": stage_med[2],
                             "accept": stage_med[3]},
         "stage_gbps": {"entropy_topk": step.bytes_stage1() / (stage_ms[0] * 1e-3) / 1e9,

@@ -618,8 +618,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
       if (ro < R) {
         const int i = div_G(ro), gi = ro - i * G;
         const uint4 val = *reinterpret_cast<const uint4*>(stage + row_l * ST_ROW + chunk * 16);
-        *reinterpret_cast<uint4*>(static_cast<char*>(a.o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES +
-                                  chunk * 16) = val;
+        char* dst = static_cast<char*>(a.o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES + chunk * 16;
+        *reinterpret_cast<uint4*>(dst) = val;
       }
     }
   } else {

@@ -116,11 +116,15 @@ class Step:
                                 self.t["d_max"], self.t["theta"], self.t["max_nodes"],
                                 out=self.t["s2_out"], ws=self.t["s2_ws"])
 
-    def stage3(self):
+    def stage3_tree(self):
+        """With several layers: the pruned tree (stage 2's device output) becomes the tree of every
+        layer's batch entry (a small device copy, no host round trip)."""
         t, h = self.t, self.host
         if self.layers > 1:
-            # the pruned tree (stage 2's device output) is the tree of every layer
             t["attn_parent"].view(self.layers, -1).copy_(t["s2_out"]["out_parent"][:h["NNp"]])
+
+    def stage3(self):
+        t, h = self.t, self.host
         return hs.hs_tree_attention(t["q"], t["k_prefix"], t["v_prefix"], t["k_tree"], t["v_tree"],
                                     t["attn_parent"], t["attn_node_offsets"], t["attn_prefix_offsets"],
                                     h["attn_node_offsets"], h["attn_prefix_offsets"], h["scale"],
@@ -137,6 +141,7 @@ class Step:
     def run(self):
         self.stage1()
         self.stage2()
+        self.stage3_tree()
         self.stage3()
         self.stage4()
 
