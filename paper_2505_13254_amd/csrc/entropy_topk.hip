@@ -1,32 +1,36 @@
 // hs_draft_entropy_topk: one streaming pass over float32 logits rows.
 //
 // Computes, per row, the softmax statistics (max, sum of exponentials, entropy numerator) and the
-// K best (logit, index) pairs (Section 4.1, Eq. 1; Section 2.2 Expansion).  A row is cut into
-// slices handled by different workgroups (k_scan_rows); a small second kernel merges the slices of
-// a row and writes the results (k_scan_finalize).  HBM-bound: 4 bytes per logit, read once.
+// K best (logit, index) pairs (Section 4.1, Eq. 1; Section 2.2 Expansion).  HBM-bound: 4 bytes per
+// logit, read once.
 //
-// Top-K selection never sorts the data.  Each wave keeps a running sorted list of its K best
-// pairs; per 4096-element tile it compacts (ballot + popcount, deterministic positions) only the
-// elements that are not worse than a threshold into LDS and re-ranks "list + candidates" by
-// counting, which also sorts them.  The threshold is the list's K-th entry, or, for a wave's first
-// tile, the K-th best of the 64 per-lane maxima (at least K elements are at or above it, so no
-// true Top-K member is ever filtered out).  All decisions compare raw float32 logits under the
-// strict order (value descending, index ascending), so the indices do not depend on how rows are
-// split or reduced.
+// One workgroup of 16 waves scans a row (k_scan_rows), merges its waves' results and writes the
+// outputs.  Only when there are too few rows to fill the chip is a row cut into slices for several
+// workgroups; a small second kernel then merges the slices (k_scan_finalize).
+//
+// Top-K selection never sorts the data.  Each wave keeps its K best pairs as a sorted list in
+// registers, entry l in lane l.  Per tile only the elements that are not worse than the list's K-th
+// entry are looked at (one ballot per register); each of them is broadcast and inserted: the lanes
+// whose entry it beats take their left neighbour's entry (or the new one), a shift by one lane done
+// with a DPP move.  Before a list is full the threshold comes from the first tile: the K-th largest
+// of the 16 waves' maxima (of a wave's 64 lane maxima when K > 16): K elements reach it, so no
+// true Top-K member is ever filtered out, and only about K elements of the whole tile pass it.
+// All decisions compare raw float32 logits under the strict order (value descending, index
+// ascending), so the indices do not depend on how rows are split or reduced.
 #include <limits.h>
 
 #include "hs_common.h"
 
 namespace hs {
 
-constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_THREADS = 1024;
 constexpr int SCAN_WAVES = SCAN_THREADS / 64;
 constexpr int SCAN_VPT = 16;                        // values per thread per tile (4 x float4)
-constexpr int SCAN_TILE = SCAN_THREADS * SCAN_VPT;  // 4096 logits per workgroup tile
-constexpr int CAND_CAP = 64 * SCAN_VPT + HS_MAX_TOPK;  // a wave's whole tile plus its list
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_VPT;  // 16384 logits per workgroup tile
 constexpr int FIN_THREADS = 256;
 constexpr int FIN_CAP = HS_MAX_TOPK * HS_MAX_TOPK;  // candidates the merge can face
 constexpr int MAX_SPLITS = 64;                       // slices per row (one list head per lane)
+constexpr int SCAN_TARGET_WGS = 256;                 // rows are sliced until about one workgroup per compute unit exists
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct ScanPlan {
@@ -35,69 +39,22 @@ struct ScanPlan {
 };
 
 static ScanPlan plan_scan(int R, int V) {
-  int n_tiles = (V + SCAN_TILE - 1) / SCAN_TILE;
-  int want = 2048 / (R > 0 ? R : 1);  // aim at ~8 workgroups per compute unit
-  if (want < 1) want = 1;
+  const int n_tiles = (V + SCAN_TILE - 1) / SCAN_TILE;
+  // few rows: slice them until about one workgroup per compute unit exists (measured best)
+  int want = SCAN_TARGET_WGS / (R > 0 ? R : 1);
   if (want > n_tiles) want = n_tiles;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
-  int tpw = (n_tiles + want - 1) / want;
-  int min_tpw = (n_tiles + MAX_SPLITS - 1) / MAX_SPLITS;
-  if (tpw < min_tpw) tpw = min_tpw;
+  if (want < 1) want = 1;
   ScanPlan p;
-  p.tiles_per_wg = tpw;
-  p.splits = (n_tiles + tpw - 1) / tpw;
+  p.tiles_per_wg = (n_tiles + want - 1) / want;
+  p.splits = (n_tiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
   return p;
 }
 
-// Re-ranks entries [0, n) of (cv, ci) by counting and writes those of rank < K, in order, to (ov, oi).
-// Called by `nthreads` cooperating threads (whole waves) with ids 0..nthreads-1; the caller
-// synchronises around it.  The entries to compare against are held 64 at a time in registers and
-// broadcast lane by lane, so the inner loop has no memory latency in it.
-__device__ __forceinline__ void rank_select(const float* cv, const int* ci, int n, int K, float* ov, int* oi,
-                                            int id, int nthreads) {
-  const int lane = id & 63;
-  for (int base = 0; base < n; base += nthreads) {  // uniform trip count
-    const int a = base + id;
-    float av = -HS_INF;
-    int ai = INT_MAX;
-    if (a < n) {
-      av = cv[a];
-      ai = ci[a];
-    }
-    int r = 0;
-    for (int c0 = 0; c0 < n; c0 += 64) {
-      float bv = -HS_INF;
-      int bi = INT_MAX;
-      if (c0 + lane < n) {
-        bv = cv[c0 + lane];
-        bi = ci[c0 + lane];
-      }
-      const int m = (n - c0) < 64 ? (n - c0) : 64;
-      for (int j = 0; j < m; ++j) {
-        const float xv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), j));
-        const int xi = __builtin_amdgcn_readlane(bi, j);
-        r += better(xv, xi, av, ai) ? 1 : 0;
-      }
-    }
-    if (a < n && r < K) {
-      ov[r] = av;
-      oi[r] = ai;
-    }
-  }
-}
-
-// Orders this wave's LDS traffic: what lanes wrote before is visible to all lanes after.
-__device__ __forceinline__ void wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Rank of this lane's pair among the 64 lanes' pairs (number of lanes holding a better pair).
-__device__ __forceinline__ int wave_rank(float v, int i) {
+// Rank of this lane's pair among the pairs of lanes 0 .. n-1 (number of them holding a better pair).
+__device__ __forceinline__ int wave_rank(float v, int i, int n) {
   int r = 0;
-#pragma unroll
-  for (int l = 0; l < 64; ++l) {
+  for (int l = 0; l < n; ++l) {
     float ov = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
     int oi = __builtin_amdgcn_readlane(i, l);
     r += better(ov, oi, v, i) ? 1 : 0;
@@ -105,32 +62,207 @@ __device__ __forceinline__ int wave_rank(float v, int i) {
   return r;
 }
 
+// The value of the lane to the left (lane 0 receives 0): a DPP move shifted by one lane across the wave.
+__device__ __forceinline__ int from_left(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x138, 0xf, 0xf, true); }
+
+// Inserts the wave-uniform pair (xv, xi) into the sorted list held one entry per lane.
+__device__ __forceinline__ void list_insert(float xv, int xi, float& lv, int& li) {
+  const bool beats = better(xv, xi, lv, li);  // false ... false true ... true along the lanes
+  const int left_beaten = from_left(beats ? 1 : 0);
+  const float left_v = __builtin_bit_cast(float, from_left(__builtin_bit_cast(int, lv)));
+  const int left_i = from_left(li);
+  lv = beats ? (left_beaten ? left_v : xv) : lv;
+  li = beats ? (left_beaten ? left_i : xi) : li;
+}
+
+// Statistics of a wave's 64 lanes in one: the common maximum first, then plain sums of the lanes'
+// terms rescaled to it.  The lowest lane that holds the maximum keeps its own maximum's unit out of
+// s1 (as each lane did for itself); for every other lane that unit is an ordinary term.
+__device__ __forceinline__ Stats stats_wave_sum(Stats a, float inv_t) {
+  const float m = wave_max(a.m);
+  if (m == -HS_INF) return stats_empty();
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((long long)__ballot(a.m == m)) - 1;
+  float cs = 0.f, ct = 0.f;
+  if (a.m != -HS_INF) {
+    const float d = (a.m - m) * inv_t;  // <= 0
+    const float e = exp2_fast(d * 1.4426950408889634f);
+    const float w = 1.f + a.s1;
+    cs = lane == leader ? a.s1 : e * w;
+    ct = e * (a.t + d * w);
+  }
+  return Stats{m, wave_sum(cs), wave_sum(ct)};
+}
+
+// Scratch of the merges (shared memory).
+struct MergeScratch {
+  float cv[FIN_CAP];  // candidates
+  int ci[FIN_CAP];
+  int rank[FIN_CAP];
+  float ov[HS_MAX_TOPK];  // the K best of them, in order
+  int oi[HS_MAX_TOPK];
+  int cnt;
+  float thr_v;
+  int thr_i;
+  Stats total;
+};
+
+// Ranks the candidates sm.cv/ci[0, n) by counting (the order is strict: ranks are a permutation) and
+// leaves those of rank < K, in order, in sm.ov / sm.oi.  With fewer candidates than threads a
+// candidate's opponents are shared out among P threads, which add up their counts in LDS.
+// Called by all `nthreads` threads (a power of two); sm.rank[0, n) must be zero on entry (a barrier
+// before the call); ends with a barrier.
+__device__ __forceinline__ void rank_candidates(MergeScratch& sm, int n, int K, int tid, int nthreads) {
+  int shift = 0;  // P = 2^shift threads per candidate
+  while (n > 0 && (n << (shift + 1)) <= nthreads) ++shift;
+  const int P = 1 << shift;
+  const int chunk = (n + P - 1) >> shift;
+  for (int base = 0; base < n; base += nthreads) {  // one trip unless n > nthreads
+    const int a = base + (tid >> shift), part = tid & (P - 1);
+    if (a < n) {
+      const float av = sm.cv[a];
+      const int ai = sm.ci[a];
+      const int b0 = part * chunk, b1 = (b0 + chunk < n) ? b0 + chunk : n;
+      int r = 0;
+      for (int b = b0; b < b1; ++b) r += better(sm.cv[b], sm.ci[b], av, ai) ? 1 : 0;
+      if (P > 1) atomicAdd(&sm.rank[a], r);
+      else sm.rank[a] = r;
+    }
+  }
+  __syncthreads();
+  for (int a = tid; a < n; a += nthreads) {
+    const int r = sm.rank[a];
+    if (r < K) {
+      sm.ov[r] = sm.cv[a];
+      sm.oi[r] = sm.ci[a];
+    }
+  }
+  __syncthreads();
+}
+
+// Merges S <= 64 slices of a row: statistics st[s] (m, s1, t) and sorted K-lists pv/pi[s * K + k].
+// Leaves the row's statistics in sm.total and its K best pairs, in order, in sm.ov / sm.oi.
+// Called by all `nthreads` threads of the workgroup (tid 0..nthreads-1); ends with a barrier.
+__device__ __forceinline__ void merge_slices(const float4* st, const float* pv, const int* pi, int S, int K,
+                                             float inv_t, MergeScratch& sm, int tid, int nthreads) {
+  const int lane = tid & 63;
+  for (int e = tid; e < S * K; e += nthreads) sm.rank[e] = 0;
+  if (tid < 64) {
+    Stats a = stats_empty();
+    float hv = -HS_INF;
+    int hi = INT_MAX;
+    if (lane < S) {
+      const float4 f = st[lane];
+      a = Stats{f.x, f.y, f.z};
+      hv = pv[lane * K];
+      hi = pi[lane * K];
+    }
+    a = stats_wave_sum(a, inv_t);
+    // threshold: the K-th best list head when there are at least K lists, else "everything passes"
+    float tv = -HS_INF;
+    int ti = INT_MAX;
+    if (S >= K) {
+      int r = wave_rank(hv, hi, S);
+      unsigned long long who = __ballot(r == K - 1 && lane < S);
+      if (who != 0ull) {
+        int src = __ffsll((long long)who) - 1;
+        tv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hv), src));
+        ti = __builtin_amdgcn_readlane(hi, src);
+      }
+    }
+    if (lane == 0) {
+      sm.total = a;
+      sm.thr_v = tv;
+      sm.thr_i = ti;
+      sm.cnt = 0;
+    }
+  }
+  __syncthreads();
+  {
+    const float tv = sm.thr_v;
+    const int ti = sm.thr_i;
+    for (int e = tid; e < S * K; e += nthreads) {
+      float v = pv[e];
+      int i = pi[e];
+      if (i != INT_MAX && !better(tv, ti, v, i)) {  // (INT_MAX: an unused list entry)
+        int pos = atomicAdd(&sm.cnt, 1);  // order of arrival does not matter: ranks are computed below
+        sm.cv[pos] = v;                   // (at most S * K <= FIN_CAP entries)
+        sm.ci[pos] = i;
+      }
+    }
+  }
+  __syncthreads();
+  rank_candidates(sm, sm.cnt, K, tid, nthreads);
+}
+
+// Writes a row's results from its merged statistics and Top-K list (first wave of the workgroup).
+__device__ __forceinline__ void write_row(const MergeScratch& sm, int64_t row, int K, float inv_t,
+                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_logp,
+                                          float* __restrict__ ent_topk, float* __restrict__ ent_full,
+                                          float* __restrict__ lse, int tid) {
+  if (tid >= 64) return;
+  const int lane = tid;
+  const float m = sm.total.m, s1 = sm.total.s1, t = sm.total.t;
+  const float l1p = log1pf(s1);
+  if (lane < K) {
+    topk_idx[row * K + lane] = sm.oi[lane];
+    topk_logp[row * K + lane] = (sm.ov[lane] - m) * inv_t - l1p;
+  }
+  // Top-K probabilities renormalised over the K: weights relative to the best one (lane = entry);
+  // entropy = ln(1 + sum w) - sum(w a) / (1 + sum w), every term of one sign
+  float w = 0.f, wa = 0.f;
+  if (lane >= 1 && lane < K) {
+    const float a = (sm.ov[lane] - sm.ov[0]) * inv_t;
+    if (a > -100.f) {
+      w = expf(a);
+      wa = w * a;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    w += __shfl_xor(w, off);
+    wa += __shfl_xor(wa, off);
+  }
+  if (lane == 0) {
+    ent_topk[row] = log1pf(w) - wa / (1.f + w);
+    if (ent_full) ent_full[row] = l1p - t / (1.f + s1);
+    if (lse) lse[row] = m * inv_t + l1p;
+  }
+}
+
+// grid (S, R): slice `blockIdx.x` of row `blockIdx.y`.  S == 1: the outputs are written here;
+// S > 1: the slice's statistics and K-list go to part_* for k_scan_finalize.
 template <bool VEC>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restrict__ logits, int64_t row_stride,
                                                             int V, int K, float inv_t, int tiles_per_wg,
                                                             float4* __restrict__ part_stats,
-                                                            float* __restrict__ part_val, int* __restrict__ part_idx) {
-  __shared__ float cv[SCAN_WAVES][CAND_CAP];
-  __shared__ int ci[SCAN_WAVES][CAND_CAP];
-  __shared__ float lv[2][SCAN_WAVES][HS_MAX_TOPK];
-  __shared__ int li[2][SCAN_WAVES][HS_MAX_TOPK];
-  __shared__ Stats wstats[SCAN_WAVES];
+                                                            float* __restrict__ part_val, int* __restrict__ part_idx,
+                                                            int32_t* __restrict__ topk_idx,
+                                                            float* __restrict__ topk_logp,
+                                                            float* __restrict__ ent_topk,
+                                                            float* __restrict__ ent_full, float* __restrict__ lse) {
+  __shared__ float4 wave_st[SCAN_WAVES];
+  __shared__ float wave_maxima[SCAN_WAVES];
+  __shared__ MergeScratch sm;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x, S = gridDim.x, row = blockIdx.y;
   const float* __restrict__ x = logits + (int64_t)row * row_stride;
 
-  // the list starts as K distinct "worse than anything" entries
-  int cur = 0;
-  if (lane < K) {
-    lv[0][wave][lane] = -HS_INF;
-    li[0][wave][lane] = INT_MAX - lane;
-  }
+  // this wave's K best pairs so far, best first, entry l in lane l; the rest holds a pair that
+  // loses against every real one
+  float lv = -HS_INF;
+  int li = INT_MAX;
   // statistics are kept in the log2 domain while scanning: y = (x - m) * c, c = log2(e) / T
   const float c = inv_t * LOG2E;
   float m = -HS_INF, s1 = 0.f, t2 = 0.f;
-  bool first = true;
-  wave_sync();
+  float thr = -HS_INF;
+  if (tid == 0) sm.cnt = 0;
+  if (tid < HS_MAX_TOPK) {  // a slice with fewer than K elements leaves the rest of its list unused
+    sm.ov[tid] = -HS_INF;
+    sm.oi[tid] = INT_MAX;
+  }
+  __syncthreads();
 
   auto load_tile = [&](int tile, float (&v)[SCAN_VPT]) {
     const int tbase = (split * tiles_per_wg + tile) * SCAN_TILE;
@@ -188,107 +320,86 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
       }
     }
 
-    // ---- threshold: the list's K-th entry, or for the first tile the K-th best of the lane maxima
-    // (of the maxima of groups of four lanes when K <= 16: a quarter of the comparisons)
-    float tv;
-    int ti;
-    if (first) {
-      float bv = -HS_INF;
-      int bi = INT_MAX;
-#pragma unroll
-      for (int jj = 0; jj < SCAN_VPT; ++jj) {
-        int idx = HS_IDX(jj);
-        if (better(v[jj], idx, bv, bi)) {
-          bv = v[jj];
-          bi = idx;
-        }
-      }
-      int r;
-      if (K <= 16) {
-#pragma unroll
-        for (int off = 1; off <= 2; off <<= 1) {
-          const float ov = __shfl_xor(bv, off);
-          const int oi = __shfl_xor(bi, off);
-          if (better(ov, oi, bv, bi)) {
-            bv = ov;
-            bi = oi;
-          }
-        }
-        r = 0;
-#pragma unroll
-        for (int l = 0; l < 64; l += 4) {
-          const float ov = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), l));
-          const int oi = __builtin_amdgcn_readlane(bi, l);
-          r += better(ov, oi, bv, bi) ? 1 : 0;
-        }
+    // ---- threshold (a value): no element below it can be among the row's K best.  First tile:
+    // the K-th largest of the 16 waves' maxima (K <= 16; K elements of the tile reach it), or of
+    // this wave's 64 lane maxima; afterwards also the wave's own K-th entry once its list is full.
+    if (tile == 0) {
+      if (K <= SCAN_WAVES) {
+        const float wm = wave_max(tm);
+        if (lane == 0) wave_maxima[wave] = wm;
+        __syncthreads();
+        const float mine = lane < SCAN_WAVES ? wave_maxima[lane] : -HS_INF;
+        const int r = wave_rank(mine, lane, SCAN_WAVES);
+        const unsigned long long who = __ballot(r == K - 1 && lane < SCAN_WAVES);
+        thr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine), __ffsll((long long)who) - 1));
       } else {
-        r = wave_rank(bv, bi);
+        const int r = wave_rank(tm, lane, 64);
+        const unsigned long long who = __ballot(r == K - 1);
+        thr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, tm), __ffsll((long long)who) - 1));
       }
-      unsigned long long who = __ballot(r == K - 1);
-      int src = __ffsll((long long)who) - 1;  // never empty: the order is strict, ranks are a permutation
-      tv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), src));
-      ti = __builtin_amdgcn_readlane(bi, src);
-      first = false;
     } else {
-      tv = lv[cur][wave][K - 1];
-      ti = li[cur][wave][K - 1];
+      thr = fmaxf(thr, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lv), K - 1)));
     }
 
-    // ---- compact the elements that are not worse than the threshold (skipped when no lane's
-    // maximum reaches it), then re-rank list + candidates
-    if (__ballot(tm >= tv) != 0ull) {
-      int cnt = 0;
-      const unsigned long long lt = (1ull << lane) - 1ull;
+    // ---- insert the elements that reach the threshold (skipped when no lane's maximum does)
+    if (__ballot(tm >= thr) != 0ull) {
 #pragma unroll
       for (int jj = 0; jj < SCAN_VPT; ++jj) {
-        int idx = HS_IDX(jj);
-        bool f = !better(tv, ti, v[jj], idx);
-        unsigned long long mask = __ballot(f);
-        if (f) {
-          int pos = cnt + __popcll(mask & lt);
-          cv[wave][pos] = v[jj];
-          ci[wave][pos] = idx;
+        unsigned long long todo = __ballot(v[jj] >= thr);
+        if (todo != 0ull) {
+          const int idx = HS_IDX(jj);
+          do {
+            const int src = __ffsll((long long)todo) - 1;
+            todo &= todo - 1ull;
+            const float xv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v[jj]), src));
+            const int xi = __builtin_amdgcn_readlane(idx, src);
+            list_insert(xv, xi, lv, li);
+          } while (todo != 0ull);
+          thr = fmaxf(thr, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lv), K - 1)));
         }
-        cnt += __popcll(mask);
       }
-      if (lane < K) {
-        cv[wave][cnt + lane] = lv[cur][wave][lane];
-        ci[wave][cnt + lane] = li[cur][wave][lane];
-      }
-      wave_sync();
-      rank_select(cv[wave], ci[wave], cnt + K, K, lv[cur ^ 1][wave], li[cur ^ 1][wave], lane, 64);
-      cur ^= 1;
-      wave_sync();
     }
 #undef HS_IDX
 #pragma unroll
     for (int jj = 0; jj < SCAN_VPT; ++jj) v[jj] = vn[jj];
   }
-  Stats st{m, s1, t2 * 0.6931471805599453f};  // back to natural-log units
-  // waves flip their list buffers independently (tiles without candidates are skipped per wave):
-  // bring every wave's final list to buffer 0 before the lists are merged
-  if (cur == 1 && lane < K) {
-    lv[0][wave][lane] = lv[1][wave][lane];
-    li[0][wave][lane] = li[1][wave][lane];
-  }
 
-  // ---- merge the four waves' lists and statistics, write this slice's partial result
-  st = stats_wave_reduce(st, inv_t);
-  if (lane == 0) wstats[wave] = st;
-  __syncthreads();
-  float* mv = &cv[1][0];  // scratch for the union of the four lists (4K <= 256 entries)
-  int* mi = &ci[1][0];
-  if (tid < SCAN_WAVES * K) {
-    int w = tid / K, k = tid - w * K;
-    mv[tid] = lv[0][w][k];
-    mi[tid] = li[0][w][k];
+  // ---- the waves' statistics and the real entries of their lists meet in LDS
+  Stats st{m, s1, t2 * 0.6931471805599453f};  // back to natural-log units
+  st = stats_wave_sum(st, inv_t);
+  if (lane == 0) wave_st[wave] = make_float4(st.m, st.s1, st.t, 0.f);
+  {
+    const bool real = lane < K && li != INT_MAX;  // a list's real entries come first
+    const int n_w = __popcll(__ballot(real));
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&sm.cnt, n_w);  // (zeroed at the start, a barrier ago)
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (real) {
+      sm.cv[base + lane] = lv;
+      sm.ci[base + lane] = li;
+      sm.rank[base + lane] = 0;
+    }
   }
   __syncthreads();
-  const int64_t pbase = ((int64_t)row * S + split) * K;
-  rank_select(mv, mi, SCAN_WAVES * K, K, part_val + pbase, part_idx + pbase, tid, SCAN_THREADS);
-  if (tid == 0) {
-    Stats a = stats_merge(stats_merge(wstats[0], wstats[1], inv_t), stats_merge(wstats[2], wstats[3], inv_t), inv_t);
-    part_stats[(int64_t)row * S + split] = make_float4(a.m, a.s1, a.t, 0.f);
+  if (tid < 64) {
+    Stats a = stats_empty();
+    if (lane < SCAN_WAVES) {
+      const float4 f = wave_st[lane];
+      a = Stats{f.x, f.y, f.z};
+    }
+    a = stats_wave_sum(a, inv_t);
+    if (lane == 0) sm.total = a;
+  }
+  rank_candidates(sm, sm.cnt, K, tid, SCAN_THREADS);  // (its first barrier also publishes sm.total)
+  if (S == 1) {
+    write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
+  } else {
+    const int64_t slot = (int64_t)row * S + split;
+    if (tid < K) {
+      part_val[slot * K + tid] = sm.ov[tid];
+      part_idx[slot * K + tid] = sm.oi[tid];
+    }
+    if (tid == 0) part_stats[slot] = make_float4(sm.total.m, sm.total.s1, sm.total.t, 0.f);
   }
 }
 
@@ -300,99 +411,11 @@ __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __r
                                                                float* __restrict__ ent_topk,
                                                                float* __restrict__ ent_full,
                                                                float* __restrict__ lse) {
-  __shared__ float cv[FIN_CAP];
-  __shared__ int ci[FIN_CAP];
-  __shared__ float ov[HS_MAX_TOPK];
-  __shared__ int oi[HS_MAX_TOPK];
-  __shared__ int cnt;
-  __shared__ float thr_v;
-  __shared__ int thr_i;
-  __shared__ Stats total;
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int row = blockIdx.x;
-  const float* pv = part_val + (int64_t)row * S * K;
-  const int* pi = part_idx + (int64_t)row * S * K;
-
-  if (tid < 64) {
-    Stats a = stats_empty();
-    float hv = -HS_INF;
-    int hi = INT_MAX;
-    if (lane < S) {
-      float4 f = part_stats[(int64_t)row * S + lane];
-      a = Stats{f.x, f.y, f.z};
-      hv = pv[lane * K];
-      hi = pi[lane * K];
-    }
-    a = stats_wave_reduce(a, inv_t);
-    // threshold: the K-th best list head when there are at least K lists, else "everything passes"
-    float tv = -HS_INF;
-    int ti = INT_MAX;
-    if (S >= K) {
-      int r = wave_rank(hv, hi);
-      unsigned long long who = __ballot(r == K - 1 && lane < S);
-      if (who != 0ull) {
-        int src = __ffsll((long long)who) - 1;
-        tv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hv), src));
-        ti = __builtin_amdgcn_readlane(hi, src);
-      }
-    }
-    if (lane == 0) {
-      total = a;
-      thr_v = tv;
-      thr_i = ti;
-      cnt = 0;
-    }
-  }
-  __syncthreads();
-  {
-    const float tv = thr_v;
-    const int ti = thr_i;
-    for (int e = tid; e < S * K; e += FIN_THREADS) {
-      float v = pv[e];
-      int i = pi[e];
-      if (!better(tv, ti, v, i)) {
-        int pos = atomicAdd(&cnt, 1);  // order of arrival does not matter: ranks are recomputed below
-        if (pos < FIN_CAP) {
-          cv[pos] = v;
-          ci[pos] = i;
-        }
-      }
-    }
-  }
-  __syncthreads();
-  const int n = cnt < FIN_CAP ? cnt : FIN_CAP;
-  rank_select(cv, ci, n, K, ov, oi, tid, FIN_THREADS);
-  __syncthreads();
-
-  const float m = total.m, s1 = total.s1, t = total.t;
-  const float l1p = log1pf(s1);
-  if (tid < K) {
-    topk_idx[(int64_t)row * K + tid] = oi[tid];
-    topk_logp[(int64_t)row * K + tid] = (ov[tid] - m) * inv_t - l1p;
-  }
-  if (tid < 64) {
-    // Top-K probabilities renormalised over the K: weights relative to the best one (lane = entry);
-    // entropy = ln(1 + sum w) - sum(w a) / (1 + sum w), every term of one sign
-    float w = 0.f, wa = 0.f;
-    if (lane >= 1 && lane < K) {
-      const float a = (ov[lane] - ov[0]) * inv_t;
-      if (a > -100.f) {
-        w = expf(a);
-        wa = w * a;
-      }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      w += __shfl_xor(w, off);
-      wa += __shfl_xor(wa, off);
-    }
-    if (lane == 0) {
-      ent_topk[row] = log1pf(w) - wa / (1.f + w);
-      if (ent_full) ent_full[row] = l1p - t / (1.f + s1);
-      if (lse) lse[row] = m * inv_t + l1p;
-    }
-  }
+  __shared__ MergeScratch sm;
+  const int tid = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  merge_slices(part_stats + row * S, part_val + row * S * K, part_idx + row * S * K, S, K, inv_t, sm, tid, FIN_THREADS);
+  write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
 }
 
 size_t row_topk_workspace(int R, int V, int K) {
@@ -416,12 +439,12 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   dim3 grid(p.splits, R);
   if (vec)
     hipLaunchKernelGGL(k_scan_rows<true>, grid, dim3(SCAN_THREADS), 0, stream, logits, row_stride, V, K, inv_t,
-                       p.tiles_per_wg, part_stats, part_val, part_idx);
+                       p.tiles_per_wg, part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse);
   else
     hipLaunchKernelGGL(k_scan_rows<false>, grid, dim3(SCAN_THREADS), 0, stream, logits, row_stride, V, K, inv_t,
-                       p.tiles_per_wg, part_stats, part_val, part_idx);
+                       p.tiles_per_wg, part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse);
   hs_status st = launch_status("row scan");
-  if (st != HS_OK) return st;
+  if (st != HS_OK || p.splits == 1) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,
                      p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse);
   return launch_status("row scan merge");

@@ -81,6 +81,31 @@ __device__ __forceinline__ Stats stats_merge(Stats a, Stats b, float inv_t) {
   return Stats{a.m, a.s1 + e * w, a.t + e * (b.t + d * w)};
 }
 
+// Reductions over the 64 lanes of a wave with DPP moves (no LDS traffic): partial results travel
+// right inside each row of 16 lanes, then from row to row; lane 63 ends up with the total, which
+// is broadcast.  `idle` is what a lane without a source takes (the identity of the operation).
+template <typename Op>
+__device__ __forceinline__ float wave_reduce_dpp(float x, float idle, Op op) {
+  const int id = __builtin_bit_cast(int, idle);
+#define HS_DPP_STEP(ctrl, rows, banks)                                                                        \
+  x = op(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(id, __builtin_bit_cast(int, x), ctrl, rows, \
+                                                                  banks, false)))
+  HS_DPP_STEP(0x111, 0xf, 0xf);  // row_shr:1
+  HS_DPP_STEP(0x112, 0xf, 0xf);  // row_shr:2
+  HS_DPP_STEP(0x114, 0xf, 0xe);  // row_shr:4
+  HS_DPP_STEP(0x118, 0xf, 0xc);  // row_shr:8
+  HS_DPP_STEP(0x142, 0xa, 0xf);  // row_bcast:15
+  HS_DPP_STEP(0x143, 0xc, 0xf);  // row_bcast:31
+#undef HS_DPP_STEP
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  return wave_reduce_dpp(x, -HS_INF, [](float a, float b) { return fmaxf(a, b); });
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  return wave_reduce_dpp(x, 0.f, [](float a, float b) { return a + b; });
+}
+
 __device__ __forceinline__ Stats stats_shfl_xor(Stats a, int mask) {
   return Stats{__shfl_xor(a.m, mask), __shfl_xor(a.s1, mask), __shfl_xor(a.t, mask)};
 }
