@@ -99,6 +99,18 @@ __device__ __forceinline__ float wave_reduce_dpp(float x, float idle, Op op) {
 #undef HS_DPP_STEP
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
+// Inclusive prefix sums over the lanes of a wave, same DPP steps: lane l receives x_0 + ... + x_l.
+__device__ __forceinline__ int wave_prefix_sum(int x) {
+#define HS_DPP_STEP(ctrl, rows, banks) x += __builtin_amdgcn_update_dpp(0, x, ctrl, rows, banks, false)
+  HS_DPP_STEP(0x111, 0xf, 0xf);  // row_shr:1
+  HS_DPP_STEP(0x112, 0xf, 0xf);  // row_shr:2
+  HS_DPP_STEP(0x114, 0xf, 0xe);  // row_shr:4
+  HS_DPP_STEP(0x118, 0xf, 0xc);  // row_shr:8
+  HS_DPP_STEP(0x142, 0xa, 0xf);  // row_bcast:15
+  HS_DPP_STEP(0x143, 0xc, 0xf);  // row_bcast:31
+#undef HS_DPP_STEP
+  return x;
+}
 __device__ __forceinline__ float wave_max(float x) {
   return wave_reduce_dpp(x, -HS_INF, [](float a, float b) { return fmaxf(a, b); });
 }

@@ -40,8 +40,10 @@ __device__ __forceinline__ int block_reduce_sum(int v, int* red) {
 }
 
 // (value, index) as one 45-bit key, index < 8192: larger key = better (larger value, then lower
-// index); never 0.
+// index); never 0.  The budget-th best key is found digit by digit, 6 bits at a time.
 constexpr int KEY_BITS = 45;
+constexpr int DIGIT_BITS = 6;
+constexpr int N_DIGITS = (KEY_BITS + DIGIT_BITS - 1) / DIGIT_BITS;  // 8
 __device__ __forceinline__ unsigned long long order_key(float v, int i) {
   unsigned u = __builtin_bit_cast(unsigned, v);
   u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;  // monotone map of float order onto unsigned order
@@ -52,11 +54,12 @@ __device__ __forceinline__ unsigned long long order_key(float v, int i) {
 // that each copy is compiled for its own address space.
 template <typename IP, typename FP>
 __device__ __forceinline__ void prune_sequence(
-    IP par, IP dep, FP sum, IP ok, IP nxt, unsigned long long* keys, int* bit_count, int* red, int* chunk_sum, int n,
+    IP par, IP dep, FP sum, IP ok, IP nxt, unsigned long long* keys, int* digit_hist, int* red, int* chunk_sum, int n,
     int o,
     bool copy_out, FP lc, int dcap, float th, int budget, int32_t* __restrict__ depth,
     float* __restrict__ cumlogp, uint8_t* __restrict__ keep, int32_t* __restrict__ ws_pos,
-    int32_t* __restrict__ ws_count, int s) {
+    int32_t* __restrict__ ws_count, int s, bool emit, int32_t* __restrict__ out_offsets,
+    int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent) {
   const int tid = threadIdx.x, lane = tid & 63;
   // depth: walk to the root
   int my_max = 0;
@@ -91,23 +94,32 @@ __device__ __forceinline__ void prune_sequence(
   const int n_cand = block_reduce_sum(mine, red);
   if (budget > 0 && n_cand > budget) {
     if (keys != nullptr) {
-      // The budget-th best key, bit by bit from the top: x grows while at least `budget` keys are
-      // >= x.  Keys are distinct, so exactly `budget` candidates end up >= x.  One count (wave
-      // popcounts added in LDS) and one barrier per bit; non-candidates carry key 0.
+      // The budget-th best key, digit by digit from the top.  Per digit: a 64-bin histogram of the
+      // keys that match the digits fixed so far (LDS atomics, one histogram per round so that no
+      // round waits for a reset), one barrier, then every wave finds, with a prefix sum over the
+      // bins from the top, the largest digit d such that at least `need` matching keys have a digit
+      // >= d; the keys above d are all in, the search goes on among those with digit d.  Keys are
+      // distinct, so exactly `budget` candidates end up >= x.  Non-candidates carry key 0.
       for (int i = tid; i < n; i += PR_THREADS) keys[i] = (i >= 1 && ok[i]) ? order_key(sum[i], i) : 0ull;
-      for (int b = tid; b < 64; b += PR_THREADS) bit_count[b] = 0;
+      for (int b = tid; b < N_DIGITS * 64; b += PR_THREADS) digit_hist[b] = 0;
       __syncthreads();
-      unsigned long long x = 0ull;
-      for (int bit = KEY_BITS - 1; bit >= 0; --bit) {
-        const unsigned long long cand = x | (1ull << bit);
-        int c = 0;  // wave-wide count: ballots and scalar popcounts, no cross-lane data movement
-        for (int base = 0; base < n; base += PR_THREADS) {
-          const int i = base + tid;
-          c += __popcll(__ballot(i < n && keys[i] >= cand));
+      unsigned long long x = 0ull;  // digits fixed so far, in place
+      int need = budget;
+      for (int r = 0; r < N_DIGITS; ++r) {
+        const int shift = (N_DIGITS - 1 - r) * DIGIT_BITS;
+        int* hist = digit_hist + r * 64;
+        for (int i = tid; i < n; i += PR_THREADS) {
+          const unsigned long long k = keys[i];
+          if (k != 0ull && (k >> (shift + DIGIT_BITS)) == (x >> (shift + DIGIT_BITS)))
+            atomicAdd(&hist[(int)((k >> shift) & 63ull)], 1);
         }
-        if (lane == 0 && c != 0) atomicAdd(&bit_count[bit], c);
         __syncthreads();
-        if (bit_count[bit] >= budget) x = cand;
+        const int mine_c = hist[63 - lane];            // lane l looks at digit 63 - l
+        const int incl = wave_prefix_sum(mine_c);      // matching keys with digit >= 63 - l
+        const int l_hit = __ffsll((long long)__ballot(incl >= need)) - 1;  // never empty: need <= matching keys
+        const int above = __builtin_amdgcn_readlane(incl - mine_c, l_hit);
+        need -= above;
+        x |= (unsigned long long)(63 - l_hit) << shift;
       }
       for (int i = tid; i < n; i += PR_THREADS) nxt[i] = (i == 0) ? 1 : ((keys[i] != 0ull && keys[i] >= x) ? 1 : 0);
     } else {
@@ -152,18 +164,37 @@ __device__ __forceinline__ void prune_sequence(
     const int excl = incl - tot;
 #pragma unroll
     for (int q = 0; q < PER; ++q) chunk_sum[tid * PER + q] = excl + loc[q];
-    if (tid == 63) ws_count[s] = incl;
+    if (tid == 63) {
+      ws_count[s] = incl;
+      red[0] = incl;  // (red is idle by now; read after the next barrier)
+    }
   }
   __syncthreads();
   int pos = chunk_sum[tid];
   for (int i = lo; i < hi; ++i) {
     const int k = ok[i] ? 1 : 0;
     ws_pos[o + i] = k ? pos : -1;
+    if (emit) nxt[i] = k ? pos : -1;
     keep[o + i] = (uint8_t)k;
     pos += k;
     if (copy_out) {
       depth[o + i] = dep[i];
       cumlogp[o + i] = sum[i];
+    }
+  }
+  if (emit) {
+    // a single sequence: its packed offset is 0, so the renumbered tree can be written right here
+    __syncthreads();
+    if (tid == 0) {
+      out_offsets[0] = 0;
+      out_offsets[1] = red[0];
+    }
+    for (int i = tid; i < n; i += PR_THREADS) {
+      const int p = nxt[i];
+      if (p >= 0) {
+        out_src[p] = i;
+        out_parent[p] = (i == 0) ? -1 : nxt[par[i]];
+      }
     }
   }
 }
@@ -172,14 +203,15 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
     const int32_t* __restrict__ parent, const float* __restrict__ logc, const int32_t* __restrict__ node_offsets,
     const int32_t* __restrict__ d_max, const float* __restrict__ theta, const int32_t* __restrict__ max_nodes,
     int32_t* __restrict__ depth, float* __restrict__ cumlogp, uint8_t* __restrict__ keep,
-    int32_t* __restrict__ ws_pos, int32_t* __restrict__ ws_count, int32_t* __restrict__ ws_flag) {
+    int32_t* __restrict__ ws_pos, int32_t* __restrict__ ws_count, int32_t* __restrict__ ws_flag,
+    int32_t* __restrict__ out_offsets, int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent) {
   __shared__ int l_par[PR_LDS_NODES];
   __shared__ int l_dep[PR_LDS_NODES];
   __shared__ float l_sum[PR_LDS_NODES];
   __shared__ int l_ok[PR_LDS_NODES];
   __shared__ int l_new[PR_LDS_NODES];
   __shared__ unsigned long long l_keys[PR_LDS_NODES];
-  __shared__ int bit_count[64];
+  __shared__ int digit_hist[N_DIGITS * 64];
   __shared__ float l_logc[PR_LDS_NODES];
   __shared__ int red[PR_THREADS / 64];
   __shared__ int chunk_sum[PR_THREADS];
@@ -188,7 +220,10 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
   const int o = node_offsets[s];
   const int n = node_offsets[s + 1] - o;
   if (n <= 0) {
-    if (tid == 0) ws_count[s] = 0;
+    if (tid == 0) {
+      ws_count[s] = 0;
+      if (gridDim.x == 1) out_offsets[0] = out_offsets[1] = 0;
+    }
     return;
   }
   if (n <= PR_LDS_NODES) {
@@ -200,13 +235,14 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
       l_logc[i] = logc[o + i];
     }
     __syncthreads();
-    prune_sequence(l_par, l_dep, l_sum, l_ok, l_new, l_keys, bit_count, red, chunk_sum, n, o, true, l_logc, dcap, th, budget, depth, cumlogp, keep, ws_pos, ws_count, s);
+    prune_sequence(l_par, l_dep, l_sum, l_ok, l_new, l_keys, digit_hist, red, chunk_sum, n, o, true, l_logc, dcap, th, budget, depth, cumlogp, keep, ws_pos, ws_count, s,
+                   gridDim.x == 1, out_offsets, out_src, out_parent);
   } else {
     // very large trees: the output arrays and the workspace are the scratch (ws_pos is not written
     // before the last phase, so it can hold the budget flags meanwhile)
-    prune_sequence(const_cast<int32_t*>(parent + o), depth + o, cumlogp + o, ws_flag + o, ws_pos + o, (unsigned long long*)nullptr, bit_count, red,
+    prune_sequence(const_cast<int32_t*>(parent + o), depth + o, cumlogp + o, ws_flag + o, ws_pos + o, (unsigned long long*)nullptr, digit_hist, red,
                    chunk_sum, n, o, false, const_cast<float*>(logc + o), d_max[s], theta[s], max_nodes[s], depth, cumlogp,
-                   keep, ws_pos, ws_count, s);
+                   keep, ws_pos, ws_count, s, false, out_offsets, out_src, out_parent);
   }
 }
 
@@ -266,9 +302,12 @@ extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, con
   int32_t* ws_count = c.take<int32_t>(B);
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(hs::k_prune_select, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, logc, node_offsets, d_max,
-                     theta, max_nodes, depth, cumlogp, keep, ws_pos, ws_count, ws_flag);
+                     theta, max_nodes, depth, cumlogp, keep, ws_pos, ws_count, ws_flag, out_offsets, out_src,
+                     out_parent);
   hs_status r = hs::launch_status("prune select");
   if (r != HS_OK) return r;
+  // a single tree that fits LDS was emitted by the selecting workgroup itself
+  if (B == 1 && NN <= hs::PR_LDS_NODES) return r;
   hipLaunchKernelGGL(hs::k_prune_emit, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, node_offsets, B, ws_pos,
                      ws_count, out_offsets, out_src, out_parent);
   return hs::launch_status("prune emit");
