@@ -1,6 +1,7 @@
 // Shared pieces of the tree-attention kernels (internal).
 //
-// Work decomposition (all kernels): grid.y = sequence, grid.x enumerates (key split, row block,
+// Work decomposition, plain launches (float32 / any-shape kernel; matrix-core kernel when a batch
+// has more sequences than the table below holds): grid.y = sequence, grid.x enumerates (key split, row block,
 // KV head) of that sequence; workgroups whose indices fall outside their sequence's extent exit at
 // once.  The prefix of sequence s is cut into n_sp = max(1, ceil(L_s / split_len)) splits; the last
 // split also handles the tree rows themselves (the masked part).  Rows of one KV head g are
@@ -41,6 +42,23 @@ __device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_elem<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
+// One sequence of the launch as the host planned it (work-list launches).  Its work items are
+// numbered first_item + (split * n_rg + row_group) * Hkv + kv_head; entries are listed by falling
+// cost of an item, so that the hardware's in-order dispatch starts the long items first.  The
+// prefix is cut into n_sp splits of tiles_per_split 64-key tiles (the last one takes the rest and
+// the tree rows).
+struct SeqEntry {
+  int first_item;
+  int n0;               // first tree row of the sequence (global row number)
+  int M;                // tree rows
+  int L;                // prefix tokens
+  long long p0;         // first prefix token (global)
+  int tiles_per_split;
+  short n_sp, n_rg;
+};
+static_assert(sizeof(SeqEntry) == 32, "eight dwords, fetched as two 16-byte loads per lane");
+constexpr int ATTN_TBL = 96;  // entries that fit the kernel-argument segment next to the rest
+
 struct AttnArgs {
   const void* q;
   const void* k_prefix;
@@ -58,6 +76,9 @@ struct AttnArgs {
   void* o;
   float* lse;
   float* part;
+  int n_tbl;       // > 0: work-list launch (1-D grid over the items of tbl[0 .. n_tbl)); 0: grid.y = sequence
+  int n_items;
+  SeqEntry tbl[ATTN_TBL];
 };
 
 __host__ __device__ __forceinline__ int splits_of(int64_t L, int split_len) {

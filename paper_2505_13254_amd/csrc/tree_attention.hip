@@ -5,6 +5,8 @@
 // (k_attn_generic: vector ALU, K/V tiles staged through LDS, 16 rows per workgroup) and the
 // split combine (k_attn_combine).  bfloat16 with head dimension 128 goes to the MFMA kernel in
 // tree_attention_mfma.hip.
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "attn_common.h"
@@ -144,14 +146,14 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
     }
   }
 
-  // write the result (sp_max == 1) or this split's partial record
+  // write the result (sequences with one split) or this split's partial record
 #pragma unroll
   for (int rr = 0; rr < 4; ++rr) {
     const int r = r0 + wave * 4 + rr;
     if (r >= R) continue;
     const int i = r / G, gi = r - i * G;
     const int64_t row = (int64_t)(n0 + i) * Hq + g * G + gi;
-    if (a.sp_max == 1) {
+    if (n_sp == 1) {
       T* out = static_cast<T*>(a.o) + row * D;
       const float inv = 1.f / l_run[rr];
 #pragma unroll
@@ -169,32 +171,62 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
   }
 }
 
-// Merges the splits of one (node, head): weights exp(m_sp - max m).
+// Merges the splits of one (node, head) row: weights exp(m_sp - max m), splits taken in rising
+// order.  One wave per row, lane l owns D / 64 adjacent output elements
+constexpr int CMB_ROWS = 4;  // rows (waves) per workgroup
 template <typename T, int D>
-__global__ __launch_bounds__(D) void k_attn_combine(AttnArgs a, int NN) {
-  const int64_t row = blockIdx.x;  // node_global * Hq + h
+__global__ __launch_bounds__(64 * CMB_ROWS) void k_attn_combine(AttnArgs a, int64_t n_rows) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * CMB_ROWS + (threadIdx.x >> 6);  // node_global * Hq + h
+  if (row >= n_rows) return;
   const int node = (int)(row / a.Hq);
-  // sequence of this node: last s with node_offsets[s] <= node
-  int lo = 0, hi = a.B;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.node_offsets[mid] <= node) lo = mid; else hi = mid;
+  int n_sp;
+  if (a.n_tbl > 0) {
+    // the table entry whose row range holds this node
+    n_sp = 1;
+    for (int base = 0; base < a.n_tbl; base += 64) {
+      const int idx = base + lane;
+      bool mine = false;
+      int cnt = 0;
+      if (idx < a.n_tbl) {
+        mine = node >= a.tbl[idx].n0 && node < a.tbl[idx].n0 + a.tbl[idx].M;
+        cnt = a.tbl[idx].n_sp;
+      }
+      const unsigned long long hit = __ballot(mine);
+      if (hit != 0ull) {
+        n_sp = __builtin_amdgcn_readlane(cnt, __builtin_ctzll(hit));
+        break;
+      }
+    }
+  } else {
+    // sequence of this node: last s with node_offsets[s] <= node
+    int lo = 0, hi = a.B;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.node_offsets[mid] <= node) lo = mid; else hi = mid;
+    }
+    n_sp = splits_of(a.prefix_offsets[lo + 1] - a.prefix_offsets[lo], a.split_len);
   }
-  const int64_t L = a.prefix_offsets[lo + 1] - a.prefix_offsets[lo];
-  const int n_sp = splits_of(L, a.split_len);
-  const float* rec = a.part + row * a.sp_max * (D + ATTN_REC_PAD);
+  if (n_sp == 1) return;  // written directly by the attention kernel
+  constexpr int REC = D + ATTN_REC_PAD;
+  const float* rec = a.part + row * a.sp_max * REC;
   float m = -HS_INF;
-  for (int sp = 0; sp < n_sp; ++sp) m = fmaxf(m, rec[sp * (D + ATTN_REC_PAD) + D]);
-  float l = 0.f, o = 0.f;
-  const int d = threadIdx.x;
+  for (int sp = 0; sp < n_sp; ++sp) m = fmaxf(m, rec[sp * REC + D]);
+  constexpr int DPL = D / 64;
+  float l = 0.f, o[DPL];
+#pragma unroll
+  for (int dd = 0; dd < DPL; ++dd) o[dd] = 0.f;
   for (int sp = 0; sp < n_sp; ++sp) {
-    const float* r = rec + sp * (D + ATTN_REC_PAD);
+    const float* r = rec + sp * REC;
     const float w = __expf(r[D] - m);
     l = fmaf(r[D + 1], w, l);
-    o = fmaf(r[d], w, o);
+#pragma unroll
+    for (int dd = 0; dd < DPL; ++dd) o[dd] = fmaf(r[lane * DPL + dd], w, o[dd]);
   }
-  store_elem<T>(static_cast<T*>(a.o) + row * D + d, o / l);
-  if (a.lse && d == 0) a.lse[row] = m + __logf(l);
+  const float inv = 1.f / l;
+#pragma unroll
+  for (int dd = 0; dd < DPL; ++dd) store_elem<T>(static_cast<T*>(a.o) + row * D + lane * DPL + dd, o[dd] * inv);
+  if (a.lse && lane == 0) a.lse[row] = m + __logf(l);
 }
 
 struct AttnPlan {
@@ -236,6 +268,126 @@ static AttnPlan plan_attention(const int32_t* hno, const int64_t* hpo, int B, in
   p.sp_max = splits_of(max_L, p.split_len);
   p.ok = true;
   return p;
+}
+
+// ---- work-list plan for the matrix-core kernel.
+// Every (sequence, split, row group, KV head) is one work item = one workgroup.  The hardware
+// starts workgroups in index order as compute units free up, so listing the items by falling cost
+// is longest-processing-time-first scheduling.  The cost model (microseconds, fitted to
+// measurements on MI355X) only has to rank alternatives: an item costs a fixed part plus a
+// per-tile part that grows with the number of waves that have rows.
+constexpr int PLAN_CUS = 256;
+constexpr float PLAN_ITEM_US = 10.f;
+constexpr int PLAN_MIN_SPLIT_TILES = 8;  // splits of at least 512 tokens (the workspace bound relies on it)
+static inline float plan_tile_us(int waves) { return 1.25f + 0.04f * (float)waves; }
+
+struct ListPlan {
+  float est_us;
+  int target;
+};
+
+// Splits of a sequence of `tiles` prefix tiles when items should hold about `target` tiles.
+static inline int plan_splits(int tiles, int target, int sp_cap) {
+  int n = (tiles + target / 2) / target;
+  const int most = tiles / PLAN_MIN_SPLIT_TILES;
+  if (n > most) n = most;
+  if (n > sp_cap) n = sp_cap;
+  return n < 1 ? 1 : n;
+}
+
+// Fills a.tbl / a.n_tbl / a.n_items / a.sp_max.  Returns false when the batch does not fit the table.
+static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, int B, int sp_cap) {
+  struct Seq {
+    int s, M, tiles, rg, waves0, waves_last, ttiles;
+  };
+  Seq seqs[ATTN_TBL];
+  int n = 0;
+  for (int s = 0; s < B; ++s) {
+    const int M = hno[s + 1] - hno[s];
+    const int64_t L = hpo[s + 1] - hpo[s];
+    if (M <= 0) continue;
+    if (n == ATTN_TBL || L >= (int64_t)1 << 30) return false;
+    const int blocks = (a.G * M + 31) / 32;  // 32-row wave blocks
+    Seq q;
+    q.s = s;
+    q.M = M;
+    q.tiles = (int)((L + 63) / 64);
+    q.rg = (blocks + 7) / 8;
+    q.waves0 = blocks < 8 ? blocks : 8;
+    q.waves_last = blocks - 8 * (q.rg - 1);
+    q.ttiles = (M + 63) / 64;
+    seqs[n++] = q;
+  }
+  if (n == 0) return false;
+  static const int targets[] = {1 << 20, 192, 128, 96, 64, 48, 32, 24, 16, 8};
+  static const int forced = [] {
+    const char* e = getenv("HS_ATTN_SPLIT_TILES");  // tuning aid: fixes the target tiles per item
+    return e ? atoi(e) : 0;
+  }();
+  ListPlan best{0.f, 0};
+  for (int target : targets) {
+    if (forced > 0) target = forced;
+    double total = 0.0, rec_bytes = 0.0;
+    float mx = 0.f, mn = 1e30f;
+    int64_t items = 0;
+    for (int i = 0; i < n; ++i) {
+      const Seq& q = seqs[i];
+      const int nsp = plan_splits(q.tiles, target, sp_cap);
+      const int per = (q.tiles + nsp - 1) / nsp;
+      const float big = PLAN_ITEM_US + (float)(per + q.ttiles) * plan_tile_us(q.waves0);
+      const float one = PLAN_ITEM_US + (float)per * plan_tile_us(q.waves0);
+      const float one_last = PLAN_ITEM_US + (float)per * plan_tile_us(q.waves_last);
+      total += (double)a.Hkv * nsp * ((q.rg - 1) * one + one_last);
+      items += (int64_t)a.Hkv * nsp * q.rg;
+      if (big > mx) mx = big;
+      if (one_last < mn) mn = one_last;
+      if (nsp > 1) rec_bytes += (double)q.M * a.Hq * nsp * ATTN_REC * 4 * 2;  // written, then read
+    }
+    float est = (float)(total / PLAN_CUS) + 0.15f * mx;
+    if (mx > est) est = mx;
+    if (mx - mn <= 0.1f * mx) {  // equal items run in whole rounds
+      const float rounds = (float)((items + PLAN_CUS - 1) / PLAN_CUS) * (float)(total / (double)items);
+      if (rounds > est) est = rounds;
+    }
+    if (rec_bytes > 0.0) est += 4.f + (float)(rec_bytes / 2.5e6);  // the combine launch, ~2.5 TB/s
+    if (best.target == 0 || est < best.est_us) best = ListPlan{est, target};
+    if (forced > 0) break;
+  }
+  // the table: sequences by falling cost of an item
+  int order[ATTN_TBL];
+  float cost[ATTN_TBL];
+  int nsp_of[ATTN_TBL], per_of[ATTN_TBL];
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = seqs[i];
+    nsp_of[i] = plan_splits(q.tiles, best.target, sp_cap);
+    per_of[i] = (q.tiles + nsp_of[i] - 1) / nsp_of[i];
+    if (per_of[i] < 1) per_of[i] = 1;
+    cost[i] = (float)per_of[i] * plan_tile_us(q.waves0);
+    order[i] = i;
+  }
+  std::stable_sort(order, order + n, [&](int x, int y) { return cost[x] > cost[y]; });
+  int64_t first = 0;
+  int sp_max = 1;
+  for (int k = 0; k < n; ++k) {
+    const int i = order[k];
+    const Seq& q = seqs[i];
+    SeqEntry& e = a.tbl[k];
+    e.first_item = (int)first;
+    e.n0 = hno[q.s];
+    e.M = q.M;
+    e.L = (int)(hpo[q.s + 1] - hpo[q.s]);
+    e.p0 = hpo[q.s];
+    e.tiles_per_split = per_of[i];
+    e.n_sp = (short)nsp_of[i];
+    e.n_rg = (short)q.rg;
+    first += (int64_t)a.Hkv * nsp_of[i] * q.rg;
+    if (nsp_of[i] > sp_max) sp_max = nsp_of[i];
+    if (first >= (int64_t)1 << 30) return false;
+  }
+  a.n_tbl = n;
+  a.n_items = (int)first;
+  a.sp_max = sp_max;
+  return true;
 }
 
 }  // namespace hs
@@ -293,24 +445,33 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
   const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && Hq / Hkv <= 128 && Hkv <= 4096 && aligned16(q) &&
                     aligned16(k_prefix) && aligned16(v_prefix) && aligned16(k_tree) && aligned16(v_tree) &&
                     aligned16(o);
-  AttnPlan plan = plan_attention(host_node_offsets, host_prefix_offsets, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
-  // the workspace bound assumes at most 64 splits per sequence
-  while (plan.sp_max > 64) {
-    plan.split_len *= 2;
-    plan.sp_max = splits_of(plan.max_L, plan.split_len);
-  }
-  const size_t need = part_bytes(NN, Hq, D, plan.sp_max);
-  HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
-             HS_ERR_WORKSPACE, "hs_tree_attention: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
-             workspace_bytes);
-
   AttnArgs a;
   a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_tree = k_tree; a.v_tree = v_tree;
   a.parent = parent; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
-  a.split_len = plan.split_len; a.sp_max = plan.sp_max; a.n_rb_max = plan.n_rb_max;
   a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
+  a.n_tbl = 0; a.n_items = 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  // the workspace query bounds the splits of a sequence the same way
+  const int64_t sp_bound = total_prefix / 512 + 1;
+  const int sp_cap = (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound);
+
+  AttnPlan plan{};
+  if (!(mfma && plan_worklist(a, host_node_offsets, host_prefix_offsets, B, sp_cap))) {
+    a.n_tbl = 0;
+    plan = plan_attention(host_node_offsets, host_prefix_offsets, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
+    while (plan.sp_max > sp_cap) {
+      plan.split_len *= 2;
+      plan.sp_max = splits_of(plan.max_L, plan.split_len);
+    }
+    a.split_len = plan.split_len; a.sp_max = plan.sp_max; a.n_rb_max = plan.n_rb_max;
+  } else {
+    a.split_len = 0; a.n_rb_max = 1;
+  }
+  const size_t need = part_bytes(NN, Hq, D, a.sp_max);
+  HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
+             HS_ERR_WORKSPACE, "hs_tree_attention: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+             workspace_bytes);
 
   if (mfma) {
     hs_status r = attn_mfma_launch(a, max_M, st);
@@ -324,12 +485,13 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
     hs_status r = launch_status("tree attention");
     if (r != HS_OK) return r;
   }
-  if (plan.sp_max > 1) {
-    dim3 grid((unsigned)((int64_t)NN * Hq));
-    if (dt == HS_F32 && D == 64) hipLaunchKernelGGL((k_attn_combine<float, 64>), grid, dim3(64), 0, st, a, NN);
-    else if (dt == HS_F32) hipLaunchKernelGGL((k_attn_combine<float, 128>), grid, dim3(128), 0, st, a, NN);
-    else if (D == 64) hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, dim3(64), 0, st, a, NN);
-    else hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, dim3(128), 0, st, a, NN);
+  if (a.sp_max > 1) {
+    const int64_t n_rows = (int64_t)NN * Hq;
+    dim3 grid((unsigned)((n_rows + CMB_ROWS - 1) / CMB_ROWS)), block(64 * CMB_ROWS);
+    if (dt == HS_F32 && D == 64) hipLaunchKernelGGL((k_attn_combine<float, 64>), grid, block, 0, st, a, n_rows);
+    else if (dt == HS_F32) hipLaunchKernelGGL((k_attn_combine<float, 128>), grid, block, 0, st, a, n_rows);
+    else if (D == 64) hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, block, 0, st, a, n_rows);
+    else hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, block, 0, st, a, n_rows);
     return launch_status("tree attention combine");
   }
   return HS_OK;

@@ -135,24 +135,63 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   unsigned long long ts_[16] = {0};
 #endif
   TS(0);
-  const int s = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int n0 = a.node_offsets[s];
-  const int M = a.node_offsets[s + 1] - n0;
-  const int64_t p0 = a.prefix_offsets[s];
-  const int64_t L = a.prefix_offsets[s + 1] - p0;
-  if (M <= 0) return;
   const int G = a.G, Hkv = a.Hkv, Hq = a.Hq;
+  int n0, M, g, rg, sp, n_sp, tiles_per_split;
+  int64_t p0, L;
+  if (a.n_tbl > 0) {
+    // Work-list launch: the table of sequences sits in the kernel arguments; lane l fetches entry
+    // l (and l + 64), a ballot finds the entry whose item range holds this workgroup, and its
+    // fields are read from that lane: one memory round trip, no dependent offset loads.
+    const int x = blockIdx.x;
+    unsigned f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int base = 0; base < a.n_tbl; base += 64) {
+      const int idx = base + lane;
+      uintx4 lo = {0x7fffffffu, 0, 0, 0}, hi = {0, 0, 0, 0};
+      if (idx < a.n_tbl) {
+        lo = *reinterpret_cast<const uintx4*>(&a.tbl[idx]);
+        hi = *(reinterpret_cast<const uintx4*>(&a.tbl[idx]) + 1);
+      }
+      const unsigned long long below = __ballot((int)lo[0] <= x);  // entries are in rising first_item order
+      if (below == 0ull) break;
+      const int e = __builtin_popcountll(below) - 1;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        f[k] = __builtin_amdgcn_readlane(lo[k], e);
+        f[4 + k] = __builtin_amdgcn_readlane(hi[k], e);
+      }
+      if (below != ~0ull) break;
+    }
+    n0 = (int)f[1];
+    M = (int)f[2];
+    L = (int)f[3];
+    p0 = (int64_t)(((unsigned long long)f[5] << 32) | f[4]);
+    tiles_per_split = (int)f[6];
+    n_sp = (int)(short)(f[7] & 0xffffu);
+    const int n_rg = (int)(short)(f[7] >> 16);
+    int local = x - (int)f[0];
+    g = local % Hkv;
+    local /= Hkv;
+    rg = local % n_rg;
+    sp = local / n_rg;
+  } else {
+    const int s = blockIdx.y;
+    n0 = a.node_offsets[s];
+    M = a.node_offsets[s + 1] - n0;
+    p0 = a.prefix_offsets[s];
+    L = a.prefix_offsets[s + 1] - p0;
+    if (M <= 0) return;
+    n_sp = splits_of(L, a.split_len);
+    tiles_per_split = a.split_len / MF_TILE;
+    int x = blockIdx.x;
+    g = x % Hkv;
+    x /= Hkv;
+    rg = x % n_rg_max;
+    sp = x / n_rg_max;
+    if (rg >= (G * M + MF_ROWS - 1) / MF_ROWS || sp >= n_sp) return;
+  }
   const int R = G * M;
-  const int n_rg = (R + MF_ROWS - 1) / MF_ROWS;
-  const int n_sp = splits_of(L, a.split_len);
-  int x = blockIdx.x;
-  const int g = x % Hkv;
-  x /= Hkv;
-  const int rg = x % n_rg_max;
-  const int sp = x / n_rg_max;
-  if (rg >= n_rg || sp >= n_sp) return;
 
   const char* kp = static_cast<const char*>(a.k_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
   const char* vp = static_cast<const char*>(a.v_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
@@ -161,8 +200,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const int64_t tok_stride = (int64_t)Hkv * MF_ROW_BYTES;
 
   const bool last_split = sp == n_sp - 1;
-  const int64_t k_lo = (int64_t)sp * a.split_len;
-  const int64_t k_hi = last_split ? L : k_lo + a.split_len;
+  const int64_t k_lo = (int64_t)sp * tiles_per_split * MF_TILE;
+  const int64_t k_hi = last_split ? L : k_lo + (int64_t)tiles_per_split * MF_TILE;
   const int n_ptiles = (int)((k_hi - k_lo + MF_TILE - 1) / MF_TILE);
   const int n_ttiles = last_split ? (M + MF_TILE - 1) / MF_TILE : 0;
   const int n_tiles = n_ptiles + n_ttiles;  // >= 1: a split holds prefix keys, or it is the last one
@@ -586,8 +625,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   }
   if (!wave_active) return;
 
-  if (a.sp_max == 1) {
-    // ---- results, single split everywhere: normalised rows go out as bf16.  Each wave turns its
+  if (n_sp == 1) {
+    // ---- results, sequence with a single split: normalised rows go out as bf16.  Each wave turns its
     // 32 x 128 block around in LDS (the tile ring is free: every wave has passed the last barrier),
     // so that a lane stores 16 contiguous bytes and a store instruction covers four whole rows.
     constexpr int ST_ROW = MF_ROW_BYTES + 16;  // padded row: the 8-byte writes of 16 rows spread over all banks
@@ -658,6 +697,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
 hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream) {
   const int n_rg_max = (a.G * max_tree_rows + MF_ROWS - 1) / MF_ROWS;
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);
+  if (a.n_tbl > 0) grid = dim3((unsigned)a.n_items, 1u);
   hipLaunchKernelGGL(k_attn_mfma, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
   return launch_status("tree attention (mfma)");
 }

@@ -107,6 +107,29 @@ def test_ragged_batch_with_empty_sequence(G):
     _compare(G, _case(w, 3, parents, Ls, "peaky"), "bf16")
 
 
+def test_split_and_unsplit_sequences_in_one_launch(G):
+    """A long sequence is cut into key splits (merged by the combine kernel) while the short ones of
+    the same launch are written directly by the attention kernel."""
+    w = W.small(W.WORKLOADS[5])
+    rs = np.random.RandomState(11)
+    sizes, Ls = [33, 9, 70, 129, 5], [6000, 100, 3000, 9000, 511]
+    _compare(G, _case(w, 8, [_random_parents(rs, n) for n in sizes], Ls, "peaky"), "bf16")
+
+
+@pytest.mark.parametrize("B", [70, 96, 100])
+def test_batches_around_the_work_list_capacity(G, B):
+    """More than 64 sequences need the second half of the kernel-argument table; more than 96 do
+    not fit it and take the launch with one grid row per sequence."""
+    w = W.small(W.WORKLOADS[5])
+    rs = np.random.RandomState(B)
+    sizes = [int(x) for x in rs.randint(0, 20, size=B)]
+    Ls = [int(x) for x in rs.randint(0, 300, size=B)]
+    Ls[B // 2] = 2500                                        # one sequence long enough to be split
+    sizes[B // 2] = 40
+    parents = [_random_parents(rs, n) if n else [] for n in sizes]
+    _compare(G, _case(w, 9, parents, Ls, "unit"), "bf16")
+
+
 def test_many_splits_long_prefix(G):
     w = W.WORKLOADS[2]
     rs = np.random.RandomState(8)
