@@ -14,10 +14,14 @@ Pin status (see tests/test_oracle_*.py):
   verify_accept       pinned: brute-force longest matching path (greedy), planted paths, chain tree
                       == textbook speculative sampling, exact output-distribution enumeration
                       on tiny vocabularies, one-hot target == greedy.
+  adaptive_control    pinned: the Section 4.3 formulas worked by hand on the framework figure's
+                      example, Eq. 1 on uniform rows (T ln K), brute-force enumeration of the
+                      deepest paths, numpy.searchsorted for the bin lookup.
 """
 from .entropy_topk import draft_entropy_topk
 from .tree_prune import tree_prune
 from .tree_attention import tree_attention
 from .verify_accept import verify_accept
+from .adaptive_control import adaptive_control
 
-__all__ = ["draft_entropy_topk", "tree_prune", "tree_attention", "verify_accept"]
+__all__ = ["draft_entropy_topk", "tree_prune", "tree_attention", "verify_accept", "adaptive_control"]
