@@ -11,6 +11,15 @@
  *                                                                      (Section 2.2: tree-mask attention)
  *   hs_verify_accept        greedy or stochastic accept walk           (Section 2.1 acceptance rule)
  *
+ * and, around them, the device-side pieces of the adaptive step (no host round trip inside):
+ *
+ *   hs_tree_expand          one level of Top-K growth of the draft tree from the Top-K results of
+ *                           the rows expanded last                     (Section 2.2 Expansion; Section 4.3
+ *                                                                       Dynamic Extended Drafting)
+ *   hs_adaptive_control     cumulative Top-K entropy of the operational path, its entropy bin, and
+ *                           the depth extension and node budget of that bin (Section 4.1 Eq. 1; 4.2; 4.3)
+ *   hs_tree_prune_counted   hs_tree_prune on trees stored with spare capacity
+ *
  * Conventions that hold for every call
  *   - Pointers are DEVICE pointers unless the parameter name starts with host_.  The caller owns
  *     every buffer; the library allocates and frees nothing, and keeps nothing after a call.
@@ -28,6 +37,9 @@
  *   - Same inputs give bit-identical outputs (no floating-point atomics).
  *   - Trees: row 0 of each sequence is the root (the last committed token), parent[root] = -1,
  *     parents are LOCAL indices within the sequence and parent[i] < i.
+ *   - Trees with spare capacity: where a call takes node_counts [B], sequence s uses rows
+ *     node_offsets[s] .. node_offsets[s] + node_counts[s] - 1 and the rows up to node_offsets[s+1]
+ *     are unused capacity; node_counts == NULL means that every row is used.
  */
 #ifndef HETEROSPEC_H_
 #define HETEROSPEC_H_
@@ -55,6 +67,11 @@ typedef enum {
   HS_ACCEPT_STOCHASTIC = 1,           /* accept x with prob min(1, p(x)/p_hat(x)); residual on rejection */
   HS_ACCEPT_STOCHASTIC_POINTMASS = 2  /* candidates treated as point-mass proposals: accept with p(x)    */
 } hs_accept_mode;
+
+typedef enum {
+  HS_PSTAR_CUMULATIVE = 0, /* operational path = deepest-level node with the largest cumulative value */
+  HS_PSTAR_LOCAL = 1       /* ... with the largest confidence of its own (final) token                 */
+} hs_pstar_mode;
 
 typedef void* hs_stream; /* a hipStream_t */
 
@@ -176,6 +193,83 @@ hs_status hs_verify_accept(const float* target_logits, const float* draft_logits
                            const float* uniforms, int32_t max_depth,
                            int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
                            void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_tree_prune_counted: hs_tree_prune for trees stored with spare capacity (see the conventions):
+ * node_counts [B] int32 gives the used rows of each sequence; depth / cumlogp / keep are written for
+ * used rows only.  NN = node_offsets[B] (capacity).  node_counts == NULL is hs_tree_prune.
+ */
+hs_status hs_tree_prune_counted(const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                                const int32_t* node_counts, int32_t B, int32_t NN,
+                                const int32_t* d_max, const float* theta, const int32_t* max_nodes,
+                                int32_t* depth, float* cumlogp, uint8_t* keep,
+                                int32_t* out_offsets, int32_t* out_src, int32_t* out_parent,
+                                void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_tree_expand  (Section 2.2, Expansion: the tree grows one depth at a time; the nodes of the
+ * newest depth with the largest value V, the product of the confidences on their root path, are
+ * expanded with the Top-k tokens of their draft distribution.  Section 4.3, Dynamic Extended
+ * Drafting: the number of levels may differ per sequence.)
+ *
+ * The draft trees of B sequences live in arrays with room for `cap` rows per sequence (sequence s
+ * starts at row s * cap): parent, token, depth int32; logc, cumlogp, ent float.  n_nodes [B] counts
+ * the used rows, level [B] the levels grown, frontier [B,F] lists the rows to expand now (local
+ * indices, ascending) and n_frontier [B] how many of them there are.
+ *
+ * One call grows every sequence by one level from the results of hs_draft_entropy_topk on the
+ * draft distributions of its frontier rows: result row s * F + j belongs to frontier[s,j].
+ *   first != 0: the state is initialised first (root alone: parent -1, token -1, values 0; the
+ *     frontier is the root, level 0), so the results are those of the roots' rows (j = 0).
+ *   For each frontier row f (in order) and k < K: a new row with parent f, token topk_idx[.,k],
+ *     logc = topk_logp[.,k], cumlogp = fl32(cumlogp[f] + min(logc, 0)), depth[f] + 1, ent 0;
+ *     ent[f] = ent_topk[.].  A frontier row whose K children would exceed `cap` gets none.
+ *   The next frontier is the F best new rows under (cumlogp descending, row ascending), listed in
+ *     ascending row order; level += 1.
+ *   A sequence with level >= d_limit[s] (d_limit may be NULL: no limit) or an empty frontier is
+ *     left unchanged and its n_frontier becomes 0.
+ * frontier_rows [B*F] int32 (may be NULL): global row (s * cap + local) of each frontier slot, for
+ *   gathering the next draft inputs; slots past n_frontier repeat the sequence's last valid one
+ *   (row s * cap when there is none).
+ * Requires 1 <= K <= HS_MAX_TOPK, 1 <= F, F * K <= 4096, cap >= 1 + K.
+ */
+hs_status hs_tree_expand(int32_t* parent, int32_t* token, float* logc, float* cumlogp, int32_t* depth,
+                         float* ent, int32_t* n_nodes, int32_t* level, int32_t* frontier,
+                         int32_t* n_frontier, int32_t* frontier_rows,
+                         const int32_t* topk_idx, const float* topk_logp, const float* ent_topk,
+                         const int32_t* d_limit, int32_t B, int32_t cap, int32_t F, int32_t K,
+                         int32_t first, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_adaptive_control  (Section 4.1, Eq. 1: Phi(P) = sum over the positions of path P of the
+ * Top-K entropy of the draft distribution at that position, evaluated on the operational path P*,
+ * the candidate path with the highest final-token confidence; Section 4.2: the trained decision
+ * tree partitions Phi into entropy bins B_0 .. B_{n-1}, lowest entropy first; Section 4.3:
+ * d'(B_i) = d_base + Delta(B_i), N'(B_i) = gamma_i * N_default + Delta(B_i), Delta(B_i) = alpha - i
+ * for the low-entropy bins, nothing changes for the others.)
+ *
+ * Per sequence (trees as in hs_tree_prune, optionally with spare capacity):
+ *   P*      the node of the deepest level present with the largest cumulative value (cumlogp as
+ *           hs_tree_prune defines it; HS_PSTAR_LOCAL: the largest min(logc, 0)); ties -> lower row
+ *   phi     sum of ent[a] over the strict ancestors a of P*, root first, in float32: ent[a] is the
+ *           Top-K entropy of the draft distribution at a (hs_draft_entropy_topk's ent_topk of its row)
+ *   bin     number of boundaries host_bin_edges[0 .. n_bins-2] (ascending) that phi has reached
+ *   Delta   max(alpha - bin, 0) if bin < n_low, else 0
+ *   d_prime = d_base + Delta
+ *   n_prime = floor((double)host_gamma[bin] * n_default + 0.5) + Delta if bin < n_low, else n_default
+ * Outputs phi float [B]; pstar (local row, -1 for an empty sequence), bin, d_prime, n_prime int32 [B]:
+ * d_prime / n_prime can be handed to hs_tree_expand (d_limit) and hs_tree_prune (d_max, max_nodes)
+ * without leaving the device.  host_bin_edges and host_gamma are HOST arrays, read during the call.
+ * Requires 1 <= n_bins <= 64, 0 <= n_low <= min(8, n_bins).  No workspace.
+ */
+hs_status hs_adaptive_control(const int32_t* parent, const float* logc, const float* ent,
+                              const int32_t* node_offsets, const int32_t* node_counts,
+                              int32_t B, int32_t NN,
+                              const float* host_bin_edges, int32_t n_bins,
+                              const float* host_gamma, int32_t n_low,
+                              int32_t alpha, int32_t d_base, int32_t n_default, hs_pstar_mode mode,
+                              float* phi, int32_t* pstar, int32_t* bin, int32_t* d_prime,
+                              int32_t* n_prime, hs_stream stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libheterospec.so")
 
 HS_F32, HS_BF16 = 0, 1
 HS_ACCEPT_GREEDY, HS_ACCEPT_STOCHASTIC, HS_ACCEPT_STOCHASTIC_POINTMASS = 0, 1, 2
+HS_PSTAR_CUMULATIVE, HS_PSTAR_LOCAL = 0, 1
 HS_MAX_TOPK = 64
 
 _c = ctypes
@@ -30,6 +31,11 @@ _SIGNATURES = {
     "hs_draft_entropy_topk": (_c.c_int, [_vp, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "hs_tree_prune_workspace": (_sz, [_i32, _i32]),
     "hs_tree_prune": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "hs_tree_prune_counted": (_c.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                         _sz, _vp]),
+    "hs_tree_expand": (_c.c_int, [_vp] * 15 + [_i32] * 5 + [_vp]),
+    "hs_adaptive_control": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i32, _vp, _i32, _i32, _i32, _i32,
+                                       _c.c_int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "hs_tree_attention_workspace": (_sz, [_i32, _i32, _i64, _i32, _i32, _i32, _c.c_int]),
     "hs_tree_attention": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                      _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
@@ -120,11 +126,15 @@ def hs_draft_entropy_topk(logits: torch.Tensor, K: int, temperature: float = 1.0
 
 
 def hs_tree_prune(parent: torch.Tensor, logc: torch.Tensor, node_offsets: torch.Tensor, d_max: torch.Tensor,
-                  theta: torch.Tensor, max_nodes: torch.Tensor, *, out: Optional[Dict[str, torch.Tensor]] = None,
+                  theta: torch.Tensor, max_nodes: torch.Tensor, *, node_counts: Optional[torch.Tensor] = None,
+                  out: Optional[Dict[str, torch.Tensor]] = None,
                   ws: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
     """All arguments are GPU tensors: parent int32 [NN], logc float32 [NN], node_offsets int32 [B+1],
     d_max int32 [B], theta float32 [B], max_nodes int32 [B].  Returns depth, cumlogp, keep, out_offsets,
-    out_src, out_parent (the last two sized NN; the first out_offsets[B] entries are valid)."""
+    out_src, out_parent (the last two sized NN; the first out_offsets[B] entries are valid).
+    With node_counts int32 [B] the call is hs_tree_prune_counted (trees stored with spare capacity)."""
+    if node_counts is not None:
+        _dev(node_counts, torch.int32, "node_counts")
     _dev(parent, torch.int32, "parent"); _dev(logc, torch.float32, "logc")
     _dev(node_offsets, torch.int32, "node_offsets"); _dev(d_max, torch.int32, "d_max")
     _dev(theta, torch.float32, "theta"); _dev(max_nodes, torch.int32, "max_nodes")
@@ -140,11 +150,76 @@ def hs_tree_prune(parent: torch.Tensor, logc: torch.Tensor, node_offsets: torch.
     need = lib().hs_tree_prune_workspace(B, NN)
     if ws is None:
         ws = workspace(need, dev)
-    st = lib().hs_tree_prune(_ptr(parent), _ptr(logc), _ptr(node_offsets), B, NN, _ptr(d_max), _ptr(theta),
-                             _ptr(max_nodes), _ptr(out["depth"]), _ptr(out["cumlogp"]), _ptr(out["keep"]),
-                             _ptr(out["out_offsets"]), _ptr(out["out_src"]), _ptr(out["out_parent"]),
-                             _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
+    tail = (_ptr(d_max), _ptr(theta), _ptr(max_nodes), _ptr(out["depth"]), _ptr(out["cumlogp"]), _ptr(out["keep"]),
+            _ptr(out["out_offsets"]), _ptr(out["out_src"]), _ptr(out["out_parent"]),
+            _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
+    if node_counts is None:
+        st = lib().hs_tree_prune(_ptr(parent), _ptr(logc), _ptr(node_offsets), B, NN, *tail)
+    else:
+        st = lib().hs_tree_prune_counted(_ptr(parent), _ptr(logc), _ptr(node_offsets), _ptr(node_counts), B, NN, *tail)
     _check(st, "hs_tree_prune")
+    return out
+
+
+def new_tree_state(B: int, cap: int, F: int, device) -> Dict[str, torch.Tensor]:
+    """Device arrays of hs_tree_expand's draft-tree state (uninitialised: the first call initialises them)."""
+    i32 = dict(dtype=torch.int32, device=device)
+    f32 = dict(dtype=torch.float32, device=device)
+    return dict(parent=torch.empty(B * cap, **i32), token=torch.empty(B * cap, **i32), depth=torch.empty(B * cap, **i32),
+                logc=torch.empty(B * cap, **f32), cumlogp=torch.empty(B * cap, **f32), ent=torch.empty(B * cap, **f32),
+                n_nodes=torch.empty(B, **i32), level=torch.empty(B, **i32), frontier=torch.empty(B * F, **i32),
+                n_frontier=torch.empty(B, **i32), frontier_rows=torch.empty(B * F, **i32),
+                node_offsets=(torch.arange(B + 1, dtype=torch.int64) * cap).to(torch.int32).to(device))
+
+
+def hs_tree_expand(state: Dict[str, torch.Tensor], topk_idx, topk_logp, ent_topk, d_limit, B: int, cap: int, F: int,
+                   K: int, first: bool, *, stream=None) -> Dict[str, torch.Tensor]:
+    """state: the tensors of new_tree_state(); topk_idx int32 [B*F, K], topk_logp float32 [B*F, K], ent_topk
+    float32 [B*F] (hs_draft_entropy_topk's results for the frontier slots); d_limit int32 [B] or None."""
+    _dev(topk_idx, torch.int32, "topk_idx"); _dev(topk_logp, torch.float32, "topk_logp")
+    _dev(ent_topk, torch.float32, "ent_topk")
+    if topk_idx.numel() < B * F * K or ent_topk.numel() < B * F:
+        raise ValueError("Top-K results must cover B * F frontier slots")
+    if d_limit is not None:
+        _dev(d_limit, torch.int32, "d_limit")
+    for k in ("parent", "token", "depth", "n_nodes", "level", "frontier", "n_frontier", "frontier_rows"):
+        _dev(state[k], torch.int32, k)
+    for k in ("logc", "cumlogp", "ent"):
+        _dev(state[k], torch.float32, k)
+    if state["parent"].numel() < B * cap or state["frontier"].numel() < B * F:
+        raise ValueError("state arrays are smaller than B * cap / B * F")
+    st = lib().hs_tree_expand(_ptr(state["parent"]), _ptr(state["token"]), _ptr(state["logc"]), _ptr(state["cumlogp"]),
+                              _ptr(state["depth"]), _ptr(state["ent"]), _ptr(state["n_nodes"]), _ptr(state["level"]),
+                              _ptr(state["frontier"]), _ptr(state["n_frontier"]), _ptr(state["frontier_rows"]),
+                              _ptr(topk_idx), _ptr(topk_logp), _ptr(ent_topk), _ptr(d_limit), B, cap, F, K,
+                              1 if first else 0, _stream(stream))
+    _check(st, "hs_tree_expand")
+    return state
+
+
+def hs_adaptive_control(parent, logc, ent, node_offsets, node_counts, bin_edges, gamma, alpha: int, d_base: int,
+                        n_default: int, mode: int = 0, *, out: Optional[Dict[str, torch.Tensor]] = None,
+                        stream=None) -> Dict[str, torch.Tensor]:
+    """parent int32 [NN], logc / ent float32 [NN], node_offsets int32 [B+1], node_counts int32 [B] or None (GPU);
+    bin_edges (ascending, n_bins - 1 values) and gamma are host sequences of floats.
+    Returns phi float32 [B] and pstar, bin, d_prime, n_prime int32 [B]."""
+    _dev(parent, torch.int32, "parent"); _dev(logc, torch.float32, "logc"); _dev(ent, torch.float32, "ent")
+    _dev(node_offsets, torch.int32, "node_offsets")
+    if node_counts is not None:
+        _dev(node_counts, torch.int32, "node_counts")
+    B, NN = node_offsets.numel() - 1, parent.numel()
+    dev = parent.device
+    edges = (_f32 * max(1, len(bin_edges)))(*[float(x) for x in bin_edges])
+    gam = (_f32 * max(1, len(gamma)))(*[float(x) for x in gamma])
+    if out is None:
+        out = dict(phi=torch.empty(B, dtype=torch.float32, device=dev))
+        for k in ("pstar", "bin", "d_prime", "n_prime"):
+            out[k] = torch.empty(B, dtype=torch.int32, device=dev)
+    st = lib().hs_adaptive_control(_ptr(parent), _ptr(logc), _ptr(ent), _ptr(node_offsets), _ptr(node_counts), B, NN,
+                                   _c.cast(edges, _vp), len(bin_edges) + 1, _c.cast(gam, _vp), len(gamma), int(alpha),
+                                   int(d_base), int(n_default), int(mode), _ptr(out["phi"]), _ptr(out["pstar"]),
+                                   _ptr(out["bin"]), _ptr(out["d_prime"]), _ptr(out["n_prime"]), _stream(stream))
+    _check(st, "hs_adaptive_control")
     return out
 
 

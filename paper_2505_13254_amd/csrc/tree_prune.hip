@@ -201,7 +201,7 @@ __device__ __forceinline__ void prune_sequence(
 
 __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
     const int32_t* __restrict__ parent, const float* __restrict__ logc, const int32_t* __restrict__ node_offsets,
-    const int32_t* __restrict__ d_max, const float* __restrict__ theta, const int32_t* __restrict__ max_nodes,
+    const int32_t* __restrict__ node_counts, const int32_t* __restrict__ d_max, const float* __restrict__ theta, const int32_t* __restrict__ max_nodes,
     int32_t* __restrict__ depth, float* __restrict__ cumlogp, uint8_t* __restrict__ keep,
     int32_t* __restrict__ ws_pos, int32_t* __restrict__ ws_count, int32_t* __restrict__ ws_flag,
     int32_t* __restrict__ out_offsets, int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent) {
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
 
   const int s = blockIdx.x, tid = threadIdx.x;
   const int o = node_offsets[s];
-  const int n = node_offsets[s + 1] - o;
+  const int n = node_counts != nullptr ? node_counts[s] : node_offsets[s + 1] - o;
   if (n <= 0) {
     if (tid == 0) {
       ws_count[s] = 0;
@@ -247,7 +247,8 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
 }
 
 __global__ __launch_bounds__(PR_THREADS) void k_prune_emit(const int32_t* __restrict__ parent,
-                                                           const int32_t* __restrict__ node_offsets, int B,
+                                                           const int32_t* __restrict__ node_offsets,
+                                                           const int32_t* __restrict__ node_counts, int B,
                                                            const int32_t* __restrict__ ws_pos,
                                                            const int32_t* __restrict__ ws_count,
                                                            int32_t* __restrict__ out_offsets,
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_emit(const int32_t* __rest
     if (s == B - 1) out_offsets[B] = base + ws_count[s];
   }
   const int o = node_offsets[s];
-  const int n = node_offsets[s + 1] - o;
+  const int n = node_counts != nullptr ? node_counts[s] : node_offsets[s + 1] - o;
   for (int i = tid; i < n; i += PR_THREADS) {
     const int p = ws_pos[o + i];
     if (p >= 0) {
@@ -281,11 +282,12 @@ extern "C" size_t hs_tree_prune_workspace(int32_t B, int32_t NN) {
          hs::align_up((size_t)B * sizeof(int32_t), 256);
 }
 
-extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, const int32_t* node_offsets, int32_t B,
-                                   int32_t NN, const int32_t* d_max, const float* theta, const int32_t* max_nodes,
-                                   int32_t* depth, float* cumlogp, uint8_t* keep, int32_t* out_offsets,
-                                   int32_t* out_src, int32_t* out_parent, void* workspace, size_t workspace_bytes,
-                                   hs_stream stream) {
+extern "C" hs_status hs_tree_prune_counted(const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                                           const int32_t* node_counts, int32_t B, int32_t NN, const int32_t* d_max,
+                                           const float* theta, const int32_t* max_nodes, int32_t* depth,
+                                           float* cumlogp, uint8_t* keep, int32_t* out_offsets, int32_t* out_src,
+                                           int32_t* out_parent, void* workspace, size_t workspace_bytes,
+                                           hs_stream stream) {
   hs::clear_error();
   HS_REQUIRE(B >= 0 && NN >= 0, HS_ERR_SHAPE, "hs_tree_prune: B=%d NN=%d", B, NN);
   if (B == 0) return HS_OK;
@@ -301,14 +303,23 @@ extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, con
   int32_t* ws_flag = c.take<int32_t>(NN > 0 ? NN : 1);
   int32_t* ws_count = c.take<int32_t>(B);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL(hs::k_prune_select, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, logc, node_offsets, d_max,
-                     theta, max_nodes, depth, cumlogp, keep, ws_pos, ws_count, ws_flag, out_offsets, out_src,
+  hipLaunchKernelGGL(hs::k_prune_select, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, logc, node_offsets, node_counts,
+                     d_max, theta, max_nodes, depth, cumlogp, keep, ws_pos, ws_count, ws_flag, out_offsets, out_src,
                      out_parent);
   hs_status r = hs::launch_status("prune select");
   if (r != HS_OK) return r;
   // a single tree that fits LDS was emitted by the selecting workgroup itself
   if (B == 1 && NN <= hs::PR_LDS_NODES) return r;
-  hipLaunchKernelGGL(hs::k_prune_emit, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, node_offsets, B, ws_pos,
-                     ws_count, out_offsets, out_src, out_parent);
+  hipLaunchKernelGGL(hs::k_prune_emit, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, node_offsets, node_counts, B,
+                     ws_pos, ws_count, out_offsets, out_src, out_parent);
   return hs::launch_status("prune emit");
+}
+
+extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, const int32_t* node_offsets, int32_t B,
+                                   int32_t NN, const int32_t* d_max, const float* theta, const int32_t* max_nodes,
+                                   int32_t* depth, float* cumlogp, uint8_t* keep, int32_t* out_offsets,
+                                   int32_t* out_src, int32_t* out_parent, void* workspace, size_t workspace_bytes,
+                                   hs_stream stream) {
+  return hs_tree_prune_counted(parent, logc, node_offsets, nullptr, B, NN, d_max, theta, max_nodes, depth, cumlogp,
+                               keep, out_offsets, out_src, out_parent, workspace, workspace_bytes, stream);
 }
