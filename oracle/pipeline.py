@@ -212,3 +212,37 @@ def safe_uniforms(step, mode, rel=1e-4, cdf_abs=1e-5, tries=64):
         if ok:
             return u, base
     raise RuntimeError("no margin-safe uniforms found")
+
+
+# ----------------------------------------------------------------------------- the adaptive step
+def adaptive_step(w, seed, edges, gamma, alpha, logp_dtype=np.float32):
+    """The whole adaptive step of a single-sequence expansion workload with the checker: base
+    drafting to w.max_depth levels, complexity decision, extended drafting, pruning to the decided
+    budget, greedy accept walk (Sections 4.1 - 4.3 around the Section 2.2 tree).  Confidences are
+    rounded to `logp_dtype` before they enter the tree, as the library's are."""
+    from .tree_expand import new_state, tree_expand
+    from .adaptive_control import adaptive_control
+    K, F, d_base = w.topk, w.frontier, w.max_depth
+    cap = 1 + K + (d_base + alpha - 1) * F * K
+    st = new_state()
+
+    def level():
+        x = W.logits_rows(w, seed, "draft", 0, st["frontier"])
+        r = draft_entropy_topk(x, K, w.temperature)
+        tree_expand(st, r["topk_idx"], r["topk_logp"].astype(logp_dtype), r["ent_topk"].astype(np.float32), F, cap)
+
+    for _ in range(d_base):
+        level()
+    n = len(st["parent"])
+    ctl = adaptive_control(st["parent"], st["logc"], st["ent"], [0, n], edges, gamma, alpha, d_base, w.max_nodes, 0)
+    d_prime, n_prime = int(ctl["d_prime"][0]), int(ctl["n_prime"][0])
+    for _ in range(d_prime - d_base):
+        level()
+    n = len(st["parent"])
+    pr = tree_prune(np.asarray(st["parent"], np.int32), np.asarray(st["logc"], np.float32), [0, n], [d_prime],
+                    [w.theta[0]], [n_prime])
+    src = pr["out_src"]
+    token = np.asarray(st["token"], np.int32)[src]
+    tgt = W.logits_rows(w, seed, "target", 0, src)
+    acc = verify_accept(tgt, None, token, pr["out_parent"], pr["out_offsets"], GREEDY, w.temperature, None, d_prime)
+    return dict(state=st, control=ctl, prune=pr, token=token, accept=acc)

@@ -18,34 +18,46 @@
 // All decisions compare raw float32 logits under the strict order (value descending, index
 // ascending), so the indices do not depend on how rows are split or reduced.
 #include <limits.h>
+#include <stdlib.h>
 
 #include "hs_common.h"
 
 namespace hs {
 
-constexpr int SCAN_THREADS = 1024;
-constexpr int SCAN_WAVES = SCAN_THREADS / 64;
+// The row scan is built for two workgroup sizes.  Sixteen waves: fewest slices to merge, best
+// for a few dozen rows.  Four waves, several workgroups per compute unit: the workgroups' set-up,
+// merge and write-out phases overlap with other workgroups' streaming, best for many rows (and
+// for very few, where a row is cut into many short slices anyway).
+constexpr int SCAN_BIG = 1024, SCAN_SMALL = 256;
 constexpr int SCAN_VPT = 16;                        // values per thread per tile (4 x float4)
-constexpr int SCAN_TILE = SCAN_THREADS * SCAN_VPT;  // 16384 logits per workgroup tile
+constexpr int scan_tile(int threads) { return threads * SCAN_VPT; }  // logits per workgroup tile
 constexpr int FIN_THREADS = 256;
-constexpr int FIN_CAP = HS_MAX_TOPK * HS_MAX_TOPK;  // candidates the merge can face
+constexpr int FIN_CAP = HS_MAX_TOPK * HS_MAX_TOPK;  // candidates the merge of 64 slices can face
 constexpr int MAX_SPLITS = 64;                       // slices per row (one list head per lane)
-constexpr int SCAN_TARGET_WGS = 256;                 // rows are sliced until about one workgroup per compute unit exists
+constexpr int SCAN_TARGET_WGS = 256;                 // rows are sliced until about one 16-wave workgroup per compute unit exists
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct ScanPlan {
+  int threads;       // workgroup size
   int splits;        // workgroups per row
   int tiles_per_wg;  // tiles each of them scans
 };
 
 static ScanPlan plan_scan(int R, int V) {
-  const int n_tiles = (V + SCAN_TILE - 1) / SCAN_TILE;
-  // few rows: slice them until about one workgroup per compute unit exists (measured best)
-  int want = SCAN_TARGET_WGS / (R > 0 ? R : 1);
+  ScanPlan p;
+  p.threads = (R >= 256 || R <= 16) ? SCAN_SMALL : SCAN_BIG;  // measured on MI355X
+  const int tile = scan_tile(p.threads);
+  const int n_tiles = (V + tile - 1) / tile;
+  // few rows: slice them until the chip is full (measured best)
+  int want = SCAN_TARGET_WGS * (SCAN_BIG / p.threads) / (R > 0 ? R : 1);
+  static const int forced = [] {
+    const char* e = getenv("HS_SCAN_SPLITS");  // tuning aid: fixes the slices per row
+    return e ? atoi(e) : 0;
+  }();
+  if (forced > 0) want = forced;
   if (want > n_tiles) want = n_tiles;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
   if (want < 1) want = 1;
-  ScanPlan p;
   p.tiles_per_wg = (n_tiles + want - 1) / want;
   p.splits = (n_tiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
   return p;
@@ -75,6 +87,19 @@ __device__ __forceinline__ void list_insert(float xv, int xi, float& lv, int& li
   li = beats ? (left_beaten ? left_i : xi) : li;
 }
 
+// Maximum of each row of 16 lanes; lane 15 of a row holds it.
+__device__ __forceinline__ float row16_max(float x) {
+  const int id = __builtin_bit_cast(int, -HS_INF);
+#define HS_DPP_STEP(ctrl, banks) \
+  x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(id, __builtin_bit_cast(int, x), ctrl, 0xf, banks, false)))
+  HS_DPP_STEP(0x111, 0xf);  // row_shr:1
+  HS_DPP_STEP(0x112, 0xf);  // row_shr:2
+  HS_DPP_STEP(0x114, 0xe);  // row_shr:4
+  HS_DPP_STEP(0x118, 0xc);  // row_shr:8
+#undef HS_DPP_STEP
+  return x;
+}
+
 // Statistics of a wave's 64 lanes in one: the common maximum first, then plain sums of the lanes'
 // terms rescaled to it.  The lowest lane that holds the maximum keeps its own maximum's unit out of
 // s1 (as each lane did for itself); for every other lane that unit is an ordinary term.
@@ -95,10 +120,11 @@ __device__ __forceinline__ Stats stats_wave_sum(Stats a, float inv_t) {
 }
 
 // Scratch of the merges (shared memory).
+template <int CAP>
 struct MergeScratch {
-  float cv[FIN_CAP];  // candidates
-  int ci[FIN_CAP];
-  int rank[FIN_CAP];
+  float cv[CAP];  // candidates
+  int ci[CAP];
+  int rank[CAP];
   float ov[HS_MAX_TOPK];  // the K best of them, in order
   int oi[HS_MAX_TOPK];
   int cnt;
@@ -112,7 +138,8 @@ struct MergeScratch {
 // candidate's opponents are shared out among P threads, which add up their counts in LDS.
 // Called by all `nthreads` threads (a power of two); sm.rank[0, n) must be zero on entry (a barrier
 // before the call); ends with a barrier.
-__device__ __forceinline__ void rank_candidates(MergeScratch& sm, int n, int K, int tid, int nthreads) {
+template <int CAP>
+__device__ __forceinline__ void rank_candidates(MergeScratch<CAP>& sm, int n, int K, int tid, int nthreads) {
   int shift = 0;  // P = 2^shift threads per candidate
   while (n > 0 && (n << (shift + 1)) <= nthreads) ++shift;
   const int P = 1 << shift;
@@ -143,8 +170,9 @@ __device__ __forceinline__ void rank_candidates(MergeScratch& sm, int n, int K, 
 // Merges S <= 64 slices of a row: statistics st[s] (m, s1, t) and sorted K-lists pv/pi[s * K + k].
 // Leaves the row's statistics in sm.total and its K best pairs, in order, in sm.ov / sm.oi.
 // Called by all `nthreads` threads of the workgroup (tid 0..nthreads-1); ends with a barrier.
+template <int CAP>
 __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, const int* pi, int S, int K,
-                                             float inv_t, MergeScratch& sm, int tid, int nthreads) {
+                                             float inv_t, MergeScratch<CAP>& sm, int tid, int nthreads) {
   const int lane = tid & 63;
   for (int e = tid; e < S * K; e += nthreads) sm.rank[e] = 0;
   if (tid < 64) {
@@ -196,7 +224,8 @@ __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, 
 }
 
 // Writes a row's results from its merged statistics and Top-K list (first wave of the workgroup).
-__device__ __forceinline__ void write_row(const MergeScratch& sm, int64_t row, int K, float inv_t,
+template <int CAP>
+__device__ __forceinline__ void write_row(const MergeScratch<CAP>& sm, int64_t row, int K, float inv_t,
                                           int32_t* __restrict__ topk_idx, float* __restrict__ topk_logp,
                                           float* __restrict__ ent_topk, float* __restrict__ ent_full,
                                           float* __restrict__ lse, int tid) {
@@ -232,7 +261,7 @@ __device__ __forceinline__ void write_row(const MergeScratch& sm, int64_t row, i
 
 // grid (S, R): slice `blockIdx.x` of row `blockIdx.y`.  S == 1: the outputs are written here;
 // S > 1: the slice's statistics and K-list go to part_* for k_scan_finalize.
-template <bool VEC>
+template <bool VEC, int SCAN_THREADS>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restrict__ logits, int64_t row_stride,
                                                             int V, int K, float inv_t, int tiles_per_wg,
                                                             float4* __restrict__ part_stats,
@@ -241,9 +270,13 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
                                                             float* __restrict__ topk_logp,
                                                             float* __restrict__ ent_topk,
                                                             float* __restrict__ ent_full, float* __restrict__ lse) {
+  constexpr int SCAN_WAVES = SCAN_THREADS / 64;
+  constexpr int SCAN_GROUPS = SCAN_WAVES * 4 < 64 ? SCAN_WAVES * 4 : 64;  // rows of 16 lanes, at most one per lane
+  constexpr int SCAN_TILE = scan_tile(SCAN_THREADS);
+  constexpr int SCAN_CAP = SCAN_WAVES * HS_MAX_TOPK;  // candidates the merge of the waves can face
   __shared__ float4 wave_st[SCAN_WAVES];
-  __shared__ float wave_maxima[SCAN_WAVES];
-  __shared__ MergeScratch sm;
+  __shared__ float group_maxima[SCAN_GROUPS];
+  __shared__ MergeScratch<SCAN_CAP> sm;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x, S = gridDim.x, row = blockIdx.y;
@@ -281,15 +314,29 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
       }
     }
   };
+  // a tile that lies inside the row as a whole (aligned rows): four loads, no conditions, so the
+  // compiler can count them when it waits for an older tile
+  auto load_full_tile = [&](int tile, float (&v)[SCAN_VPT]) {
+    const float* __restrict__ src = x + (int64_t)(split * tiles_per_wg + tile) * SCAN_TILE + tid * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float4 f = *reinterpret_cast<const float4*>(src + j * SCAN_THREADS * 4);
+      v[j * 4 + 0] = f.x;
+      v[j * 4 + 1] = f.y;
+      v[j * 4 + 2] = f.z;
+      v[j * 4 + 3] = f.w;
+    }
+  };
   // tiles this workgroup really has (uniform)
   int n_my = (V - split * tiles_per_wg * SCAN_TILE + SCAN_TILE - 1) / SCAN_TILE;
   n_my = n_my < 0 ? 0 : (n_my > tiles_per_wg ? tiles_per_wg : n_my);
+  int n_full = VEC ? (V - split * tiles_per_wg * SCAN_TILE) / SCAN_TILE : 0;  // leading whole tiles
+  n_full = n_full < 0 ? 0 : (n_full > n_my ? n_my : n_full);
 
-  float v[SCAN_VPT], vn[SCAN_VPT];
-  if (n_my > 0) load_tile(0, v);
-  for (int tile = 0; tile < n_my; ++tile) {
+  // One tile: statistics of this thread's 16 values, threshold, insertion of the few values that
+  // reach it.
+  auto process = [&](const float (&v)[SCAN_VPT], int tile) {
     const int tbase = (split * tiles_per_wg + tile) * SCAN_TILE;
-    if (tile + 1 < n_my) load_tile(tile + 1, vn);  // next tile's loads fly while this one is processed
 #define HS_IDX(jj) (tbase + (((jj) >> 2) * SCAN_THREADS + tid) * 4 + ((jj)&3))
 
     // ---- softmax statistics of this thread's values
@@ -324,13 +371,21 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     // the K-th largest of the 16 waves' maxima (K <= 16; K elements of the tile reach it), or of
     // this wave's 64 lane maxima; afterwards also the wave's own K-th entry once its list is full.
     if (tile == 0) {
-      if (K <= SCAN_WAVES) {
-        const float wm = wave_max(tm);
-        if (lane == 0) wave_maxima[wave] = wm;
+      if (K <= SCAN_GROUPS) {
+        // maxima of the waves, or of their rows of 16 lanes when there are fewer waves than K
+        const bool by_wave = K <= SCAN_WAVES;
+        const int n_groups = by_wave ? SCAN_WAVES : SCAN_GROUPS;
+        if (by_wave) {
+          const float wm = wave_max(tm);
+          if (lane == 0) group_maxima[wave] = wm;
+        } else {
+          const float rm = row16_max(tm);
+          if ((lane & 15) == 15) group_maxima[wave * 4 + (lane >> 4)] = rm;
+        }
         __syncthreads();
-        const float mine = lane < SCAN_WAVES ? wave_maxima[lane] : -HS_INF;
-        const int r = wave_rank(mine, lane, SCAN_WAVES);
-        const unsigned long long who = __ballot(r == K - 1 && lane < SCAN_WAVES);
+        const float mine = lane < n_groups ? group_maxima[lane] : -HS_INF;
+        const int r = wave_rank(mine, lane, n_groups);
+        const unsigned long long who = __ballot(r == K - 1 && lane < n_groups);
         thr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine), __ffsll((long long)who) - 1));
       } else {
         const int r = wave_rank(tm, lane, 64);
@@ -360,8 +415,34 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
       }
     }
 #undef HS_IDX
-#pragma unroll
-    for (int jj = 0; jj < SCAN_VPT; ++jj) v[jj] = vn[jj];
+  };
+  // Three register buffers, two tiles in flight: the loads of tile t + 2 are requested before tile
+  // t is processed (one workgroup per compute unit: what is in flight bounds the bandwidth).  The
+  // steady-state loop requests without a condition, so that the wait before a tile's values counts
+  // exactly the two younger tiles; the last tiles run through the guarded copy below.
+  float b0[SCAN_VPT], b1[SCAN_VPT], b2[SCAN_VPT];
+  if (n_my > 0) load_tile(0, b0);
+  if (n_my > 1) load_tile(1, b1);
+  int tile = 0;
+  for (; tile + 4 < n_full; tile += 3) {
+    load_full_tile(tile + 2, b2);
+    process(b0, tile);
+    load_full_tile(tile + 3, b0);
+    process(b1, tile + 1);
+    load_full_tile(tile + 4, b1);
+    process(b2, tile + 2);
+  }
+  for (; tile < n_my; tile += 3) {
+    if (tile + 2 < n_my) load_tile(tile + 2, b2);
+    process(b0, tile);
+    if (tile + 1 < n_my) {
+      if (tile + 3 < n_my) load_tile(tile + 3, b0);
+      process(b1, tile + 1);
+    }
+    if (tile + 2 < n_my) {
+      if (tile + 4 < n_my) load_tile(tile + 4, b1);
+      process(b2, tile + 2);
+    }
   }
 
   // ---- the waves' statistics and the real entries of their lists meet in LDS
@@ -411,7 +492,7 @@ __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __r
                                                                float* __restrict__ ent_topk,
                                                                float* __restrict__ ent_full,
                                                                float* __restrict__ lse) {
-  __shared__ MergeScratch sm;
+  __shared__ MergeScratch<FIN_CAP> sm;
   const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
   merge_slices(part_stats + row * S, part_val + row * S * K, part_idx + row * S * K, S, K, inv_t, sm, tid, FIN_THREADS);
@@ -437,12 +518,17 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   const float inv_t = 1.0f / temperature;
   const bool vec = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 4 == 0);
   dim3 grid(p.splits, R);
-  if (vec)
-    hipLaunchKernelGGL(k_scan_rows<true>, grid, dim3(SCAN_THREADS), 0, stream, logits, row_stride, V, K, inv_t,
-                       p.tiles_per_wg, part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse);
-  else
-    hipLaunchKernelGGL(k_scan_rows<false>, grid, dim3(SCAN_THREADS), 0, stream, logits, row_stride, V, K, inv_t,
-                       p.tiles_per_wg, part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse);
+#define HS_SCAN_LAUNCH(VEC, T)                                                                                      \
+  hipLaunchKernelGGL((k_scan_rows<VEC, T>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
+                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse)
+  if (p.threads == SCAN_BIG) {
+    if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG);
+    else HS_SCAN_LAUNCH(false, SCAN_BIG);
+  } else {
+    if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL);
+    else HS_SCAN_LAUNCH(false, SCAN_SMALL);
+  }
+#undef HS_SCAN_LAUNCH
   hs_status st = launch_status("row scan");
   if (st != HS_OK || p.splits == 1) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,

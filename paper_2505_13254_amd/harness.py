@@ -271,3 +271,194 @@ def build_step(w: W.Workload, seed: int = 0, layers: Optional[int] = None, accep
     t["s3_ws"] = hs.workspace(hs.lib().hs_tree_attention_workspace(
         nb, int(no[-1]), int(po[-1]), w.Hq, w.Hkv, w.D, hs.HS_F32 if w.dtype == "f32" else hs.HS_BF16), device)
     return st
+
+
+# ------------------------------------------------------------------------------------------------
+# The adaptive step, device-driven: Top-K growth level by level (hs_tree_expand), complexity
+# quantification and decision (hs_adaptive_control), extended drafting, pruning to the decided
+# budget, verification.  The host reads one number per step, the entropy bin, and replays the HIP
+# graph specialised for that bin (Section 4.3, Dynamic Computational Adaptation: one cached
+# computation graph per complexity region).
+@dataclass
+class AdaptiveStep:
+    w: W.Workload
+    layers: int
+    d_base: int
+    alpha: int
+    n_default: int
+    edges: List[float]
+    gamma: List[float]
+    t: Dict[str, object] = field(default_factory=dict)
+    host: Dict[str, object] = field(default_factory=dict)
+    graphs: Dict[object, object] = field(default_factory=dict)
+
+    # ---- what the bins mean (Section 4.3), on the host: which graph to replay
+    def decision(self, b: int):
+        low = b < len(self.gamma)
+        delta = max(self.alpha - b, 0) if low else 0
+        n = (int(np.floor(np.float64(np.float32(self.gamma[b])) * self.n_default + 0.5)) + delta) if low \
+            else self.n_default
+        return self.d_base + delta, n
+
+    # ---- pieces, each a few library calls on device-resident data
+    def _level(self, first: bool):
+        t, w, h = self.t, self.w, self.host
+        if first:
+            x = t["x_root"]
+        else:
+            # stands in for the draft model's pass over the frontier: its logits rows are gathered
+            # from the pre-generated rows of all candidates
+            x = torch.index_select(t["draft_all"], 0, t["state"]["frontier_rows"], out=t["x_slots"])
+        r = hs.hs_draft_entropy_topk(x, w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"])
+        hs.hs_tree_expand(t["state"], r["topk_idx"], r["topk_logp"], r["ent_topk"], None, 1, h["cap"], w.frontier,
+                          w.topk, first=first)
+
+    def run_draft(self):
+        """Base drafting to d_base levels, then the complexity decision (device only)."""
+        t, h = self.t, self.host
+        for lvl in range(self.d_base):
+            self._level(lvl == 0)
+        st = t["state"]
+        hs.hs_adaptive_control(st["parent"], st["logc"], st["ent"], st["node_offsets"], st["n_nodes"], self.edges,
+                               self.gamma, self.alpha, self.d_base, self.n_default, 0, out=t["ctl"])
+
+    def run_verify(self, b: int):
+        """Extended drafting for bin b, pruning to the decided budget, attention on all layers, accept."""
+        t, h, w = self.t, self.host, self.w
+        d_prime, n_prime = self.decision(b)
+        for _ in range(d_prime - self.d_base):
+            self._level(False)
+        st, ctl = t["state"], t["ctl"]
+        hs.hs_tree_prune(st["parent"], st["logc"], st["node_offsets"], ctl["d_prime"], t["theta"], ctl["n_prime"],
+                         node_counts=st["n_nodes"], out=t["s2_out"], ws=t["s2_ws"])
+        M = n_prime + 1
+        a = t["attn"][M]
+        src = t["s2_out"]["out_src"][:M]
+        par = t["s2_out"]["out_parent"][:M]
+        a["parent"].view(self.layers, M).copy_(par)
+        hs.hs_tree_attention(a["q"], t["k_prefix"], t["v_prefix"], a["k_tree"], a["v_tree"], a["parent"],
+                             a["node_offsets"], t["prefix_offsets"], a["host_node_offsets"], h["prefix_offsets"],
+                             h["scale"], out=a["o"], ws=a["ws"])
+        # stands in for the target model's output rows of the kept nodes
+        torch.index_select(st["token"], 0, src, out=a["token"])
+        torch.index_select(t["target_all"], 0, src, out=a["target"])
+        hs.hs_verify_accept(a["target"], None, a["token"], par, t["s2_out"]["out_offsets"], 0, w.temperature, None,
+                            d_prime, out=a["s4_out"], ws=a["s4_ws"])
+
+    def read_bin(self) -> int:
+        return int(self.t["ctl"]["bin"].cpu()[0])
+
+    # ---- HIP graphs: one for the drafting part, one per bin for the rest
+    def capture(self, bins=None):
+        pool = None
+        self.run_draft()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.run_draft()
+        self.graphs["draft"] = g
+        for b in (bins if bins is not None else range(len(self.edges) + 1)):
+            key = self.decision(b)
+            if key in self.graphs:
+                self.graphs[b] = self.graphs[key]
+                continue
+            self.run_draft()
+            self.run_verify(b)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self.run_verify(b)
+            self.graphs[key] = self.graphs[b] = g
+
+    def step_eager(self) -> int:
+        self.run_draft()
+        b = self.read_bin()
+        self.run_verify(b)
+        return b
+
+    def step_graph(self) -> int:
+        self.graphs["draft"].replay()
+        b = self.read_bin()
+        self.graphs[b].replay()
+        return b
+
+    def result(self, b: int):
+        d_prime, n_prime = self.decision(b)
+        a = self.t["attn"][n_prime + 1]
+        torch.cuda.synchronize()
+        return dict(bin=b, d_prime=d_prime, n_prime=n_prime,
+                    accept_len=int(a["s4_out"]["accept_len"].cpu()[0]),
+                    bonus_token=int(a["s4_out"]["bonus_token"].cpu()[0]))
+
+
+def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, edges=None, gamma=(0.3, 0.6, 1.0),
+                   alpha: Optional[int] = None, device="cuda:0") -> AdaptiveStep:
+    """Single-sequence workloads grown by Top-K expansion (the 8B shape).  edges: the seven bin
+    boundaries of the eight entropy bins (synthetic: the paper prints none)."""
+    if w.B != 1 or w.tree != "expand":
+        raise ValueError("the adaptive step is built for single-sequence Top-K expansion workloads")
+    layers = layers or 1
+    d_base, K, F = w.max_depth, w.topk, w.frontier
+    alpha = alpha if alpha is not None else -(-d_base // 2)          # ceil(depth / 2), Section 5
+    edges = list(edges) if edges is not None else [0.5 * d_base * x for x in (0.2, 0.4, 0.6, 0.8, 1.0, 1.3, 1.7)]
+    st = AdaptiveStep(w=w, layers=layers, d_base=d_base, alpha=alpha, n_default=w.max_nodes, edges=edges,
+                      gamma=list(gamma))
+    t, h = st.t, st.host
+    cap = 1 + K + (d_base + alpha - 1) * F * K
+    h.update(cap=cap, scale=1.0 / float(np.sqrt(w.D)))
+    i32 = dict(dtype=torch.int32, device=device)
+    # the draft and target rows of every possible candidate (row = candidate index)
+    t["draft_all"] = torch.empty((cap, w.V), dtype=torch.float32, device=device)
+    t["target_all"] = torch.empty((cap, w.V), dtype=torch.float32, device=device)
+    for i0 in range(0, cap, 64):
+        ids = range(i0, min(i0 + 64, cap))
+        t["draft_all"][i0:i0 + len(ids)] = _dev(W.logits_rows(w, seed, "draft", 0, ids), device=device)
+        t["target_all"][i0:i0 + len(ids)] = _dev(W.logits_rows(w, seed, "target", 0, ids), device=device)
+    t["x_root"] = t["draft_all"][:1].repeat(F, 1).contiguous()
+    t["x_slots"] = torch.empty((F, w.V), dtype=torch.float32, device=device)
+    t["s1_out"] = dict(topk_idx=torch.empty((F, K), **i32),
+                       topk_logp=torch.empty((F, K), dtype=torch.float32, device=device),
+                       ent_topk=torch.empty(F, dtype=torch.float32, device=device))
+    t["s1_ws"] = hs.workspace(hs.lib().hs_draft_entropy_topk_workspace(F, w.V, K), device)
+    t["state"] = hs.new_tree_state(1, cap, F, device)
+    t["ctl"] = dict(phi=torch.empty(1, dtype=torch.float32, device=device))
+    for k in ("pstar", "bin", "d_prime", "n_prime"):
+        t["ctl"][k] = torch.empty(1, **i32)
+    t["theta"] = _dev(np.full(1, w.theta[0]), torch.float32, device)
+    t["s2_out"] = dict(depth=torch.empty(cap, **i32), cumlogp=torch.empty(cap, dtype=torch.float32, device=device),
+                       keep=torch.empty(cap, dtype=torch.uint8, device=device), out_offsets=torch.empty(2, **i32),
+                       out_src=torch.empty(cap, **i32), out_parent=torch.empty(cap, **i32))
+    t["s2_ws"] = hs.workspace(hs.lib().hs_tree_prune_workspace(1, cap), device)
+    # attention: the prefix caches of all layers are shared by the bins; Q and the tree K/V depend
+    # on the number of verified rows
+    L = int(W.prefix_lengths(w, seed)[0])
+    sizes = sorted({st.decision(b)[1] + 1 for b in range(len(edges) + 1)})
+    kp, vp = [], []
+    for l in range(layers):
+        _, a, b_, _, _ = W.attention_inputs(w, seed, 1000 + l, L, 1, "config")
+        kp.append(_store(a, device))
+        vp.append(_store(b_, device))
+    t["k_prefix"], t["v_prefix"] = torch.cat(kp, dim=0).contiguous(), torch.cat(vp, dim=0).contiguous()
+    po = (np.arange(layers + 1) * L).astype(np.int64)
+    t["prefix_offsets"] = _dev(po, torch.int64, device)
+    h["prefix_offsets"] = torch.from_numpy(po.copy())
+    dt = hs.HS_F32 if w.dtype == "f32" else hs.HS_BF16
+    t["attn"] = {}
+    for M in sizes:
+        parts = [W.attention_inputs(w, seed, 2000 + l, 0, M, "config") for l in range(layers)]
+        no = (np.arange(layers + 1) * M).astype(np.int32)
+        a = dict(q=torch.cat([_store(p[0], device) for p in parts], dim=0).contiguous(),
+                 k_tree=torch.cat([_store(p[3], device) for p in parts], dim=0).contiguous(),
+                 v_tree=torch.cat([_store(p[4], device) for p in parts], dim=0).contiguous(),
+                 parent=torch.empty(layers * M, **i32), node_offsets=_dev(no, torch.int32, device),
+                 host_node_offsets=torch.from_numpy(no.copy()), token=torch.empty(M, **i32),
+                 target=torch.empty((M, w.V), dtype=torch.float32, device=device))
+        a["o"] = torch.empty_like(a["q"])
+        a["ws"] = hs.workspace(hs.lib().hs_tree_attention_workspace(layers, layers * M, int(po[-1]), w.Hq, w.Hkv, w.D,
+                                                                   dt), device)
+        a["s4_out"] = dict(accept_len=torch.empty(1, **i32), bonus_token=torch.empty(1, **i32),
+                           accept_path=torch.empty((1, d_base + alpha), **i32))
+        a["s4_ws"] = hs.workspace(hs.lib().hs_verify_accept_workspace(1, M, w.V), device)
+        t["attn"][M] = a
+    h["sizes"] = sizes
+    return st
