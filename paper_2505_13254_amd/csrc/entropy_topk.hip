@@ -508,7 +508,7 @@ size_t row_topk_workspace(int R, int V, int K) {
 
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
-                          void* workspace, hipStream_t stream) {
+                          void* workspace, hipStream_t stream, ScanSlices* slices) {
   ScanPlan p = plan_scan(R, V);
   Carver c(workspace);
   size_t n = (size_t)R * p.splits;
@@ -530,7 +530,8 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   }
 #undef HS_SCAN_LAUNCH
   hs_status st = launch_status("row scan");
-  if (st != HS_OK || p.splits == 1) return st;
+  if (slices != nullptr) *slices = ScanSlices{part_val, part_idx, p.splits};
+  if (st != HS_OK || p.splits == 1 || slices != nullptr) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,
                      p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse);
   return launch_status("row scan merge");

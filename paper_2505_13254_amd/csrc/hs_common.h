@@ -36,9 +36,18 @@ struct Carver {
 
 // Row scan shared by hs_draft_entropy_topk and hs_verify_accept (defined in entropy_topk.hip).
 size_t row_topk_workspace(int R, int V, int K);
+// `slices` (may be NULL): when the rows had to be cut into slices, the merge launch is left to the
+// caller, who receives the per-slice results instead: entry (row * count + slice) * K + k of
+// val / idx is the slice's k-th best pair (an unused entry has index INT_MAX).  count == 1 means
+// the outputs were written in full.
+struct ScanSlices {
+  const float* val;
+  const int32_t* idx;
+  int count;
+};
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
-                          void* workspace, hipStream_t stream);
+                          void* workspace, hipStream_t stream, ScanSlices* slices = nullptr);
 
 #define HS_REQUIRE(cond, st, ...) \
   do {                            \

@@ -26,7 +26,12 @@ constexpr int AC_MAX_KIDS = 256;    // children tried per node
 constexpr int AC_MAX_ROWS = 8192;   // 64-token rows of the CDF search held in LDS (V <= 524288)
 
 // ----------------------------------------------------------------------------------- greedy
-__global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(const int32_t* __restrict__ arg,
+// With n_slices > 1 the target rows' argmax arrives as one (value, index) pair per row slice
+// (the row scan's merge launch is folded into this kernel): the best pair under (value
+// descending, index ascending) is the row's argmax, stored in `arg` for the walk.
+__global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(int32_t* __restrict__ arg,
+                                                              const float* __restrict__ slice_val,
+                                                              const int32_t* __restrict__ slice_idx, int n_slices,
                                                               const int32_t* __restrict__ token,
                                                               const int32_t* __restrict__ parent,
                                                               const int32_t* __restrict__ node_offsets,
@@ -45,6 +50,23 @@ __global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(const int32_t* __r
       bonus_token[s] = -1;
     }
     return;
+  }
+  if (n_slices > 1) {
+    for (int i = tid; i < n; i += GR_THREADS) {
+      const int64_t base = (int64_t)(o + i) * n_slices;
+      float bv = slice_val[base];
+      int bi = slice_idx[base];
+      for (int q = 1; q < n_slices; ++q) {
+        const float v = slice_val[base + q];
+        const int x = slice_idx[base + q];
+        if (better(v, x, bv, bi)) {
+          bv = v;
+          bi = x;
+        }
+      }
+      arg[o + i] = bi;
+    }
+    __syncthreads();  // every row's argmax is visible to the workgroup
   }
   // key = depth of a fully confirmed node (higher wins), then lower index
   long long best = ((long long)0 << 32) | (unsigned)(INT_MAX - 0);  // the root: depth 0
@@ -336,6 +358,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
              workspace_bytes);
   int32_t *t_arg = nullptr, *d_arg = nullptr;
   float *t_lz = nullptr, *d_lz = nullptr;
+  hs::ScanSlices slices{nullptr, nullptr, 1};
   if (NN > 0) {
     hs::Carver c(workspace);
     t_arg = c.take<int32_t>(NN);
@@ -346,8 +369,9 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     float* d_ent = c.take<float>(NN);
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
+    // greedy: the merge of the row slices is done by the accept kernel (one launch less)
     hs_status r = hs::row_topk_launch(target_logits, row_stride, NN, V, 1, T, t_arg, t_lz, t_ent, nullptr, nullptr,
-                                      scan_ws, st);
+                                      scan_ws, st, stochastic ? nullptr : &slices);
     if (r != HS_OK) return r;
     if (mode == HS_ACCEPT_STOCHASTIC) {
       r = hs::row_topk_launch(draft_logits, row_stride, NN, V, 1, T, d_arg, d_lz, d_ent, nullptr, nullptr, scan_ws,
@@ -356,8 +380,8 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     }
   }
   if (!stochastic) {
-    hipLaunchKernelGGL(hs::k_accept_greedy, dim3(B), dim3(hs::GR_THREADS), 0, st, t_arg, token, parent, node_offsets,
-                       max_depth, accept_len, accept_path, bonus_token);
+    hipLaunchKernelGGL(hs::k_accept_greedy, dim3(B), dim3(hs::GR_THREADS), 0, st, t_arg, slices.val, slices.idx,
+                       slices.count, token, parent, node_offsets, max_depth, accept_len, accept_path, bonus_token);
     return hs::launch_status("accept (greedy)");
   }
   hipLaunchKernelGGL(hs::k_accept_walk, dim3(B), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits, row_stride,
