@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 
 
 def cpu_baseline(w, step, layers, seed):
@@ -219,6 +220,10 @@ def main():
     tokens = h["kept_draft_nodes"]
     bytes3 = step.bytes_stage3()
     achieved = bytes3 / (stage_ms[2] * 1e-3) / 1e9
+    flops3 = step.flops_stage3()
+    # the attention launch is bound by the matrix cores when its arithmetic intensity lies above the
+    # ridge of the two published peaks (workload 4: 776 rows share every K/V byte)
+    mfma_bound = w.dtype == "bf16" and flops3 / bytes3 > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_tree_attention_w%d.json" % w.wid)
     if os.path.exists(tpath):
@@ -246,8 +251,13 @@ def main():
         "copy_ceiling_gbps": copy_gbps,
         "roofline": {"kernel": "hs_tree_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": bytes3, "launch_ms": stage_ms[2]},
+                     "algorithmic_bytes_per_launch": bytes3, "algorithmic_flops_per_launch": flops3,
+                     "launch_ms": stage_ms[2]},
     }
+    if mfma_bound:
+        tf = flops3 / (stage_ms[2] * 1e-3) / 1e12
+        out["roofline"].update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "hbm_gbps": achieved})
     acc = step.t["s4_out"]
     out["result"] = {"accept_len": [int(x) for x in acc["accept_len"].cpu().numpy()][:16],
                      "bonus_token": [int(x) for x in acc["bonus_token"].cpu().numpy()][:16]}

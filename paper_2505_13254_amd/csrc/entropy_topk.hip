@@ -4,16 +4,18 @@
 // K best (logit, index) pairs (Section 4.1, Eq. 1; Section 2.2 Expansion).  HBM-bound: 4 bytes per
 // logit, read once.
 //
-// One workgroup of 16 waves scans a row (k_scan_rows), merges its waves' results and writes the
-// outputs.  Only when there are too few rows to fill the chip is a row cut into slices for several
-// workgroups; a small second kernel then merges the slices (k_scan_finalize).
+// One workgroup (four or sixteen waves, see below) scans a row (k_scan_rows), merges its waves'
+// results and writes the outputs.  Only when there are too few rows to fill the chip is a row cut
+// into slices for several workgroups; a small second kernel then merges the slices
+// (k_scan_finalize).
 //
 // Top-K selection never sorts the data.  Each wave keeps its K best pairs as a sorted list in
 // registers, entry l in lane l.  Per tile only the elements that are not worse than the list's K-th
 // entry are looked at (one ballot per register); each of them is broadcast and inserted: the lanes
 // whose entry it beats take their left neighbour's entry (or the new one), a shift by one lane done
 // with a DPP move.  Before a list is full the threshold comes from the first tile: the K-th largest
-// of the 16 waves' maxima (of a wave's 64 lane maxima when K > 16): K elements reach it, so no
+// of the workgroup's wave maxima (of its 16-lane row maxima when it has fewer waves than K, of a
+// wave's 64 lane maxima when even those are too few): K elements reach it, so no
 // true Top-K member is ever filtered out, and only about K elements of the whole tile pass it.
 // All decisions compare raw float32 logits under the strict order (value descending, index
 // ascending), so the indices do not depend on how rows are split or reduced.
@@ -368,7 +370,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     }
 
     // ---- threshold (a value): no element below it can be among the row's K best.  First tile:
-    // the K-th largest of the 16 waves' maxima (K <= 16; K elements of the tile reach it), or of
+    // the K-th largest of the workgroup's group maxima (K elements of the tile reach it), or of
     // this wave's 64 lane maxima; afterwards also the wave's own K-th entry once its list is full.
     if (tile == 0) {
       if (K <= SCAN_GROUPS) {

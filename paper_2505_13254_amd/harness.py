@@ -159,6 +159,20 @@ class Step:
             total += (2 * (L + M) * w.Hkv * w.D + 2 * M * w.Hq * w.D) * es
         return total
 
+    def flops_stage3(self) -> int:
+        """Multiply-adds of both products times two: every row meets its prefix and its root path."""
+        h, w = self.host, self.w
+        no, po = h["attn_node_offsets"].numpy(), h["attn_prefix_offsets"].numpy()
+        par = self.t["attn_parent"].cpu().numpy()
+        total = 0
+        for s in range(len(no) - 1):
+            n0, M, L = int(no[s]), int(no[s + 1] - no[s]), int(po[s + 1] - po[s])
+            depth = np.zeros(M, np.int64)
+            for i in range(1, M):
+                depth[i] = depth[par[n0 + i]] + 1
+            total += 4 * w.Hq * w.D * int((L + depth + 1).sum())
+        return total
+
     def bytes_stage4(self) -> int:
         n = int(self.t["target_logits"].numel()) * 4
         return n * (2 if self.accept_mode == 1 else 1)
