@@ -17,11 +17,17 @@ Pin status (see tests/test_oracle_*.py):
   adaptive_control    pinned: the Section 4.3 formulas worked by hand on the framework figure's
                       example, Eq. 1 on uniform rows (T ln K), brute-force enumeration of the
                       deepest paths, numpy.searchsorted for the bin lookup.
+  tree_expand         pinned: hand-worked two-level tree, brute-force ranking by float64 path
+                      products, structural invariants, the pipeline's whole-tree builder.
+  kv_commit           pinned: numpy.concatenate of the accepted rows, and decoding through several
+                      commits equals dense causal attention (torch) over the whole sequence.
 """
 from .entropy_topk import draft_entropy_topk
 from .tree_prune import tree_prune
 from .tree_attention import tree_attention
 from .verify_accept import verify_accept
 from .adaptive_control import adaptive_control
+from .tree_expand import tree_expand
+from .kv_commit import kv_commit
 
-__all__ = ["draft_entropy_topk", "tree_prune", "tree_attention", "verify_accept", "adaptive_control"]
+__all__ = ["draft_entropy_topk", "tree_prune", "tree_attention", "verify_accept", "adaptive_control", "tree_expand", "kv_commit"]
