@@ -19,6 +19,9 @@
  *   hs_adaptive_control     cumulative Top-K entropy of the operational path, its entropy bin, and
  *                           the depth extension and node budget of that bin (Section 4.1 Eq. 1; 4.2; 4.3)
  *   hs_tree_prune_counted   hs_tree_prune on trees stored with spare capacity
+ *   hs_kv_commit            the accepted path's K/V rows join the KV cache (Section 2.1: decoding
+ *                           resumes behind the last accepted token)
+ *   hs_tree_attention_lens  hs_tree_attention on caches stored with spare capacity
  *
  * Conventions that hold for every call
  *   - Pointers are DEVICE pointers unless the parameter name starts with host_.  The caller owns
@@ -163,6 +166,21 @@ hs_status hs_tree_attention(const void* q, const void* k_prefix, const void* v_p
                             void* o, float* lse,
                             void* workspace, size_t workspace_bytes, hs_stream stream);
 
+/* hs_tree_attention_lens: hs_tree_attention on KV caches stored with spare capacity (what
+ * hs_kv_commit grows): sequence s owns the token range prefix_offsets[s] .. prefix_offsets[s+1] of
+ * k_prefix / v_prefix and prefix_lens[s] (int64 [B], device; host_prefix_lens the same on the host)
+ * of it are in use.  Both NULL: the whole range, i.e. hs_tree_attention.  The workspace query takes
+ * the total capacity as total_prefix. */
+hs_status hs_tree_attention_lens(const void* q, const void* k_prefix, const void* v_prefix,
+                                 const void* k_tree, const void* v_tree,
+                                 const int32_t* parent, const int32_t* node_offsets,
+                                 const int64_t* prefix_offsets,
+                                 const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                                 const int64_t* prefix_lens, const int64_t* host_prefix_lens,
+                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale,
+                                 void* o, float* lse,
+                                 void* workspace, size_t workspace_bytes, hs_stream stream);
+
 /* ------------------------------------------------------------------------------------------------
  * hs_verify_accept  (Section 2.1: a drafted token x is accepted with probability
  * min(1, p(x)/p_hat(x)); on rejection a token is drawn from the residual of p and later drafts are
@@ -270,6 +288,25 @@ hs_status hs_adaptive_control(const int32_t* parent, const float* logc, const fl
                               int32_t alpha, int32_t d_base, int32_t n_default, hs_pstar_mode mode,
                               float* phi, int32_t* pstar, int32_t* bin, int32_t* d_prime,
                               int32_t* n_prime, hs_stream stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * hs_kv_commit  (Section 2.1: accepted draft tokens become part of the context, later drafts are
+ * discarded, and decoding resumes behind the last accepted token)
+ *
+ * For each sequence with a tree, the K/V rows of the tree's root (the last committed token, whose
+ * K/V is not in the cache yet) and of the accept_len[s] accepted rows accept_path[s, 0..] (local
+ * rows, as hs_verify_accept writes them; row stride max_depth) are appended, in that order, to the
+ * sequence's cache: token position cache_offsets[s] + cache_lens[s] onwards of k_cache / v_cache
+ * [capacity, Hkv, D] (element type dt, as k_tree / v_tree [NN, Hkv, D]).  cache_lens[s] (int64,
+ * device, in/out) grows by the number of rows written.  A sequence whose region
+ * (cache_offsets[s+1] - cache_offsets[s] tokens) cannot take all its rows takes the leading ones
+ * that fit; the caller sees that from cache_lens.  Rows of rejected tree nodes are not copied.
+ * Requires Hkv * D * sizeof(element) to be a multiple of 16 and 16-byte aligned tensors.  No workspace.
+ */
+hs_status hs_kv_commit(const void* k_tree, const void* v_tree, const int32_t* node_offsets,
+                       const int32_t* accept_path, const int32_t* accept_len, int32_t max_depth,
+                       void* k_cache, void* v_cache, const int64_t* cache_offsets, int64_t* cache_lens,
+                       int32_t B, int32_t Hkv, int32_t D, hs_dtype dt, hs_stream stream);
 
 #ifdef __cplusplus
 }

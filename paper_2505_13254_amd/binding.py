@@ -39,6 +39,9 @@ _SIGNATURES = {
     "hs_tree_attention_workspace": (_sz, [_i32, _i32, _i64, _i32, _i32, _i32, _c.c_int]),
     "hs_tree_attention": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                      _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "hs_tree_attention_lens": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
+                                          _i32, _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "hs_kv_commit": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _vp]),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
     "hs_verify_accept": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _f32, _vp, _i32,
                                     _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -234,10 +237,13 @@ def _dtype_code(t: torch.Tensor) -> int:
 def hs_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offsets, prefix_offsets,
                       host_node_offsets, host_prefix_offsets, scale: float, *, want_lse: bool = False,
                       out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                      ws: Optional[torch.Tensor] = None, stream=None):
+                      ws: Optional[torch.Tensor] = None, stream=None,
+                      prefix_lens: Optional[torch.Tensor] = None, host_prefix_lens: Optional[torch.Tensor] = None):
     """q [NN,Hq,D]; k_prefix, v_prefix [total_prefix,Hkv,D]; k_tree, v_tree [NN,Hkv,D] (float32 or bfloat16, GPU);
     parent int32 [NN], node_offsets int32 [B+1], prefix_offsets int64 [B+1] on the GPU and the same two offset
-    arrays on the host (CPU tensors).  Returns (o [NN,Hq,D], lse [NN,Hq] or None)."""
+    arrays on the host (CPU tensors).  Returns (o [NN,Hq,D], lse [NN,Hq] or None).
+    With prefix_lens (int64 [B], GPU) and host_prefix_lens (the same on the CPU) the call is
+    hs_tree_attention_lens: prefix_offsets then delimit cache regions with spare capacity."""
     dt = _dtype_code(q)
     for name, t in (("q", q), ("k_prefix", k_prefix), ("v_prefix", v_prefix), ("k_tree", k_tree), ("v_tree", v_tree)):
         _dev(t, q.dtype, name)
@@ -256,12 +262,40 @@ def hs_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offset
     need = lib().hs_tree_attention_workspace(B, NN, int(hpo[-1]), Hq, Hkv, D, dt)
     if ws is None:
         ws = workspace(need, dev)
-    st = lib().hs_tree_attention(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(parent),
-                                 _ptr(node_offsets), _ptr(prefix_offsets), _vp(hno.data_ptr()), _vp(hpo.data_ptr()),
-                                 B, Hq, Hkv, D, dt, float(scale), _ptr(out), _ptr(lse), _ptr(ws),
-                                 0 if ws is None else ws.numel(), _stream(stream))
+    head = (_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(parent),
+            _ptr(node_offsets), _ptr(prefix_offsets), _vp(hno.data_ptr()), _vp(hpo.data_ptr()))
+    tail = (B, Hq, Hkv, D, dt, float(scale), _ptr(out), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(),
+            _stream(stream))
+    if prefix_lens is None:
+        st = lib().hs_tree_attention(*head, *tail)
+    else:
+        _dev(prefix_lens, torch.int64, "prefix_lens")
+        hl = host_prefix_lens.to(dtype=torch.int64, device="cpu").contiguous()
+        st = lib().hs_tree_attention_lens(*head, _ptr(prefix_lens), _vp(hl.data_ptr()), *tail)
     _check(st, "hs_tree_attention")
     return out, lse
+
+
+def hs_kv_commit(k_tree, v_tree, node_offsets, accept_path, accept_len, k_cache, v_cache, cache_offsets, cache_lens,
+                 *, stream=None):
+    """k_tree, v_tree [NN,Hkv,D] and k_cache, v_cache [capacity,Hkv,D] of one element type; node_offsets int32
+    [B+1], accept_path int32 [B,max_depth], accept_len int32 [B], cache_offsets int64 [B+1], cache_lens int64
+    [B] (updated in place); all on the GPU."""
+    dt = _dtype_code(k_tree)
+    for name, t in (("k_tree", k_tree), ("v_tree", v_tree), ("k_cache", k_cache), ("v_cache", v_cache)):
+        _dev(t, k_tree.dtype, name)
+    _dev(node_offsets, torch.int32, "node_offsets"); _dev(accept_path, torch.int32, "accept_path")
+    _dev(accept_len, torch.int32, "accept_len"); _dev(cache_offsets, torch.int64, "cache_offsets")
+    _dev(cache_lens, torch.int64, "cache_lens")
+    B = node_offsets.numel() - 1
+    if accept_path.dim() != 2 or accept_path.shape[0] != B or accept_len.numel() != B or cache_lens.numel() != B:
+        raise ValueError("accept_path must be [B, max_depth]; accept_len and cache_lens [B]")
+    Hkv, D = k_tree.shape[1], k_tree.shape[2]
+    st = lib().hs_kv_commit(_ptr(k_tree), _ptr(v_tree), _ptr(node_offsets), _ptr(accept_path), _ptr(accept_len),
+                            accept_path.shape[1], _ptr(k_cache), _ptr(v_cache), _ptr(cache_offsets), _ptr(cache_lens),
+                            B, Hkv, D, dt, _stream(stream))
+    _check(st, "hs_kv_commit")
+    return cache_lens
 
 
 def hs_verify_accept(target_logits, draft_logits, token, parent, node_offsets, mode: int, temperature: float,

@@ -68,6 +68,7 @@ struct AttnArgs {
   const int32_t* parent;
   const int32_t* node_offsets;
   const int64_t* prefix_offsets;
+  const int64_t* prefix_lens;  // used tokens of each sequence's prefix region; NULL: the whole region
   int B, Hq, Hkv, G;
   float scale;
   int split_len;   // prefix tokens per split (multiple of 64)
@@ -80,6 +81,11 @@ struct AttnArgs {
   int n_items;
   SeqEntry tbl[ATTN_TBL];
 };
+
+// Prefix length of sequence s (plain launches read it on the device).
+__device__ __forceinline__ int64_t prefix_len_of(const AttnArgs& a, int s) {
+  return a.prefix_lens != nullptr ? a.prefix_lens[s] : a.prefix_offsets[s + 1] - a.prefix_offsets[s];
+}
 
 __host__ __device__ __forceinline__ int splits_of(int64_t L, int split_len) {
   int n = (int)((L + split_len - 1) / split_len);

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
   const int n0 = a.node_offsets[s];
   const int M = a.node_offsets[s + 1] - n0;
   const int64_t p0 = a.prefix_offsets[s];
-  const int64_t L = a.prefix_offsets[s + 1] - p0;
+  const int64_t L = prefix_len_of(a, s);
   if (M <= 0) return;
   const int G = a.G, Hkv = a.Hkv, Hq = a.Hq;
   const int R = G * M;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64 * CMB_ROWS) void k_attn_combine(AttnArgs a, int6
       const int mid = (lo + hi) >> 1;
       if (a.node_offsets[mid] <= node) lo = mid; else hi = mid;
     }
-    n_sp = splits_of(a.prefix_offsets[lo + 1] - a.prefix_offsets[lo], a.split_len);
+    n_sp = splits_of(prefix_len_of(a, lo), a.split_len);
   }
   if (n_sp == 1) return;  // written directly by the attention kernel
   constexpr int REC = D + ATTN_REC_PAD;
@@ -237,14 +237,14 @@ struct AttnPlan {
 
 // Chooses the split length from the host copies of the offsets: enough workgroups to fill the
 // chip, but splits long enough that partial records stay small next to the K/V they summarise.
-static AttnPlan plan_attention(const int32_t* hno, const int64_t* hpo, int B, int Hq, int Hkv, int rows_per_wg,
-                               int target_wgs) {
+static AttnPlan plan_attention(const int32_t* hno, const int64_t* hpo, const int64_t* hlens, int B, int Hq, int Hkv,
+                               int rows_per_wg, int target_wgs) {
   AttnPlan p{};
   int max_M = 0;
   int64_t max_L = 0, sum_L = 0;
   for (int s = 0; s < B; ++s) {
     const int M = hno[s + 1] - hno[s];
-    const int64_t L = hpo[s + 1] - hpo[s];
+    const int64_t L = hlens != nullptr ? hlens[s] : hpo[s + 1] - hpo[s];
     if (M > max_M) max_M = M;
     if (M > 0) {
       if (L > max_L) max_L = L;
@@ -296,7 +296,8 @@ static inline int plan_splits(int tiles, int target, int sp_cap) {
 }
 
 // Fills a.tbl / a.n_tbl / a.n_items / a.sp_max.  Returns false when the batch does not fit the table.
-static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, int B, int sp_cap) {
+static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, const int64_t* hlens, int B,
+                          int sp_cap) {
   struct Seq {
     int s, M, tiles, rg, waves0, waves_last, ttiles;
   };
@@ -304,7 +305,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, i
   int n = 0;
   for (int s = 0; s < B; ++s) {
     const int M = hno[s + 1] - hno[s];
-    const int64_t L = hpo[s + 1] - hpo[s];
+    const int64_t L = hlens != nullptr ? hlens[s] : hpo[s + 1] - hpo[s];
     if (M <= 0) continue;
     if (n == ATTN_TBL || L >= (int64_t)1 << 30) return false;
     const int blocks = (a.G * M + 31) / 32;  // 32-row wave blocks
@@ -375,7 +376,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, i
     e.first_item = (int)first;
     e.n0 = hno[q.s];
     e.M = q.M;
-    e.L = (int)(hpo[q.s + 1] - hpo[q.s]);
+    e.L = (int)(hlens != nullptr ? hlens[q.s] : hpo[q.s + 1] - hpo[q.s]);
     e.p0 = hpo[q.s];
     e.tiles_per_split = per_of[i];
     e.n_sp = (short)nsp_of[i];
@@ -414,6 +415,18 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
                                        const int64_t* host_prefix_offsets, int32_t B, int32_t Hq, int32_t Hkv,
                                        int32_t D, hs_dtype dt, float scale, void* o, float* lse, void* workspace,
                                        size_t workspace_bytes, hs_stream stream) {
+  return hs_tree_attention_lens(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offsets, prefix_offsets,
+                                host_node_offsets, host_prefix_offsets, nullptr, nullptr, B, Hq, Hkv, D, dt, scale, o,
+                                lse, workspace, workspace_bytes, stream);
+}
+
+extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix, const void* v_prefix,
+                                            const void* k_tree, const void* v_tree, const int32_t* parent,
+                                            const int32_t* node_offsets, const int64_t* prefix_offsets,
+                                            const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                                            const int64_t* prefix_lens, const int64_t* host_prefix_lens, int32_t B,
+                                            int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
+                                            float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
   clear_error();
   HS_REQUIRE(B >= 0, HS_ERR_SHAPE, "hs_tree_attention: B=%d", B);
   HS_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, HS_ERR_SHAPE, "hs_tree_attention: Hq=%d must be a multiple of Hkv=%d",
@@ -431,7 +444,12 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
                "hs_tree_attention: offsets decrease at sequence %d", s);
     HS_REQUIRE(M <= MAX_TREE_ROWS, HS_ERR_UNSUPPORTED, "hs_tree_attention: sequence %d has %d tree rows (limit %d)", s,
                M, MAX_TREE_ROWS);
+    HS_REQUIRE(host_prefix_lens == nullptr ||
+                   (host_prefix_lens[s] >= 0 && host_prefix_lens[s] <= host_prefix_offsets[s + 1] - host_prefix_offsets[s]),
+               HS_ERR_SHAPE, "hs_tree_attention: prefix length of sequence %d exceeds its region", s);
   }
+  HS_REQUIRE((prefix_lens == nullptr) == (host_prefix_lens == nullptr), HS_ERR_NULL,
+             "hs_tree_attention: prefix_lens and host_prefix_lens go together");
   const int NN = host_node_offsets[B];
   const int64_t total_prefix = host_prefix_offsets[B];
   if (NN == 0) return HS_OK;
@@ -447,7 +465,7 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
                     aligned16(o);
   AttnArgs a;
   a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_tree = k_tree; a.v_tree = v_tree;
-  a.parent = parent; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets;
+  a.parent = parent; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets; a.prefix_lens = prefix_lens;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
   a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
   a.n_tbl = 0; a.n_items = 0;
@@ -457,9 +475,9 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
   const int sp_cap = (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound);
 
   AttnPlan plan{};
-  if (!(mfma && plan_worklist(a, host_node_offsets, host_prefix_offsets, B, sp_cap))) {
+  if (!(mfma && plan_worklist(a, host_node_offsets, host_prefix_offsets, host_prefix_lens, B, sp_cap))) {
     a.n_tbl = 0;
-    plan = plan_attention(host_node_offsets, host_prefix_offsets, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
+    plan = plan_attention(host_node_offsets, host_prefix_offsets, host_prefix_lens, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
     while (plan.sp_max > sp_cap) {
       plan.split_len *= 2;
       plan.sp_max = splits_of(plan.max_L, plan.split_len);

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     n0 = a.node_offsets[s];
     M = a.node_offsets[s + 1] - n0;
     p0 = a.prefix_offsets[s];
-    L = a.prefix_offsets[s + 1] - p0;
+    L = prefix_len_of(a, s);
     if (M <= 0) return;
     n_sp = splits_of(L, a.split_len);
     tiles_per_split = a.split_len / MF_TILE;

@@ -1,0 +1,116 @@
+"""GPU parity of hs_kv_commit (bit-exact) and of hs_tree_attention_lens on caches with spare
+capacity, alone and in a decoding loop of several verify / commit steps."""
+import numpy as np
+import pytest
+
+from oracle import tree_attention
+from oracle.kv_commit import kv_commit
+from synth import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _bits(t):
+    torch.cuda.synchronize()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def _random_parents(rs, n, back=5):
+    return [-1] + [int(rs.randint(max(0, i - back), i)) for i in range(1, n)]
+
+
+def _random_path(rs, parent, max_depth):
+    """A root path of random length (what an accept walk could return)."""
+    n = len(parent)
+    if n == 0:
+        return [], 0
+    children = {i: [j for j in range(n) if parent[j] == i] for i in range(n)}
+    path, cur = [], 0
+    while children[cur] and len(path) < max_depth and rs.uniform() < 0.75:
+        cur = children[cur][int(rs.randint(len(children[cur])))]
+        path.append(cur)
+    return path, len(path)
+
+
+@pytest.mark.parametrize("wid", [1, 2])
+def test_commit_matches_the_checker(G, wid):
+    import paper_2505_13254_amd as hs
+    w = W.WORKLOADS[wid]
+    rs = np.random.RandomState(wid)
+    sizes = [9, 0, 33, 1, 17]
+    caps = [20, 8, 40, 3, 10]
+    lens = [4, 2, 0, 3, 7]                                # sequence 3 is full, sequence 4 overflows
+    B, max_depth = len(sizes), 6
+    parents = [_random_parents(rs, n) if n else [] for n in sizes]
+    parts = [W.attention_inputs(w, 0, s, caps[s], sizes[s], "unit", parent=np.asarray(parents[s])) for s in range(B)]
+    kc, vc, kt, vt = (np.concatenate([p[i] for p in parts], axis=0) for i in (1, 2, 3, 4))
+    no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    co = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+    path = np.full((B, max_depth), -1, np.int32)
+    alen = np.zeros(B, np.int32)
+    for s in range(B):
+        p, n = _random_path(rs, parents[s], max_depth)
+        path[s, :n], alen[s] = p, n
+    alen[4] = max(alen[4], 3)                             # make sure the overflow case overflows
+    path[4, :3] = np.where(path[4, :3] < 0, 1, path[4, :3])
+    want_k, want_v, want_l = kv_commit(kt, vt, no, path, alen, kc, vc, co, np.asarray(lens, np.int64))
+    dk, dv, dl = G.dev_store(kc), G.dev_store(vc), G.dev(np.asarray(lens, np.int64))
+    hs.hs_kv_commit(G.dev_store(kt), G.dev_store(vt), G.dev(no), G.dev(path), G.dev(alen), dk, dv, G.dev(co), dl)
+    assert np.array_equal(_bits(dl), want_l)
+    assert np.array_equal(_bits(dk), want_k) and np.array_equal(_bits(dv), want_v)
+    assert int(want_l[4]) == caps[4] and int(want_l[3]) == 3
+
+
+@pytest.mark.parametrize("wid,B", [(1, 3), (2, 4), (5, 100)])
+def test_decoding_loop_on_caches_with_spare_capacity(G, wid, B):
+    """Three verify / commit rounds: attention over the used part of each cache region, a random
+    accepted path, commit; the checker follows with its own commit and attention."""
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[wid], B=B)
+    rs = np.random.RandomState(10 + wid)
+    tol = 1e-4 if w.dtype == "f32" else 2e-2
+    max_depth = 5
+    caps = [int(x) for x in rs.randint(40, 400 if B < 50 else 90, size=B)]
+    lens = np.asarray([int(rs.randint(0, c - 30)) for c in caps], np.int64)
+    if B == 4:
+        caps[1], lens[1] = 3000, 2700                      # long enough to be cut into key splits
+    co = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+    fill = [W.attention_inputs(w, 1, s, caps[s], 1, "unit") for s in range(B)]
+    kc, vc = (np.concatenate([p[i] for p in fill], axis=0) for i in (1, 2))
+    dk, dv, dl, dco = G.dev_store(kc), G.dev_store(vc), G.dev(lens), G.dev(co)
+    for step in range(3):
+        sizes = [int(x) for x in rs.randint(0 if step else 1, 12, size=B)]
+        parents = [_random_parents(rs, n) if n else [] for n in sizes]
+        parts = [W.attention_inputs(w, 2 + step, s, 0, sizes[s], "unit", parent=np.asarray(parents[s])) for s in range(B)]
+        q, kt, vt = (np.concatenate([p[i] for p in parts], axis=0) for i in (0, 3, 4))
+        par = np.concatenate([np.asarray(p, np.int32) for p in parents]).astype(np.int32)
+        no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        # the checker: packed prefix = the used part of every region
+        used_k = np.concatenate([kc[co[s]:co[s] + lens[s]] for s in range(B)], axis=0)
+        used_v = np.concatenate([vc[co[s]:co[s] + lens[s]] for s in range(B)], axis=0)
+        po = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        want_o, _ = tree_attention(q, used_k, used_v, kt, vt, par, no, po, 1.0 / np.sqrt(w.D))
+        dkt, dvt = G.dev_store(kt), G.dev_store(vt)
+        o, _ = hs.hs_tree_attention(G.dev_store(q), dk, dv, dkt, dvt, G.dev(par), G.dev(no), dco,
+                                    torch.from_numpy(no), torch.from_numpy(co), 1.0 / float(np.sqrt(w.D)),
+                                    prefix_lens=dl, host_prefix_lens=torch.from_numpy(lens.copy()))
+        assert np.abs(G.host(o).astype(np.float64) - want_o).max() <= tol, step
+        path = np.full((B, max_depth), -1, np.int32)
+        alen = np.zeros(B, np.int32)
+        for s in range(B):
+            p, n = _random_path(rs, parents[s], max_depth)
+            path[s, :n], alen[s] = p, n
+        kc, vc, lens = kv_commit(kt, vt, no, path, alen, kc, vc, co, lens)
+        hs.hs_kv_commit(dkt, dvt, G.dev(no), G.dev(path), G.dev(alen), dk, dv, dco, dl)
+        assert np.array_equal(_bits(dl), lens) and np.array_equal(_bits(dk), kc) and np.array_equal(_bits(dv), vc)
