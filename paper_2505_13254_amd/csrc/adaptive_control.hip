@@ -3,7 +3,8 @@
 // Section 4.2: entropy bins; Section 4.3: depth extension d' and node budget N').
 //
 // Nothing to stream: a few hundred nodes per sequence, one workgroup per sequence, no workspace.
-// Every node finds its depth by walking to the root; the nodes of the deepest level form their
+// The parent pointers are staged in LDS (trees of up to 8192 rows; larger ones are walked in global
+// memory).  Every node finds its depth by walking to the root; the nodes of the deepest level form their
 // value root-first (the float32 add per node of the reranking step, so the choice of P* is taken
 // on the same numbers as the pruning that follows); one 64-bit (value, row) key per node and a
 // workgroup maximum pick P*; one thread then sums the path's entropies root-first in float32 and
@@ -17,6 +18,7 @@ namespace hs {
 constexpr int CTL_THREADS = 256;
 constexpr int CTL_MAX_BINS = 64;
 constexpr int CTL_MAX_LOW = 8;
+constexpr int CTL_LDS_NODES = 8192;
 
 struct ControlArgs {
   const int32_t* parent;
@@ -42,29 +44,18 @@ __device__ __forceinline__ unsigned long long control_key(float v, int i) {
 }
 
 // The ancestor of node i that is `up` levels above it.
-__device__ __forceinline__ int ancestor(const int32_t* __restrict__ par, int i, int up) {
+template <typename IP>
+__device__ __forceinline__ int ancestor(IP par, int i, int up) {
   for (; up > 0; --up) i = par[i];
   return i;
 }
 
-__global__ __launch_bounds__(CTL_THREADS) void k_adaptive_control(ControlArgs a) {
-  __shared__ int red_i[CTL_THREADS / 64];
-  __shared__ unsigned long long red_k[CTL_THREADS / 64];
-  const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int o = a.node_offsets[s];
-  const int n = a.node_counts != nullptr ? a.node_counts[s] : a.node_offsets[s + 1] - o;
-  if (n <= 0) {
-    if (tid == 0) {
-      a.phi[s] = 0.f;
-      a.pstar[s] = -1;
-      a.bin[s] = 0;
-      a.d_prime[s] = a.d_base;
-      a.n_prime[s] = a.n_default;
-    }
-    return;
-  }
-  const int32_t* __restrict__ par = a.parent + o;
-  const float* __restrict__ lc = a.logc + o;
+// The decision for one sequence; `par` points to LDS or to global memory.
+template <typename IP>
+__device__ __forceinline__ void control_sequence(const ControlArgs& a, int s, int n, IP par,
+                                                 const float* __restrict__ lc, const float* __restrict__ ent,
+                                                 int* red_i, unsigned long long* red_k) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   // deepest level
   int my_max = 0;
@@ -108,7 +99,6 @@ __global__ __launch_bounds__(CTL_THREADS) void k_adaptive_control(ControlArgs a)
   const int p = 0x7fffffff - (int)(unsigned)(best & 0xffffffffull);
 
   // Eq. 1 along the path to P*: the rows of its strict ancestors, root first
-  const float* __restrict__ ent = a.ent + o;
   float acc = 0.f;
   for (int t = 0; t < D; ++t) acc = acc + ent[ancestor(par, p, D - t)];
   int b = 0;
@@ -124,6 +114,34 @@ __global__ __launch_bounds__(CTL_THREADS) void k_adaptive_control(ControlArgs a)
   a.bin[s] = b;
   a.d_prime[s] = a.d_base + delta;
   a.n_prime[s] = budget;
+}
+
+__global__ __launch_bounds__(CTL_THREADS) void k_adaptive_control(ControlArgs a) {
+  __shared__ int red_i[CTL_THREADS / 64];
+  __shared__ unsigned long long red_k[CTL_THREADS / 64];
+  __shared__ int par_lds[CTL_LDS_NODES];
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const int o = a.node_offsets[s];
+  const int n = a.node_counts != nullptr ? a.node_counts[s] : a.node_offsets[s + 1] - o;
+  if (n <= 0) {
+    if (tid == 0) {
+      a.phi[s] = 0.f;
+      a.pstar[s] = -1;
+      a.bin[s] = 0;
+      a.d_prime[s] = a.d_base;
+      a.n_prime[s] = a.n_default;
+    }
+    return;
+  }
+  const float* __restrict__ lc = a.logc + o;
+  const float* __restrict__ ent = a.ent + o;
+  if (n <= CTL_LDS_NODES) {
+    for (int i = tid; i < n; i += CTL_THREADS) par_lds[i] = a.parent[o + i];
+    __syncthreads();
+    control_sequence(a, s, n, (const int*)par_lds, lc, ent, red_i, red_k);
+  } else {
+    control_sequence(a, s, n, a.parent + o, lc, ent, red_i, red_k);
+  }
 }
 
 }  // namespace hs
