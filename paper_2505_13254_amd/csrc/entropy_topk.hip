@@ -292,6 +292,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
   const float c = inv_t * LOG2E;
   float m = -HS_INF, s1 = 0.f, t2 = 0.f;
   float thr = -HS_INF;
+  int thr_i = INT_MAX;  // among elements equal to thr only those with a lower index can still enter the list
   if (tid == 0) sm.cnt = 0;
   if (tid < HS_MAX_TOPK) {  // a slice with fewer than K elements leaves the rest of its list unused
     sm.ov[tid] = -HS_INF;
@@ -394,17 +395,26 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
         const unsigned long long who = __ballot(r == K - 1);
         thr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, tm), __ffsll((long long)who) - 1));
       }
-    } else {
-      thr = fmaxf(thr, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lv), K - 1)));
     }
+    // the wave's own K-th entry, once it is at least as good as the threshold, replaces it as a
+    // (value, index) pair: an element that equals it in value enters only with a lower index
+    // (rows of equal logits would otherwise send every element through the insertion)
+    auto tighten = [&]() {
+      const float kv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lv), K - 1));
+      if (kv >= thr) {
+        thr = kv;
+        thr_i = __builtin_amdgcn_readlane(li, K - 1);  // INT_MAX while the list is not full
+      }
+    };
+    tighten();
 
     // ---- insert the elements that reach the threshold (skipped when no lane's maximum does)
     if (__ballot(tm >= thr) != 0ull) {
 #pragma unroll
       for (int jj = 0; jj < SCAN_VPT; ++jj) {
-        unsigned long long todo = __ballot(v[jj] >= thr);
+        const int idx = HS_IDX(jj);
+        unsigned long long todo = __ballot(v[jj] > thr || (v[jj] == thr && idx < thr_i));
         if (todo != 0ull) {
-          const int idx = HS_IDX(jj);
           do {
             const int src = __ffsll((long long)todo) - 1;
             todo &= todo - 1ull;
@@ -412,7 +422,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
             const int xi = __builtin_amdgcn_readlane(idx, src);
             list_insert(xv, xi, lv, li);
           } while (todo != 0ull);
-          thr = fmaxf(thr, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lv), K - 1)));
+          tighten();
         }
       }
     }

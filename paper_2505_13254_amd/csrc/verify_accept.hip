@@ -6,13 +6,19 @@
 // Stage B (one workgroup per sequence, latency-bound):
 //   greedy      every node checks in parallel whether its whole root path is confirmed by the
 //               target's argmax; the deepest confirmed node is the end of the accepted path.
-//   stochastic  the walk is serial by nature.  Per rejection the normaliser of the residual
-//               distribution needs one cooperative pass over the node's two vocabulary rows; the
-//               residual itself is never materialised: after j rejections at a node it is
-//               max(p(v) - beta_j q(v), 0) for every token not yet rejected (beta_j a scalar that
-//               accumulates Z_i / (1 - sum of rejected q)), and frozen at its value of the time for a
-//               rejected token.  The bonus token is an inverse-CDF search done as row sums of 64
-//               tokens, a scan of the row sums, and a scan inside the one row that is hit.
+//   stochastic  the walk is serial by nature, but what a node's children face is not: the state
+//               after j rejections at a node depends on the node and j alone, not on the path that
+//               led there.  Per rejection the normaliser of the residual distribution needs one
+//               cooperative pass over the node's two vocabulary rows; the residual itself is never
+//               materialised: after j rejections it is max(p(v) - beta_j q(v), 0) for every token
+//               not yet rejected (beta_j a scalar that accumulates Z_i / (1 - sum of rejected q)),
+//               and frozen at its value of the time for a rejected token.  So one workgroup per
+//               node with children runs that node's chain of rejections ahead of the walk, all
+//               nodes in parallel (k_accept_chain), and leaves each child's pair of current
+//               probabilities; the walk itself (k_accept_walk, one workgroup per sequence) then
+//               only compares uniforms with them, and draws the bonus token at the node where it
+//               stops: an inverse-CDF search done as row sums of 64 tokens, a scan of the row sums,
+//               and a scan inside the one row that is hit.
 #include <limits.h>
 
 #include "hs_common.h"
@@ -111,6 +117,13 @@ struct RowView {
   float lz;        // -ln(sum exp((x - m) / T))
   float inv_t;
   __device__ __forceinline__ float prob(int v) const { return __expf(fmaf(x[v] - m, inv_t, lz)); }
+  // tokens 4 i .. 4 i + 3 with one 16-byte load (the row must be 16-byte aligned)
+  __device__ __forceinline__ float4 prob4(int i) const {
+    const float4 f = reinterpret_cast<const float4*>(x)[i];
+    return make_float4(__expf(fmaf(f.x - m, inv_t, lz)), __expf(fmaf(f.y - m, inv_t, lz)),
+                       __expf(fmaf(f.z - m, inv_t, lz)), __expf(fmaf(f.w - m, inv_t, lz)));
+  }
+  __device__ __forceinline__ bool aligned16() const { return reinterpret_cast<uintptr_t>(x) % 16 == 0; }
 };
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -128,11 +141,139 @@ __device__ __forceinline__ double wave_incl_scan(double v, int lane) {
   return v;
 }
 
-// Weight of token v in the current (unnormalised) distribution, ignoring frozen tokens.
-__device__ __forceinline__ double weight(const RowView& p, const RowView& q, bool use_q, double beta, int v) {
-  double w = (double)p.prob(v);
-  if (use_q) w = fmax(w - beta * (double)q.prob(v), 0.0);
-  return w;
+// Sum of max(p(v) - beta q(v), 0) over the vocabulary, all threads of the workgroup; the result is
+// the same in every thread.  Terms are formed in float32 (relative error 2^-24 of p(v)), summed in
+// four float32 partial sums per thread over about V / (4 * threads) terms each, then in float64.
+__device__ __forceinline__ double residual_mass(const RowView& p, const RowView& q, double beta, int V, double* red) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float bf = (float)beta;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int v = tid;  // first token of the scalar part
+  if (p.aligned16() && q.aligned16()) {
+    // 16-byte loads, four of each row in flight per thread: a single compute unit streams the two
+    // rows, so what is in flight bounds the pass
+    const int n4 = V >> 2;
+#pragma unroll 4
+    for (int i = tid; i < n4; i += AC_THREADS) {
+      const float4 pp = p.prob4(i), qq = q.prob4(i);
+      a0 += fmaxf(fmaf(-bf, qq.x, pp.x), 0.f);
+      a1 += fmaxf(fmaf(-bf, qq.y, pp.y), 0.f);
+      a2 += fmaxf(fmaf(-bf, qq.z, pp.z), 0.f);
+      a3 += fmaxf(fmaf(-bf, qq.w, pp.w), 0.f);
+    }
+    v = (n4 << 2) + tid;
+  }
+  for (; v < V; v += AC_THREADS) a0 += fmaxf(fmaf(-bf, q.prob(v), p.prob(v)), 0.f);
+  double acc = wave_sum(((double)a0 + (double)a1) + ((double)a2 + (double)a3));
+  __syncthreads();  // red is free
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  double F = 0.0;
+  for (int w = 0; w < AC_WAVES; ++w) F += red[w];
+  return F;
+}
+
+// The same term for one token, as residual_mass forms it (used to take a frozen token's live term
+// out of the sum again).
+__device__ __forceinline__ double residual_term(const RowView& p, const RowView& q, double beta, int v) {
+  return (double)fmaxf(fmaf(-(float)beta, q.prob(v), p.prob(v)), 0.f);
+}
+// Weight of token v in the distribution the bonus token is drawn from (frozen tokens aside).
+__device__ __forceinline__ double token_weight(const RowView& p, const RowView& q, bool use_q, double beta, int v) {
+  return use_q ? residual_term(p, q, beta, v) : (double)p.prob(v);
+}
+
+// Children of local row `cur` of a sequence of n rows, ascending, into kids_sorted; returns their
+// number (at most AC_MAX_KIDS).  Called by all threads; ends with a barrier.
+__device__ __forceinline__ int gather_children(const int32_t* __restrict__ parent, int o, int n, int cur, bool any,
+                                               int* kids, int* kids_sorted, int* n_kids) {
+  const int tid = threadIdx.x;
+  if (tid == 0) *n_kids = 0;
+  __syncthreads();
+  if (any)
+    for (int i = 1 + tid; i < n; i += AC_THREADS)
+      if (parent[o + i] == cur) {
+        int pos = atomicAdd(n_kids, 1);
+        if (pos < AC_MAX_KIDS) kids[pos] = i;
+      }
+  __syncthreads();
+  const int nk = *n_kids < AC_MAX_KIDS ? *n_kids : AC_MAX_KIDS;
+  if (tid < nk) {
+    int me = kids[tid], r = 0;
+    for (int j = 0; j < nk; ++j) r += kids[j] < me ? 1 : 0;
+    kids_sorted[r] = me;
+  }
+  __syncthreads();
+  return nk;
+}
+
+// What the stochastic walk needs from a node's chain of rejections.
+struct ChainOut {
+  double* child_p;       // [NN] current target probability of the child's token when its turn comes
+  double* child_q;       // [NN] current draft probability of it
+  double* child_frozen;  // [NN] its weight in the residual after its own rejection
+  double* node_beta;     // [NN] beta and normaliser after all of the node's children were rejected
+  double* node_Z;
+};
+
+// One workgroup per tree row that has children (others leave at once): the chain of rejections at
+// that node under the ratio rule, every child rejected in turn.
+__global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
+    const float* __restrict__ target, const float* __restrict__ draft, int64_t row_stride,
+    const int32_t* __restrict__ token, const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets,
+    int B, int V, float inv_t, int max_depth, const int32_t* __restrict__ t_arg, const float* __restrict__ t_lz,
+    const int32_t* __restrict__ d_arg, const float* __restrict__ d_lz, ChainOut out) {
+  __shared__ int kids[AC_MAX_KIDS];
+  __shared__ int kids_sorted[AC_MAX_KIDS];
+  __shared__ int n_kids;
+  __shared__ int rej_tok[AC_MAX_KIDS];
+  __shared__ double rej_w[AC_MAX_KIDS];
+  __shared__ double red[AC_WAVES];
+  const int g = blockIdx.x, tid = threadIdx.x;
+  int lo = 0, hi = B;  // sequence of this row: last s with node_offsets[s] <= g
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (node_offsets[mid] <= g) lo = mid; else hi = mid;
+  }
+  const int o = node_offsets[lo];
+  const int n = node_offsets[lo + 1] - o;
+  const int cur = g - o;
+  if (cur >= n) return;  // (an empty sequence before this row's: cannot happen, offsets are monotone)
+  int depth = 0;
+  for (int j = parent[o + cur]; j >= 0; j = parent[o + j]) ++depth;
+  const int nk = gather_children(parent, o, n, cur, depth < max_depth, kids, kids_sorted, &n_kids);
+  if (nk == 0) return;
+  RowView p{target + (int64_t)(o + cur) * row_stride, 0.f, t_lz[o + cur], inv_t};
+  p.m = p.x[t_arg[o + cur]];
+  RowView q{draft + (int64_t)(o + cur) * row_stride, 0.f, d_lz[o + cur], inv_t};
+  q.m = q.x[d_arg[o + cur]];
+  double beta = 0.0, Z = 1.0, sumq = 0.0;
+  for (int j = 0; j < nk; ++j) {
+    const int c = kids_sorted[j];
+    const int x = token[o + c];
+    const double px = (double)p.prob(x);
+    const double qx = (double)q.prob(x);
+    const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
+    const double qc = qx / (1.0 - sumq);              // current q(x)
+    // rejected: p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)
+    beta += Z / (1.0 - sumq);
+    sumq += qx;
+    const double frozen = fmax(px - beta * qx, 0.0);
+    if (tid == 0) {
+      out.child_p[o + c] = pc;
+      out.child_q[o + c] = qc;
+      out.child_frozen[o + c] = frozen;
+      rej_tok[j] = x;
+      rej_w[j] = frozen;
+    }
+    double F = residual_mass(p, q, beta, V, red);  // (its barriers also publish rej_*)
+    for (int i = 0; i <= j; ++i) F += rej_w[i] - residual_term(p, q, beta, rej_tok[i]);
+    Z = F;
+  }
+  if (tid == 0) {
+    out.node_beta[o + cur] = beta;
+    out.node_Z[o + cur] = Z;
+  }
 }
 
 __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
@@ -140,18 +281,14 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
     const int32_t* __restrict__ token, const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets,
     int NN, int V, int mode, float inv_t, const float* __restrict__ uniforms, int max_depth,
     const int32_t* __restrict__ t_arg, const float* __restrict__ t_lz, const int32_t* __restrict__ d_arg,
-    const float* __restrict__ d_lz, int32_t* __restrict__ accept_len, int32_t* __restrict__ accept_path,
-    int32_t* __restrict__ bonus_token) {
+    const float* __restrict__ d_lz, ChainOut chain, int32_t* __restrict__ accept_len,
+    int32_t* __restrict__ accept_path, int32_t* __restrict__ bonus_token) {
   __shared__ int kids[AC_MAX_KIDS];
   __shared__ int kids_sorted[AC_MAX_KIDS];
   __shared__ int n_kids;
   __shared__ int rej_tok[AC_MAX_KIDS];
   __shared__ double rej_w[AC_MAX_KIDS];  // frozen weight of each rejected token
-  __shared__ double red[AC_WAVES];
   __shared__ double rowsum[AC_MAX_ROWS];
-  __shared__ int found_row;
-  __shared__ double found_excl;
-  __shared__ int found_tok;
 
   const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int o = node_offsets[s];
@@ -168,23 +305,7 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
   const bool ratio_mode = mode == HS_ACCEPT_STOCHASTIC;
   int cur = 0, len = 0;
   for (;;) {
-    // ---- children of cur, ascending
-    if (tid == 0) n_kids = 0;
-    __syncthreads();
-    if (len < max_depth)
-      for (int i = 1 + tid; i < n; i += AC_THREADS)
-        if (parent[o + i] == cur) {
-          int pos = atomicAdd(&n_kids, 1);
-          if (pos < AC_MAX_KIDS) kids[pos] = i;
-        }
-    __syncthreads();
-    const int nk = n_kids < AC_MAX_KIDS ? n_kids : AC_MAX_KIDS;
-    if (tid < nk) {
-      int me = kids[tid], r = 0;
-      for (int j = 0; j < nk; ++j) r += kids[j] < me ? 1 : 0;
-      kids_sorted[r] = me;
-    }
-    __syncthreads();
+    const int nk = gather_children(parent, o, n, cur, len < max_depth, kids, kids_sorted, &n_kids);
 
     RowView p{target + (int64_t)(o + cur) * row_stride, 0.f, t_lz[o + cur], inv_t};
     p.m = p.x[t_arg[o + cur]];
@@ -197,7 +318,7 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
     }
 
     // ---- try the children in order (every thread runs the same scalar logic)
-    double beta = 0.0, Z = 1.0, sumq = 0.0, rem = 1.0;
+    double beta = 0.0, Z = 1.0, rem = 1.0;
     int n_rej = 0, accepted = -1;
     for (int j = 0; j < nk; ++j) {
       const int c = kids_sorted[j];
@@ -218,32 +339,22 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
         __syncthreads();
         continue;
       }
-      const double qx = (double)q.prob(x);
-      const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
-      const double qc = qx / (1.0 - sumq);              // current q(x)
+      // the node's chain of rejections was run ahead of the walk (k_accept_chain)
+      const double pc = chain.child_p[o + c], qc = chain.child_q[o + c];
       if (pc >= qc || u * qc < pc) {
         accepted = c;
         break;
       }
-      // rejected: p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)
-      beta += Z / (1.0 - sumq);
-      sumq += qx;
       if (tid == 0) {
         rej_tok[n_rej] = x;
-        rej_w[n_rej] = fmax(px - beta * qx, 0.0);
+        rej_w[n_rej] = chain.child_frozen[o + c];
       }
       ++n_rej;
-      double acc = 0.0;
-      for (int v = tid; v < V; v += AC_THREADS) acc += weight(p, q, true, beta, v);
-      acc = wave_sum(acc);
-      __syncthreads();  // rej_* visible; red free
-      if (lane == 0) red[wave] = acc;
       __syncthreads();
-      double F = 0.0;
-      for (int w = 0; w < AC_WAVES; ++w) F += red[w];
-      for (int i = 0; i < n_rej; ++i) F += rej_w[i] - weight(p, q, true, beta, rej_tok[i]);
-      Z = F;
-      __syncthreads();
+    }
+    if (ratio_mode && accepted < 0 && n_rej > 0) {
+      beta = chain.node_beta[o + cur];
+      Z = chain.node_Z[o + cur];
     }
     if (accepted >= 0) {
       if (tid == 0) path[len] = accepted;
@@ -257,17 +368,41 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
     const double total = ratio_mode ? Z : rem;
     const double goal = (double)uniforms[NN + s] * total;
     const int n_rows = (V + 63) / 64;
-    for (int r = wave; r < n_rows; r += AC_WAVES) {
+    int first_row = 0;  // rows below it were summed with 16-byte loads
+    if (p.aligned16() && (!sub_q || q.aligned16())) {
+      // a lane takes four tokens, 16 lanes a row of 64, a wave four rows per trip
+      const int full_rows = V >> 6;
+      const int sub = lane >> 4, l16 = lane & 15;
+      const float bf = (float)beta;
+      for (int r0 = wave * 4; r0 < full_rows; r0 += AC_WAVES * 4) {
+        const int r = r0 + sub;
+        double w = 0.0;
+        if (r < full_rows) {
+          const float4 pp = p.prob4(r * 16 + l16);
+          if (sub_q) {
+            const float4 qq = q.prob4(r * 16 + l16);
+            w = ((double)fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) + (double)fmaxf(fmaf(-bf, qq.y, pp.y), 0.f)) +
+                ((double)fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) + (double)fmaxf(fmaf(-bf, qq.w, pp.w), 0.f));
+          } else {
+            w = ((double)pp.x + (double)pp.y) + ((double)pp.z + (double)pp.w);
+          }
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) w += __shfl_xor(w, off);
+        if (l16 == 0 && r < full_rows) rowsum[r] = w;
+      }
+      first_row = full_rows;
+    }
+    for (int r = first_row + wave; r < n_rows; r += AC_WAVES) {
       const int v = r * 64 + lane;
-      double w = v < V ? weight(p, q, sub_q, beta, v) : 0.0;
+      double w = v < V ? token_weight(p, q, sub_q, beta, v) : 0.0;
       w = wave_sum(w);
       if (lane == 0) rowsum[r] = w;
     }
     __syncthreads();
     if (tid == 0) {
       for (int i = 0; i < n_rej; ++i)
-        rowsum[rej_tok[i] >> 6] += rej_w[i] - weight(p, q, sub_q, beta, rej_tok[i]);
-      found_row = -1;
+        rowsum[rej_tok[i] >> 6] += rej_w[i] - token_weight(p, q, sub_q, beta, rej_tok[i]);
     }
     __syncthreads();
     if (wave == 0) {
@@ -295,7 +430,7 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
         row_goal = HS_INF;
       }
       const int v = row * 64 + lane;
-      double w = v < V ? weight(p, q, sub_q, beta, v) : 0.0;
+      double w = v < V ? token_weight(p, q, sub_q, beta, v) : 0.0;
       for (int i = 0; i < n_rej; ++i)
         if (rej_tok[i] == v) w = rej_w[i];
       const double incl = wave_incl_scan(w, lane);
@@ -322,7 +457,9 @@ extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
   if (B <= 0 || NN <= 0 || V <= 0) return 0;
   // per row: argmax, -ln Z and an unused Top-1 entropy, for the target and for the draft rows
   const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
-  return 2 * per_set + hs::row_topk_workspace(NN, V, 1);
+  // five doubles per row: what the rejection chains hand to the walk
+  const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256);
+  return 2 * per_set + chain + hs::row_topk_workspace(NN, V, 1);
 }
 
 extern "C" hs_status hs_verify_accept(const float* target_logits, const float* draft_logits, int64_t row_stride,
@@ -359,6 +496,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   int32_t *t_arg = nullptr, *d_arg = nullptr;
   float *t_lz = nullptr, *d_lz = nullptr;
   hs::ScanSlices slices{nullptr, nullptr, 1};
+  hs::ChainOut chain{nullptr, nullptr, nullptr, nullptr, nullptr};
   if (NN > 0) {
     hs::Carver c(workspace);
     t_arg = c.take<int32_t>(NN);
@@ -367,6 +505,11 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     d_arg = c.take<int32_t>(NN);
     d_lz = c.take<float>(NN);
     float* d_ent = c.take<float>(NN);
+    chain.child_p = c.take<double>(NN);
+    chain.child_q = c.take<double>(NN);
+    chain.child_frozen = c.take<double>(NN);
+    chain.node_beta = c.take<double>(NN);
+    chain.node_Z = c.take<double>(NN);
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
     // greedy: the merge of the row slices is done by the accept kernel (one launch less)
@@ -384,8 +527,15 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
                        slices.count, token, parent, node_offsets, max_depth, accept_len, accept_path, bonus_token);
     return hs::launch_status("accept (greedy)");
   }
+  if (mode == HS_ACCEPT_STOCHASTIC && NN > 0) {
+    hipLaunchKernelGGL(hs::k_accept_chain, dim3(NN), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits,
+                       row_stride, token, parent, node_offsets, B, V, 1.0f / temperature, max_depth, t_arg, t_lz,
+                       d_arg, d_lz, chain);
+    hs_status r = hs::launch_status("accept (rejection chains)");
+    if (r != HS_OK) return r;
+  }
   hipLaunchKernelGGL(hs::k_accept_walk, dim3(B), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits, row_stride,
                      token, parent, node_offsets, NN, V, (int)mode, 1.0f / temperature, uniforms, max_depth, t_arg,
-                     t_lz, d_arg, d_lz, accept_len, accept_path, bonus_token);
+                     t_lz, d_arg, d_lz, chain, accept_len, accept_path, bonus_token);
   return hs::launch_status("accept (stochastic)");
 }

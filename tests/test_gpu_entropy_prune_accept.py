@@ -69,6 +69,19 @@ def test_entropy_edge_rows(G):
     assert got["ent_full"][1] < 1e-8 and got["ent_topk"][1] < 1e-8
 
 
+@pytest.mark.parametrize("R,K", [(3, 1), (3, 10), (40, 1), (40, 10)])
+def test_entropy_ties_across_tiles_and_slices(G, R, K):
+    """Rows of equal or heavily tied logits over the full vocabulary: the lowest indices must win in
+    every workgroup size and slicing, and nearly every element ties with the threshold."""
+    V = 128256
+    rs = np.random.RandomState(R + K)
+    rows = np.round(rs.randn(R, V)).astype(np.float32)       # a handful of distinct values
+    rows[0] = 0.0                                            # all equal
+    rows[1] = -np.inf
+    rows[1, 100000:] = 1.5                                   # equal, and only late in the row
+    _check_entropy(G, rows, K)
+
+
 def test_entropy_row_stride_and_unaligned_rows(G):
     import torch
     import paper_2505_13254_amd as hs
