@@ -385,7 +385,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
           const float rm = row16_max(tm);
           if ((lane & 15) == 15) group_maxima[wave * 4 + (lane >> 4)] = rm;
         }
-        __syncthreads();
+        // an exchange through LDS only: the barrier must not wait for the next tiles' loads
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         const float mine = lane < n_groups ? group_maxima[lane] : -HS_INF;
         const int r = wave_rank(mine, lane, n_groups);
         const unsigned long long who = __ballot(r == K - 1 && lane < n_groups);
@@ -412,16 +413,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     if (__ballot(tm >= thr) != 0ull) {
 #pragma unroll
       for (int jj = 0; jj < SCAN_VPT; ++jj) {
-        const int idx = HS_IDX(jj);
-        unsigned long long todo = __ballot(v[jj] > thr || (v[jj] == thr && idx < thr_i));
-        if (todo != 0ull) {
-          do {
+        if (__ballot(v[jj] >= thr) != 0ull) {
+          const int idx = HS_IDX(jj);
+          unsigned long long todo = __ballot(v[jj] > thr || (v[jj] == thr && idx < thr_i));
+          while (todo != 0ull) {
             const int src = __ffsll((long long)todo) - 1;
             todo &= todo - 1ull;
             const float xv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v[jj]), src));
             const int xi = __builtin_amdgcn_readlane(idx, src);
             list_insert(xv, xi, lv, li);
-          } while (todo != 0ull);
+          }
           tighten();
         }
       }
