@@ -137,19 +137,45 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   TS(0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
+  // The first 64 entries of the work-list table are requested before anything else (the table is
+  // part of the kernel arguments, so entry `lane` exists whatever the launch), and every scalar
+  // argument the kernel needs is fetched in one batch right behind: left to itself the compiler
+  // fetches each argument where it is first used, one scalar-cache round trip after another.
+  uintx4 t0_lo = *reinterpret_cast<const uintx4*>(&a.tbl[lane]);
+  uintx4 t0_hi = *(reinterpret_cast<const uintx4*>(&a.tbl[lane]) + 1);
+  const void* const h_q = a.q;
+  const void* const h_k_prefix = a.k_prefix;
+  const void* const h_v_prefix = a.v_prefix;
+  const void* const h_k_tree = a.k_tree;
+  const void* const h_v_tree = a.v_tree;
+  const int32_t* const h_parent = a.parent;
+  void* const h_o = a.o;
+  float* const h_lse = a.lse;
+  float* const h_part = a.part;
+  const float h_scale = a.scale;
+  const int h_sp_max = a.sp_max, h_n_tbl = a.n_tbl;
   const int G = a.G, Hkv = a.Hkv, Hq = a.Hq;
+  asm volatile("" : "+v"(t0_lo), "+v"(t0_hi));  // (keeps the request here instead of inside the branch that uses it)
+  asm volatile("" ::"s"(h_q), "s"(h_k_prefix), "s"(h_v_prefix), "s"(h_k_tree), "s"(h_v_tree), "s"(h_parent), "s"(h_o),
+               "s"(h_lse), "s"(h_part), "s"(h_scale), "s"(h_sp_max), "s"(h_n_tbl), "s"(G), "s"(Hkv), "s"(Hq),
+               "s"(n_rg_max));
   int n0, M, g, rg, sp, n_sp, tiles_per_split;
   int64_t p0, L;
-  if (a.n_tbl > 0) {
+  if (h_n_tbl > 0) {
     // Work-list launch: the table of sequences sits in the kernel arguments; lane l fetches entry
     // l (and l + 64), a ballot finds the entry whose item range holds this workgroup, and its
     // fields are read from that lane: one memory round trip, no dependent offset loads.
     const int x = blockIdx.x;
     unsigned f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int base = 0; base < a.n_tbl; base += 64) {
+    for (int base = 0; base < h_n_tbl; base += 64) {
       const int idx = base + lane;
       uintx4 lo = {0x7fffffffu, 0, 0, 0}, hi = {0, 0, 0, 0};
-      if (idx < a.n_tbl) {
+      if (base == 0) {
+        if (idx < h_n_tbl) {
+          lo = t0_lo;
+          hi = t0_hi;
+        }
+      } else if (idx < h_n_tbl) {
         lo = *reinterpret_cast<const uintx4*>(&a.tbl[idx]);
         hi = *(reinterpret_cast<const uintx4*>(&a.tbl[idx]) + 1);
       }
@@ -193,10 +219,10 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   }
   const int R = G * M;
 
-  const char* kp = static_cast<const char*>(a.k_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
-  const char* vp = static_cast<const char*>(a.v_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
-  const char* kt = static_cast<const char*>(a.k_tree) + ((int64_t)n0 * Hkv + g) * MF_ROW_BYTES;
-  const char* vt = static_cast<const char*>(a.v_tree) + ((int64_t)n0 * Hkv + g) * MF_ROW_BYTES;
+  const char* kp = static_cast<const char*>(h_k_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
+  const char* vp = static_cast<const char*>(h_v_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
+  const char* kt = static_cast<const char*>(h_k_tree) + ((int64_t)n0 * Hkv + g) * MF_ROW_BYTES;
+  const char* vt = static_cast<const char*>(h_v_tree) + ((int64_t)n0 * Hkv + g) * MF_ROW_BYTES;
   const int64_t tok_stride = (int64_t)Hkv * MF_ROW_BYTES;
 
   const bool last_split = sp == n_sp - 1;
@@ -271,7 +297,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const float inv_G = 1.0f / (float)G;
   auto div_G = [&](int r) { return (int)(((float)r + 0.5f) * inv_G); };
   int my_parent = -1;
-  if (last_split && tid < M) my_parent = a.parent[n0 + tid];
+  if (last_split && tid < M) my_parent = h_parent[n0 + tid];
   bf16x8 qf[8];
   int tree_row;
   {
@@ -279,7 +305,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     const int rc = r < R ? r : R - 1;
     const int i = div_G(rc), gi = rc - i * G;
     tree_row = i;
-    const char* qrow = static_cast<const char*>(a.q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES;
+    const char* qrow = static_cast<const char*>(h_q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -310,7 +336,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
 
   // ---- Q fragments (B operand of the first product), pre-multiplied by scale * log2(e) so that
   // the scores come out of the MFMA in the log2 domain
-  const float c2 = a.scale * MF_LOG2E;
+  const float c2 = h_scale * MF_LOG2E;
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
     const bf16x8 raw = qf[kk];
@@ -645,9 +671,9 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
         *reinterpret_cast<uint2*>(stage + col * ST_ROW + d0 * 2) = pk;
       }
     const int r = row_base + col;
-    if (a.lse && half == 0 && r < R) {
+    if (h_lse && half == 0 && r < R) {
       const int i = div_G(r), gi = r - i * G;
-      a.lse[(int64_t)(n0 + i) * Hq + g * G + gi] = (m_ref + __log2f(l_tot)) * MF_LN2;
+      h_lse[(int64_t)(n0 + i) * Hq + g * G + gi] = (m_ref + __log2f(l_tot)) * MF_LN2;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's staging writes are in LDS
 #pragma unroll
@@ -657,7 +683,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
       if (ro < R) {
         const int i = div_G(ro), gi = ro - i * G;
         const uint4 val = *reinterpret_cast<const uint4*>(stage + row_l * ST_ROW + chunk * 16);
-        char* dst = static_cast<char*>(a.o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES + chunk * 16;
+        char* dst = static_cast<char*>(h_o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES + chunk * 16;
         *reinterpret_cast<uint4*>(dst) = val;
       }
     }
@@ -667,7 +693,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     if (r < R) {
       const int i = div_G(r), gi = r - i * G;
       const int64_t row = (int64_t)(n0 + i) * Hq + g * G + gi;
-      float* rec = a.part + (row * a.sp_max + sp) * ATTN_REC;
+      float* rec = h_part + (row * h_sp_max + sp) * ATTN_REC;
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
