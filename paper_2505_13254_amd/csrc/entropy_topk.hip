@@ -434,8 +434,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
   // steady-state loop requests without a condition, so that the wait before a tile's values counts
   // exactly the two younger tiles; the last tiles run through the guarded copy below.
   float b0[SCAN_VPT], b1[SCAN_VPT], b2[SCAN_VPT];
-  if (n_my > 0) load_tile(0, b0);
-  if (n_my > 1) load_tile(1, b1);
+  // (whole tiles by the unconditional loads: the guarded ones wait for each other)
+  if (n_full > 0) load_full_tile(0, b0);
+  else if (n_my > 0) load_tile(0, b0);
+  if (n_full > 1) load_full_tile(1, b1);
+  else if (n_my > 1) load_tile(1, b1);
   int tile = 0;
   for (; tile + 4 < n_full; tile += 3) {
     load_full_tile(tile + 2, b2);
