@@ -25,8 +25,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 
 
-def cpu_baseline(w, step, layers, seed):
-    """The CPU checker, as it stands, on a bounded sample of the same step; scaled to the step."""
+def cpu_baseline(w, step, layers, seed, budget_s=12.0):
+    """The CPU checker, as it stands, on a bounded sample of the same step (about `budget_s` seconds of CPU
+    work: the sample is repeated until that much time has passed), each stage scaled to the full step."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import draft_entropy_topk, tree_prune, tree_attention, verify_accept
@@ -34,44 +35,56 @@ def cpu_baseline(w, step, layers, seed):
 
     h = step.host
     rows_total = int(step.t["draft_rows"].shape[0])
-    n_rows = min(8, rows_total)
+    n_rows = min(64, rows_total)
     x = step.t["draft_rows"][:n_rows].cpu().numpy()
-    t0 = time.perf_counter()
-    draft_entropy_topk(x, w.topk, w.temperature)
-    t1 = (time.perf_counter() - t0) * rows_total / n_rows
-    t0 = time.perf_counter()
-    tree_prune(step.t["cand_parent"].cpu().numpy(), step.t["cand_logc"].cpu().numpy(),
-               step.t["cand_offsets"].cpu().numpy(), step.t["d_max"].cpu().numpy(),
-               step.t["theta"].cpu().numpy(), step.t["max_nodes"].cpu().numpy())
-    t2 = time.perf_counter() - t0
-    # attention: the first entry of the batch (one layer / one sequence), scaled by bytes
+    prune_in = [step.t[k].cpu().numpy() for k in ("cand_parent", "cand_logc", "cand_offsets", "d_max", "theta", "max_nodes")]
     no, po = h["attn_node_offsets"].numpy(), h["attn_prefix_offsets"].numpy()
-    M, L = int(no[1]), int(po[1])
 
     def np_store(t):
         import torch
         return t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy()
-    q, kp, vp = np_store(step.t["q"][:M]), np_store(step.t["k_prefix"][:L]), np_store(step.t["v_prefix"][:L])
-    kt, vt = np_store(step.t["k_tree"][:M]), np_store(step.t["v_tree"][:M])
-    t0 = time.perf_counter()
-    tree_attention(q, kp, vp, kt, vt, h["out_parent"][:M], [0, M], [0, L], h["scale"])
-    one = time.perf_counter() - t0
     es = 4 if w.dtype == "f32" else 2
-    bytes_one = (2 * (L + M) * w.Hkv * w.D + 2 * M * w.Hq * w.D) * es
-    t3 = one * step.bytes_stage3() / bytes_one
-    n4 = min(64, h["NNp"])
+    # attention: leading batch entries (layers / sequences) up to about 64 MB of K/V, scaled by bytes
+    n_ent, bytes_sample = 0, 0
+    while n_ent < len(no) - 1 and (n_ent == 0 or bytes_sample < 64e6):
+        M, L = int(no[n_ent + 1] - no[n_ent]), int(po[n_ent + 1] - po[n_ent])
+        bytes_sample += (2 * (L + M) * w.Hkv * w.D + 2 * M * w.Hq * w.D) * es
+        n_ent += 1
+    n1, p1 = int(no[n_ent]), int(po[n_ent])
+    q, kp, vp = np_store(step.t["q"][:n1]), np_store(step.t["k_prefix"][:p1]), np_store(step.t["v_prefix"][:p1])
+    kt, vt = np_store(step.t["k_tree"][:n1]), np_store(step.t["v_tree"][:n1])
+    par = step.t["attn_parent"][:n1].cpu().numpy()
+    n4 = min(256, h["NNp"])
     tl = step.t["target_logits"][:n4].cpu().numpy()
-    oo = h["out_offsets"]
-    t0 = time.perf_counter()
-    for r in range(n4):
-        np.argmax(tl[r])
-    t4 = (time.perf_counter() - t0) * h["NNp"] / n4
+    t1 = t2 = t3 = t4 = 0.0
+    reps = 0
+    start = time.perf_counter()
+    while reps == 0 or time.perf_counter() - start < budget_s:
+        t0 = time.perf_counter()
+        draft_entropy_topk(x, w.topk, w.temperature)
+        t1 += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        tree_prune(*prune_in)
+        t2 += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        tree_attention(q, kp, vp, kt, vt, par, no[:n_ent + 1], po[:n_ent + 1], h["scale"])
+        t3 += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        for r in range(n4):
+            np.argmax(tl[r])
+        t4 += time.perf_counter() - t0
+        reps += 1
+    spent = time.perf_counter() - start
+    t1 = t1 / reps * rows_total / n_rows
+    t2 = t2 / reps
+    t3 = t3 / reps * step.bytes_stage3() / bytes_sample
+    t4 = t4 / reps * h["NNp"] / n4
     total = t1 + t2 + t3 + t4
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": h["kept_draft_nodes"] / total, "unit": "tree-tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "stage1 on %d of %d rows, stage2 whole, stage3 on 1 of %d batch entries (scaled by bytes), "
-                      "stage4 argmax on %d of %d rows; each scaled to the full step" %
-                      (n_rows, rows_total, len(no) - 1, n4, h["NNp"]),
+            "sample": "%d repetitions (%.1f s of CPU work) of: stage1 on %d of %d rows, stage2 whole, stage3 on %d of %d "
+                      "batch entries (scaled by bytes), stage4 argmax on %d of %d rows; each scaled to the full step" %
+                      (reps, spent, n_rows, rows_total, n_ent, len(no) - 1, n4, h["NNp"]),
             "seconds_per_step": total,
             "stage_seconds": {"entropy_topk": t1, "prune": t2, "attention": t3, "accept": t4}}
 
