@@ -227,6 +227,35 @@ def main():
     c1.record()
     torch.cuda.synchronize()
     copy_gbps = 5 * 2 * big.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+
+    # One layer of the same workload by itself (what a single hs_tree_attention call of a model's
+    # layer loop sees): warm (same buffers, resident in the last-level cache when they fit) and cold
+    # (a 1 GiB copy streams through the caches before every call).
+    single = None
+    if layers > 1:
+        one = harness.build_step(w, args.seed, layers=1, accept_mode=0)
+        for _ in range(5):
+            one.stage3()
+        torch.cuda.synchronize()
+        ev3 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(30)]
+        for a, b in ev3[:20]:
+            a.record()
+            one.stage3()
+            b.record()
+        torch.cuda.synchronize()
+        warm = float(np.median([a.elapsed_time(b) for a, b in ev3[:20]]))
+        for a, b in ev3[20:]:
+            dst.copy_(big)
+            a.record()
+            one.stage3()
+            b.record()
+        torch.cuda.synchronize()
+        cold = float(np.median([a.elapsed_time(b) for a, b in ev3[20:]]))
+        b1 = one.bytes_stage3()
+        single = {"algorithmic_bytes": b1, "warm_ms": warm, "cold_ms": cold,
+                  "warm_gbps": b1 / (warm * 1e-3) / 1e9, "cold_gbps": b1 / (cold * 1e-3) / 1e9,
+                  "note": "event pairs cost about %.0f us each" % (event_pair_ms * 1e3)}
+        del one
     del big, dst
 
     h = step.host
@@ -262,6 +291,7 @@ def main():
                        "attention": achieved, "accept": step.bytes_stage4() / (stage_ms[3] * 1e-3) / 1e9},
         "tree_attn_hbm_gbps": achieved, "tree_attn_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "copy_ceiling_gbps": copy_gbps,
+        "tree_attn_single_layer": single,
         "roofline": {"kernel": "hs_tree_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": bytes3, "algorithmic_flops_per_launch": flops3,
