@@ -308,6 +308,20 @@ hs_status hs_kv_commit(const void* k_tree, const void* v_tree, const int32_t* no
                        void* k_cache, void* v_cache, const int64_t* cache_offsets, int64_t* cache_lens,
                        int32_t B, int32_t Hkv, int32_t D, hs_dtype dt, hs_stream stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * hs_tree_validate  (debugging aid; the tree conventions above are what every other call trusts)
+ *
+ * Checks B packed trees: node_offsets [B+1] start at 0, do not decrease and end at NN; in every
+ * sequence row 0 has parent -1 and every other row's parent is an earlier row of the sequence; and,
+ * when token [NN] is given (may be NULL), no row shares parent and token with an earlier row
+ * (siblings are distinct Top-k picks, Section 2.2).
+ * report (device, int32 [2]): the number of offending rows and the global index of the first one
+ * (-1 if none); broken offsets count every row.  Valid after the stream is synchronised.
+ * Quadratic in the fan-out when token is given: not for the hot path.
+ */
+hs_status hs_tree_validate(const int32_t* parent, const int32_t* token, const int32_t* node_offsets,
+                           int32_t B, int32_t NN, int32_t* report, hs_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,8 @@ Pin status (see tests/test_oracle_*.py):
                       deepest paths, numpy.searchsorted for the bin lookup.
   tree_expand         pinned: hand-worked two-level tree, brute-force ranking by float64 path
                       products, structural invariants, the pipeline's whole-tree builder.
+  tree_validate       pinned: hand-made trees with known defects, and validity == every row reaches
+                      the root through earlier rows.
   kv_commit           pinned: numpy.concatenate of the accepted rows, and decoding through several
                       commits equals dense causal attention (torch) over the whole sequence.
 """

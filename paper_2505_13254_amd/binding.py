@@ -42,6 +42,7 @@ _SIGNATURES = {
     "hs_tree_attention_lens": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
                                           _i32, _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
     "hs_kv_commit": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _vp]),
+    "hs_tree_validate": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
     "hs_verify_accept": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _f32, _vp, _i32,
                                     _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -331,3 +332,16 @@ def hs_verify_accept(target_logits, draft_logits, token, parent, node_offsets, m
                                 _ptr(out["bonus_token"]), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "hs_verify_accept")
     return out
+
+
+def hs_tree_validate(parent, token, node_offsets, *, stream=None) -> torch.Tensor:
+    """parent int32 [NN], token int32 [NN] or None, node_offsets int32 [B+1] (GPU).  Returns the device
+    report int32 [2]: number of offending rows, global index of the first (-1 if none)."""
+    _dev(parent, torch.int32, "parent"); _dev(node_offsets, torch.int32, "node_offsets")
+    if token is not None:
+        _dev(token, torch.int32, "token")
+    report = torch.empty(2, dtype=torch.int32, device=parent.device)
+    st = lib().hs_tree_validate(_ptr(parent), _ptr(token), _ptr(node_offsets), node_offsets.numel() - 1,
+                                parent.numel(), _ptr(report), _stream(stream))
+    _check(st, "hs_tree_validate")
+    return report

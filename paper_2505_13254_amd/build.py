@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libheterospec.so")
 SOURCES = ["api.cpp", "entropy_topk.hip", "tree_prune.hip", "tree_attention.hip", "tree_attention_mfma.hip",
-           "verify_accept.hip", "tree_expand.hip", "adaptive_control.hip", "kv_commit.hip"]
+           "verify_accept.hip", "tree_expand.hip", "adaptive_control.hip", "kv_commit.hip", "tree_validate.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          # packed-fp32 instruction selection is switched off for every device function of the library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -173,3 +173,30 @@ def test_device_loop_grows_the_pipelines_tree(G):
     ent_ref = np.zeros(cap)
     ent_ref[ref["draft_ids"]] = ref["stage1"]["ent_topk"]
     assert np.all(np.abs(got["ent"] - ent_ref) <= 1e-5 * np.maximum(np.abs(ent_ref), 1e-3))
+
+
+def test_tree_validate_matches_the_checker(G):
+    import paper_2505_13254_amd as hs
+    from oracle.tree_validate import tree_validate
+    rs = np.random.RandomState(33)
+    cases = [([-1, 0, 0, 1, 1, 2], [9, 4, 5, 7, 7, 7], [0, 6]),
+             ([-1, 0, -1, 0, 5], None, [0, 2, 5]),
+             ([0, 0, 0], None, [0, 3]),
+             ([-1, 0], None, [0, 2, 1]),
+             ([-1, 0, 1, -1, 0, 0], [1, 2, 3, 4, 5, 6], [0, 3, 3, 6])]
+    for _ in range(40):                                            # random forests, some rows damaged
+        sizes = [int(x) for x in rs.randint(0, 40, size=int(rs.randint(1, 6)))]
+        par, tok = [], []
+        for n in sizes:
+            par += [-1] + [int(rs.randint(0, i)) for i in range(1, n)] if n else []
+            tok += [int(x) for x in rs.randint(0, 6, size=n)]
+        par = np.asarray(par, np.int32)
+        for k in rs.randint(0, max(len(par), 1), size=int(rs.randint(0, 3))):
+            if len(par):
+                par[k] = int(rs.randint(-2, len(par)))
+        cases.append((par, tok if rs.uniform() < 0.5 else None, np.concatenate([[0], np.cumsum(sizes)])))
+    for par, tok, off in cases:
+        want = tree_validate(par, tok, off)
+        rep = hs.hs_tree_validate(G.dev(np.asarray(par, np.int32)), None if tok is None else G.dev(np.asarray(tok, np.int32)),
+                                  G.dev(np.asarray(off, np.int32)))
+        assert tuple(int(x) for x in G.host(rep)) == want, (list(par), tok, list(off))
