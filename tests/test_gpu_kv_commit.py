@@ -114,3 +114,72 @@ def test_decoding_loop_on_caches_with_spare_capacity(G, wid, B):
         kc, vc, lens = kv_commit(kt, vt, no, path, alen, kc, vc, co, lens)
         hs.hs_kv_commit(dkt, dvt, G.dev(no), G.dev(path), G.dev(alen), dk, dv, dco, dl)
         assert np.array_equal(_bits(dl), lens) and np.array_equal(_bits(dk), kc) and np.array_equal(_bits(dv), vc)
+
+
+def test_verify_commit_loop_over_layers(G):
+    """Three decoding steps of a two-layer model slice, each: tree attention of every layer over its
+    own cache, greedy accept walk on target logits, commit of the accepted path into every layer's
+    cache with the path the accept kernel left on the device.  The checker runs the same loop."""
+    import paper_2505_13254_amd as hs
+    from oracle import verify_accept
+    w = W.small(W.WORKLOADS[2], V=3000)
+    rs = np.random.RandomState(77)
+    layers, B, cap, max_depth = 2, 3, 200, 4
+    scale = 1.0 / float(np.sqrt(w.D))
+    co = (np.arange(B + 1) * cap).astype(np.int64)
+    lens = np.asarray([60, 0, 131], np.int64)
+    kc, vc = [], []
+    for l in range(layers):
+        fill = [W.attention_inputs(w, 40 + l, s, cap, 1, "unit") for s in range(B)]
+        kc.append(np.concatenate([p[1] for p in fill], axis=0))
+        vc.append(np.concatenate([p[2] for p in fill], axis=0))
+    dk, dv = [G.dev_store(x) for x in kc], [G.dev_store(x) for x in vc]
+    dl, dco = [G.dev(lens.copy()) for _ in range(layers)], G.dev(co)
+    for step in range(3):
+        sizes = [int(x) for x in rs.randint(2, 14, size=B)]
+        parents = [_random_parents(rs, n, back=3) for n in sizes]
+        par = np.concatenate([np.asarray(p, np.int32) for p in parents])
+        no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        NN = int(no[-1])
+        token = rs.randint(0, w.V, size=NN).astype(np.int32)
+        for s in range(B):                                  # distinct tokens among siblings
+            seen = set()
+            for i in range(1, sizes[s]):
+                while (parents[s][i], int(token[no[s] + i])) in seen:
+                    token[no[s] + i] = rs.randint(0, w.V)
+                seen.add((parents[s][i], int(token[no[s] + i])))
+        tgt = rs.randn(NN, w.V).astype(np.float32)
+        for s in range(B):                                  # plant a path of random length
+            cur = 0
+            for _ in range(int(rs.randint(0, max_depth + 1))):
+                kids = [i for i in range(sizes[s]) if parents[s][i] == cur]
+                if not kids:
+                    break
+                nxt = kids[int(rs.randint(len(kids)))]
+                tgt[no[s] + cur, token[no[s] + nxt]] = 50.0
+                cur = nxt
+        want_acc = verify_accept(tgt, None, token, par, no, 0, 1.0, None, max_depth)
+        acc = hs.hs_verify_accept(G.dev(tgt), None, G.dev(token), G.dev(par), G.dev(no), 0, 1.0, None, max_depth)
+        for k in want_acc:
+            assert np.array_equal(G.host(acc[k]), want_acc[k]), (step, k)
+        po = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        for l in range(layers):
+            parts = [W.attention_inputs(w, 100 + 10 * step + l, s, 0, sizes[s], "unit", parent=np.asarray(parents[s]))
+                     for s in range(B)]
+            q, kt, vt = (np.concatenate([p[i] for p in parts], axis=0) for i in (0, 3, 4))
+            used_k = np.concatenate([kc[l][co[s]:co[s] + lens[s]] for s in range(B)], axis=0)
+            used_v = np.concatenate([vc[l][co[s]:co[s] + lens[s]] for s in range(B)], axis=0)
+            want_o, _ = tree_attention(q, used_k, used_v, kt, vt, par, no, po, scale)
+            dkt, dvt = G.dev_store(kt), G.dev_store(vt)
+            o, _ = hs.hs_tree_attention(G.dev_store(q), dk[l], dv[l], dkt, dvt, G.dev(par), G.dev(no), dco,
+                                        torch.from_numpy(no), torch.from_numpy(co), scale,
+                                        prefix_lens=dl[l], host_prefix_lens=torch.from_numpy(lens.copy()))
+            assert np.abs(G.host(o).astype(np.float64) - want_o).max() <= 2e-2, (step, l)
+            # the path goes from the accept kernel to the commit kernel without leaving the device
+            hs.hs_kv_commit(dkt, dvt, G.dev(no), acc["accept_path"], acc["accept_len"], dk[l], dv[l], dco, dl[l])
+            kc[l], vc[l], new_lens = kv_commit(kt, vt, no, want_acc["accept_path"], want_acc["accept_len"], kc[l], vc[l],
+                                               co, lens)
+            assert np.array_equal(_bits(dl[l]), new_lens) and np.array_equal(_bits(dk[l]), kc[l])
+            assert np.array_equal(_bits(dv[l]), vc[l])
+        lens = new_lens
+        assert np.array_equal(lens - (po[1:] - po[:-1]), want_acc["accept_len"] + 1)
