@@ -22,6 +22,7 @@
  *   hs_kv_commit            the accepted path's K/V rows join the KV cache (Section 2.1: decoding
  *                           resumes behind the last accepted token)
  *   hs_tree_attention_lens  hs_tree_attention on caches stored with spare capacity
+ *   hs_tree_attention_paged, hs_kv_commit_paged   the same two on caches made of pages
  *
  * Conventions that hold for every call
  *   - Pointers are DEVICE pointers unless the parameter name starts with host_.  The caller owns
@@ -181,6 +182,23 @@ hs_status hs_tree_attention_lens(const void* q, const void* k_prefix, const void
                                  void* o, float* lse,
                                  void* workspace, size_t workspace_bytes, hs_stream stream);
 
+/* hs_tree_attention_paged: hs_tree_attention on paged KV caches.  k_pages / v_pages are pools
+ * [n_pages, page_tokens, Hkv, D]; block_table (device, int32 [B, max_blocks]) names the page of each
+ * block of page_tokens consecutive prefix tokens of a sequence; prefix_lens (device int64 [B]) and
+ * host_prefix_lens (the same on the host) give the used tokens (at most max_blocks * page_tokens).
+ * Pages of 64 tokens are built (one page is one tile of the matrix-core kernel); a prefix may
+ * hold at most 1 048 576 tokens.  The workspace query takes the sum of the prefix lengths as
+ * total_prefix.  Everything else as hs_tree_attention. */
+hs_status hs_tree_attention_paged(const void* q, const void* k_pages, const void* v_pages,
+                                  const void* k_tree, const void* v_tree,
+                                  const int32_t* parent, const int32_t* node_offsets,
+                                  const int32_t* host_node_offsets,
+                                  const int32_t* block_table, int32_t max_blocks, int32_t page_tokens,
+                                  const int64_t* prefix_lens, const int64_t* host_prefix_lens,
+                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale,
+                                  void* o, float* lse,
+                                  void* workspace, size_t workspace_bytes, hs_stream stream);
+
 /* ------------------------------------------------------------------------------------------------
  * hs_verify_accept  (Section 2.1: a drafted token x is accepted with probability
  * min(1, p(x)/p_hat(x)); on rejection a token is drawn from the residual of p and later drafts are
@@ -321,6 +339,15 @@ hs_status hs_kv_commit(const void* k_tree, const void* v_tree, const int32_t* no
  */
 hs_status hs_tree_validate(const int32_t* parent, const int32_t* token, const int32_t* node_offsets,
                            int32_t B, int32_t NN, int32_t* report, hs_stream stream);
+
+/* hs_kv_commit_paged: hs_kv_commit into paged caches (pools and block_table as in
+ * hs_tree_attention_paged; any page_tokens >= 1).  The pages a sequence grows into must already be
+ * in its block-table row; a sequence takes at most max_blocks * page_tokens tokens. */
+hs_status hs_kv_commit_paged(const void* k_tree, const void* v_tree, const int32_t* node_offsets,
+                             const int32_t* accept_path, const int32_t* accept_len, int32_t max_depth,
+                             void* k_pages, void* v_pages, const int32_t* block_table, int32_t max_blocks,
+                             int32_t page_tokens, int64_t* cache_lens,
+                             int32_t B, int32_t Hkv, int32_t D, hs_dtype dt, hs_stream stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,9 @@ Pin status (see tests/test_oracle_*.py):
   tree_validate       pinned: hand-made trees with known defects, and validity == every row reaches
                       the root through earlier rows.
   kv_commit           pinned: numpy.concatenate of the accepted rows, and decoding through several
-                      commits equals dense causal attention (torch) over the whole sequence.
+                      commits equals dense causal attention (torch) over the whole sequence; the
+                      paged forms (kv_commit_paged, gather_pages) by scatter / gather identity and
+                      equality with the dense commit.
 """
 from .entropy_topk import draft_entropy_topk
 from .tree_prune import tree_prune

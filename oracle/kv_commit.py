@@ -35,3 +35,40 @@ def kv_commit(k_tree, v_tree, node_offsets, accept_path, accept_len, k_cache, v_
             v_cache[dst] = v_tree[n0 + r]
             lens[s] += 1
     return k_cache, v_cache, lens
+
+
+def gather_pages(pages, block_table, lens, page_tokens=None):
+    """Paged cache -> packed dense cache.  pages [n_pages, page_tokens, Hkv, D]; block_table int [B, max_blocks]
+    (page of each block of page_tokens consecutive tokens of a sequence); lens [B] used tokens.
+    Returns (dense [sum lens, Hkv, D], offsets int64 [B+1]): token t of sequence s is row
+    t % page_tokens of page block_table[s, t // page_tokens]."""
+    pages = np.asarray(pages)
+    pt = pages.shape[1] if page_tokens is None else page_tokens
+    rows, offs = [], [0]
+    for s, n in enumerate(lens):
+        for t in range(int(n)):
+            rows.append(pages[int(block_table[s][t // pt]), t % pt])
+        offs.append(offs[-1] + int(n))
+    dense = np.stack(rows) if rows else np.zeros((0,) + pages.shape[2:], pages.dtype)
+    return dense, np.asarray(offs, np.int64)
+
+
+def kv_commit_paged(k_tree, v_tree, node_offsets, accept_path, accept_len, k_pages, v_pages, block_table, cache_lens):
+    """kv_commit into paged caches: the same rows, appended at token positions cache_lens[s] onwards of
+    sequence s, each landing in its page; a sequence takes at most max_blocks * page_tokens tokens."""
+    k_pages, v_pages = np.array(k_pages, copy=True), np.array(v_pages, copy=True)
+    lens = np.array(cache_lens, dtype=np.int64, copy=True)
+    pt = k_pages.shape[1]
+    for s in range(len(node_offsets) - 1):
+        n0, n1 = int(node_offsets[s]), int(node_offsets[s + 1])
+        if n1 == n0:
+            continue
+        rows = [0] + [int(r) for r in accept_path[s][:int(accept_len[s])]]
+        room = len(block_table[s]) * pt - int(lens[s])
+        for r in rows[:max(room, 0)]:
+            t = int(lens[s])
+            page = int(block_table[s][t // pt])
+            k_pages[page, t % pt] = k_tree[n0 + r]
+            v_pages[page, t % pt] = v_tree[n0 + r]
+            lens[s] += 1
+    return k_pages, v_pages, lens

@@ -41,6 +41,10 @@ _SIGNATURES = {
                                      _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
     "hs_tree_attention_lens": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
                                           _i32, _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "hs_tree_attention_paged": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _i32,
+                                           _i32, _i32, _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "hs_kv_commit_paged": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _vp, _i32, _i32, _i32,
+                                      _c.c_int, _vp]),
     "hs_kv_commit": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _vp]),
     "hs_tree_validate": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
@@ -275,6 +279,61 @@ def hs_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offset
         st = lib().hs_tree_attention_lens(*head, _ptr(prefix_lens), _vp(hl.data_ptr()), *tail)
     _check(st, "hs_tree_attention")
     return out, lse
+
+
+def hs_tree_attention_paged(q, k_pages, v_pages, k_tree, v_tree, parent, node_offsets, host_node_offsets, block_table,
+                            prefix_lens, host_prefix_lens, scale: float, *, want_lse: bool = False,
+                            out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                            ws: Optional[torch.Tensor] = None, stream=None):
+    """q [NN,Hq,D]; k_pages, v_pages [n_pages, page_tokens, Hkv, D]; k_tree, v_tree [NN,Hkv,D]; parent int32 [NN],
+    node_offsets int32 [B+1], block_table int32 [B, max_blocks], prefix_lens int64 [B] on the GPU;
+    host_node_offsets and host_prefix_lens the same on the CPU.  Returns (o, lse or None)."""
+    dt = _dtype_code(q)
+    for name, t in (("q", q), ("k_pages", k_pages), ("v_pages", v_pages), ("k_tree", k_tree), ("v_tree", v_tree)):
+        _dev(t, q.dtype, name)
+    _dev(parent, torch.int32, "parent"); _dev(node_offsets, torch.int32, "node_offsets")
+    _dev(block_table, torch.int32, "block_table"); _dev(prefix_lens, torch.int64, "prefix_lens")
+    hno = host_node_offsets.to(dtype=torch.int32, device="cpu").contiguous()
+    hl = host_prefix_lens.to(dtype=torch.int64, device="cpu").contiguous()
+    NN, Hq, D = q.shape
+    Hkv = k_tree.shape[1]
+    B = hno.numel() - 1
+    if block_table.dim() != 2 or block_table.shape[0] != B or k_pages.dim() != 4:
+        raise ValueError("block_table must be [B, max_blocks] and the pools [n_pages, page_tokens, Hkv, D]")
+    dev = q.device
+    if out is None:
+        out = torch.empty_like(q)
+    if want_lse and lse is None:
+        lse = torch.empty((NN, Hq), dtype=torch.float32, device=dev)
+    need = lib().hs_tree_attention_workspace(B, NN, int(hl.sum()), Hq, Hkv, D, dt)
+    if ws is None:
+        ws = workspace(need, dev)
+    st = lib().hs_tree_attention_paged(_ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(k_tree), _ptr(v_tree), _ptr(parent),
+                                       _ptr(node_offsets), _vp(hno.data_ptr()), _ptr(block_table), block_table.shape[1],
+                                       k_pages.shape[1], _ptr(prefix_lens), _vp(hl.data_ptr()), B, Hq, Hkv, D, dt,
+                                       float(scale), _ptr(out), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(),
+                                       _stream(stream))
+    _check(st, "hs_tree_attention_paged")
+    return out, lse
+
+
+def hs_kv_commit_paged(k_tree, v_tree, node_offsets, accept_path, accept_len, k_pages, v_pages, block_table, cache_lens,
+                       *, stream=None):
+    """As hs_kv_commit, into pools k_pages, v_pages [n_pages, page_tokens, Hkv, D] through block_table int32
+    [B, max_blocks]; cache_lens int64 [B] is updated in place."""
+    dt = _dtype_code(k_tree)
+    for name, t in (("k_tree", k_tree), ("v_tree", v_tree), ("k_pages", k_pages), ("v_pages", v_pages)):
+        _dev(t, k_tree.dtype, name)
+    _dev(node_offsets, torch.int32, "node_offsets"); _dev(accept_path, torch.int32, "accept_path")
+    _dev(accept_len, torch.int32, "accept_len"); _dev(block_table, torch.int32, "block_table")
+    _dev(cache_lens, torch.int64, "cache_lens")
+    B = node_offsets.numel() - 1
+    Hkv, D = k_tree.shape[1], k_tree.shape[2]
+    st = lib().hs_kv_commit_paged(_ptr(k_tree), _ptr(v_tree), _ptr(node_offsets), _ptr(accept_path), _ptr(accept_len),
+                                  accept_path.shape[1], _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                  block_table.shape[1], k_pages.shape[1], _ptr(cache_lens), B, Hkv, D, dt, _stream(stream))
+    _check(st, "hs_kv_commit_paged")
+    return cache_lens
 
 
 def hs_kv_commit(k_tree, v_tree, node_offsets, accept_path, accept_len, k_cache, v_cache, cache_offsets, cache_lens,

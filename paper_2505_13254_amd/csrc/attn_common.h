@@ -52,7 +52,7 @@ struct SeqEntry {
   int n0;               // first tree row of the sequence (global row number)
   int M;                // tree rows
   int L;                // prefix tokens
-  long long p0;         // first prefix token (global)
+  long long p0;         // first prefix token (global); paged caches: first entry of the sequence's block-table row
   int tiles_per_split;
   short n_sp, n_rg;
 };
@@ -69,6 +69,8 @@ struct AttnArgs {
   const int32_t* node_offsets;
   const int64_t* prefix_offsets;
   const int64_t* prefix_lens;  // used tokens of each sequence's prefix region; NULL: the whole region
+  const int32_t* block_table;  // paged caches: page of each 64-token block, row s at s * max_blocks; else NULL
+  int max_blocks;
   int B, Hq, Hkv, G;
   float scale;
   int split_len;   // prefix tokens per split (multiple of 64)

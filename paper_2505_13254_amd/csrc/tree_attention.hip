@@ -33,7 +33,7 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n0 = a.node_offsets[s];
   const int M = a.node_offsets[s + 1] - n0;
-  const int64_t p0 = a.prefix_offsets[s];
+  const int64_t p0 = a.block_table != nullptr ? 0 : a.prefix_offsets[s];
   const int64_t L = prefix_len_of(a, s);
   if (M <= 0) return;
   const int G = a.G, Hkv = a.Hkv, Hq = a.Hq;
@@ -48,8 +48,9 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
   if (rb >= n_rb || sp >= n_sp) return;
 
   const T* q = static_cast<const T*>(a.q);
-  const T* kp = static_cast<const T*>(a.k_prefix) + p0 * Hkv * D;
-  const T* vp = static_cast<const T*>(a.v_prefix) + p0 * Hkv * D;
+  const bool paged = a.block_table != nullptr;  // prefix tiles are pages of GEN_TILE tokens
+  const T* kp = static_cast<const T*>(a.k_prefix) + (paged ? 0 : p0) * Hkv * D;
+  const T* vp = static_cast<const T*>(a.v_prefix) + (paged ? 0 : p0) * Hkv * D;
   const T* kt = static_cast<const T*>(a.k_tree) + (int64_t)n0 * Hkv * D;
   const T* vt = static_cast<const T*>(a.v_tree) + (int64_t)n0 * Hkv * D;
 
@@ -87,14 +88,17 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
     const int64_t limit = tree ? M : k_hi;
     const T* ksrc = tree ? kt : kp;
     const T* vsrc = tree ? vt : vp;
+    // where the tile's first key lives: in place, or in the page the block table names
+    const int64_t where = (!tree && paged) ? (int64_t)a.block_table[(int64_t)s * a.max_blocks + base / GEN_TILE] * GEN_TILE
+                                           : base;
     __syncthreads();  // previous tile fully consumed (and Qs / par written, first time)
     for (int e = tid; e < GEN_TILE * D; e += GEN_THREADS) {
       const int j = e / D, d = e - j * D;
       const int64_t key = base + j;
       float kv = 0.f, vv = 0.f;
       if (key < limit) {
-        kv = load_elem<T>(ksrc + (key * Hkv + g) * D + d);
-        vv = load_elem<T>(vsrc + (key * Hkv + g) * D + d);
+        kv = load_elem<T>(ksrc + ((where + j) * Hkv + g) * D + d);
+        vv = load_elem<T>(vsrc + ((where + j) * Hkv + g) * D + d);
       }
       Ks[j][d] = kv;
       Vs[j][d] = vv;
@@ -287,11 +291,12 @@ struct ListPlan {
 };
 
 // Splits of a sequence of `tiles` prefix tiles when items should hold about `target` tiles.
-static inline int plan_splits(int tiles, int target, int sp_cap) {
+static inline int plan_splits(int tiles, int target, int sp_cap, bool paged = false) {
   int n = (tiles + target / 2) / target;
   const int most = tiles / PLAN_MIN_SPLIT_TILES;
   if (n > most) n = most;
   if (n > sp_cap) n = sp_cap;
+  if (paged && n < (tiles + 255) / 256) n = (tiles + 255) / 256;  // the kernel holds the pages of 256 tiles
   return n < 1 ? 1 : n;
 }
 
@@ -333,7 +338,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
     int64_t items = 0;
     for (int i = 0; i < n; ++i) {
       const Seq& q = seqs[i];
-      const int nsp = plan_splits(q.tiles, target, sp_cap);
+      const int nsp = plan_splits(q.tiles, target, sp_cap, a.block_table != nullptr);
       const int per = (q.tiles + nsp - 1) / nsp;
       const float big = PLAN_ITEM_US + (float)(per + q.ttiles) * plan_tile_us(q.waves0);
       const float one = PLAN_ITEM_US + (float)per * plan_tile_us(q.waves0);
@@ -360,7 +365,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
   int nsp_of[ATTN_TBL], per_of[ATTN_TBL];
   for (int i = 0; i < n; ++i) {
     const Seq& q = seqs[i];
-    nsp_of[i] = plan_splits(q.tiles, best.target, sp_cap);
+    nsp_of[i] = plan_splits(q.tiles, best.target, sp_cap, a.block_table != nullptr);
     per_of[i] = (q.tiles + nsp_of[i] - 1) / nsp_of[i];
     if (per_of[i] < 1) per_of[i] = 1;
     cost[i] = (float)per_of[i] * plan_tile_us(q.waves0);
@@ -377,7 +382,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
     e.n0 = hno[q.s];
     e.M = q.M;
     e.L = (int)(hlens != nullptr ? hlens[q.s] : hpo[q.s + 1] - hpo[q.s]);
-    e.p0 = hpo[q.s];
+    e.p0 = a.block_table != nullptr ? (long long)q.s * a.max_blocks : hpo[q.s];
     e.tiles_per_split = per_of[i];
     e.n_sp = (short)nsp_of[i];
     e.n_rg = (short)q.rg;
@@ -420,26 +425,44 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
                                 lse, workspace, workspace_bytes, stream);
 }
 
-extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix, const void* v_prefix,
-                                            const void* k_tree, const void* v_tree, const int32_t* parent,
-                                            const int32_t* node_offsets, const int64_t* prefix_offsets,
-                                            const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
-                                            const int64_t* prefix_lens, const int64_t* host_prefix_lens, int32_t B,
-                                            int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
-                                            float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
-  clear_error();
+// The three entry points in one: dense prefix regions (prefix_lens NULL), regions with spare
+// capacity (prefix_lens given), pages (block_table given: k_prefix / v_prefix are the page pools,
+// the offset arrays are absent).
+static hs_status attention_impl(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
+                                const void* v_tree, const int32_t* parent, const int32_t* node_offsets,
+                                const int64_t* prefix_offsets, const int32_t* host_node_offsets,
+                                const int64_t* host_prefix_offsets, const int64_t* prefix_lens,
+                                const int64_t* host_prefix_lens, const int32_t* block_table, int32_t max_blocks,
+                                int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
+                                float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
+  const bool paged = block_table != nullptr;
   HS_REQUIRE(B >= 0, HS_ERR_SHAPE, "hs_tree_attention: B=%d", B);
   HS_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, HS_ERR_SHAPE, "hs_tree_attention: Hq=%d must be a multiple of Hkv=%d",
              Hq, Hkv);
   HS_REQUIRE(D == 64 || D == 128, HS_ERR_UNSUPPORTED, "hs_tree_attention: head dimension %d (64 and 128 are built)", D);
   HS_REQUIRE(dt == HS_F32 || dt == HS_BF16, HS_ERR_SHAPE, "hs_tree_attention: unknown dtype %d", (int)dt);
   if (B == 0) return HS_OK;
-  HS_REQUIRE(host_node_offsets && host_prefix_offsets && node_offsets && prefix_offsets, HS_ERR_NULL,
+  HS_REQUIRE(host_node_offsets && node_offsets && (paged || (host_prefix_offsets && prefix_offsets)), HS_ERR_NULL,
              "hs_tree_attention: offset arrays (device and host copies) are required");
-  HS_REQUIRE(host_node_offsets[0] == 0 && host_prefix_offsets[0] == 0, HS_ERR_SHAPE,
+  HS_REQUIRE(host_node_offsets[0] == 0 && (paged || host_prefix_offsets[0] == 0), HS_ERR_SHAPE,
              "hs_tree_attention: offsets must start at 0");
+  HS_REQUIRE(!paged || (prefix_lens && host_prefix_lens && max_blocks >= 0), HS_ERR_NULL,
+             "hs_tree_attention_paged: prefix lengths (device and host) are required");
+  int64_t total_used = 0;
   for (int s = 0; s < B; ++s) {
     const int M = host_node_offsets[s + 1] - host_node_offsets[s];
+    if (paged) {
+      HS_REQUIRE(M >= 0, HS_ERR_SHAPE, "hs_tree_attention: offsets decrease at sequence %d", s);
+      HS_REQUIRE(host_prefix_lens[s] >= 0 && host_prefix_lens[s] <= (int64_t)max_blocks * 64, HS_ERR_SHAPE,
+                 "hs_tree_attention_paged: prefix length of sequence %d exceeds its %d blocks", s, max_blocks);
+      // (a key split holds the pages of at most 256 tiles, a sequence has at most 64 splits)
+      HS_REQUIRE(host_prefix_lens[s] <= (int64_t)64 * 256 * 64, HS_ERR_UNSUPPORTED,
+                 "hs_tree_attention_paged: prefix of sequence %d is longer than %d tokens", s, 64 * 256 * 64);
+      total_used += host_prefix_lens[s];
+      HS_REQUIRE(M <= MAX_TREE_ROWS, HS_ERR_UNSUPPORTED, "hs_tree_attention: sequence %d has %d tree rows (limit %d)",
+                 s, M, MAX_TREE_ROWS);
+      continue;
+    }
     HS_REQUIRE(M >= 0 && host_prefix_offsets[s + 1] >= host_prefix_offsets[s], HS_ERR_SHAPE,
                "hs_tree_attention: offsets decrease at sequence %d", s);
     HS_REQUIRE(M <= MAX_TREE_ROWS, HS_ERR_UNSUPPORTED, "hs_tree_attention: sequence %d has %d tree rows (limit %d)", s,
@@ -451,7 +474,7 @@ extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix,
   HS_REQUIRE((prefix_lens == nullptr) == (host_prefix_lens == nullptr), HS_ERR_NULL,
              "hs_tree_attention: prefix_lens and host_prefix_lens go together");
   const int NN = host_node_offsets[B];
-  const int64_t total_prefix = host_prefix_offsets[B];
+  const int64_t total_prefix = paged ? total_used : host_prefix_offsets[B];
   if (NN == 0) return HS_OK;
   HS_REQUIRE(q && k_tree && v_tree && parent && o, HS_ERR_NULL, "hs_tree_attention: NULL tensor");
   HS_REQUIRE(total_prefix == 0 || (k_prefix && v_prefix), HS_ERR_NULL, "hs_tree_attention: NULL prefix cache");
@@ -466,6 +489,7 @@ extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix,
   AttnArgs a;
   a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_tree = k_tree; a.v_tree = v_tree;
   a.parent = parent; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets; a.prefix_lens = prefix_lens;
+  a.block_table = block_table; a.max_blocks = max_blocks;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
   a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
   a.n_tbl = 0; a.n_items = 0;
@@ -480,6 +504,10 @@ extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix,
     plan = plan_attention(host_node_offsets, host_prefix_offsets, host_prefix_lens, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
     while (plan.sp_max > sp_cap) {
       plan.split_len *= 2;
+      plan.sp_max = splits_of(plan.max_L, plan.split_len);
+    }
+    if (paged && plan.split_len > 256 * 64) {  // the matrix-core kernel holds the pages of 256 tiles per split
+      plan.split_len = 256 * 64;
       plan.sp_max = splits_of(plan.max_L, plan.split_len);
     }
     a.split_len = plan.split_len; a.sp_max = plan.sp_max; a.n_rb_max = plan.n_rb_max;
@@ -513,4 +541,33 @@ extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix,
     return launch_status("tree attention combine");
   }
   return HS_OK;
+}
+
+extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix, const void* v_prefix,
+                                            const void* k_tree, const void* v_tree, const int32_t* parent,
+                                            const int32_t* node_offsets, const int64_t* prefix_offsets,
+                                            const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                                            const int64_t* prefix_lens, const int64_t* host_prefix_lens, int32_t B,
+                                            int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
+                                            float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
+  clear_error();
+  return attention_impl(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offsets, prefix_offsets, host_node_offsets,
+                        host_prefix_offsets, prefix_lens, host_prefix_lens, nullptr, 0, B, Hq, Hkv, D, dt, scale, o, lse,
+                        workspace, workspace_bytes, stream);
+}
+
+extern "C" hs_status hs_tree_attention_paged(const void* q, const void* k_pages, const void* v_pages,
+                                             const void* k_tree, const void* v_tree, const int32_t* parent,
+                                             const int32_t* node_offsets, const int32_t* host_node_offsets,
+                                             const int32_t* block_table, int32_t max_blocks, int32_t page_tokens,
+                                             const int64_t* prefix_lens, const int64_t* host_prefix_lens, int32_t B,
+                                             int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
+                                             float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
+  clear_error();
+  HS_REQUIRE(page_tokens == 64, HS_ERR_UNSUPPORTED, "hs_tree_attention_paged: page_tokens=%d (pages of 64 tokens are built)",
+             page_tokens);
+  HS_REQUIRE(B == 0 || block_table, HS_ERR_NULL, "hs_tree_attention_paged: NULL block_table");
+  return attention_impl(q, k_pages, v_pages, k_tree, v_tree, parent, node_offsets, nullptr, host_node_offsets, nullptr,
+                        prefix_lens, host_prefix_lens, block_table, max_blocks, B, Hq, Hkv, D, dt, scale, o, lse,
+                        workspace, workspace_bytes, stream);
 }

@@ -124,12 +124,15 @@ __device__ unsigned long long dbg_ts[4096 * 16];
 #endif
 #define MF_PIN() __builtin_amdgcn_sched_barrier(0)
 
+// PAGED: the prefix K/V live in pages of MF_TILE tokens ([page, token, Hkv, D]); a tile is a page.
+template <bool PAGED>
 __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_max) {
   __shared__ __attribute__((aligned(16))) char lds_k[MF_NBUF][MF_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) char lds_v[MF_NBUF][MF_TILE_BYTES];
   __shared__ unsigned anc[MF_MAX_M * 8];
   __shared__ int par_lds[MF_MAX_M];
   __shared__ int exact_flag;
+  __shared__ int page_lds[PAGED ? 256 : 1];
 
 #ifdef HS_TS
   unsigned long long ts_[16] = {0};
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     const int s = blockIdx.y;
     n0 = a.node_offsets[s];
     M = a.node_offsets[s + 1] - n0;
-    p0 = a.prefix_offsets[s];
+    p0 = PAGED ? (int64_t)s * a.max_blocks : a.prefix_offsets[s];
     L = prefix_len_of(a, s);
     if (M <= 0) return;
     n_sp = splits_of(L, a.split_len);
@@ -219,8 +222,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   }
   const int R = G * M;
 
-  const char* kp = static_cast<const char*>(h_k_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
-  const char* vp = static_cast<const char*>(h_v_prefix) + (p0 * Hkv + g) * MF_ROW_BYTES;
+  const char* kp = static_cast<const char*>(h_k_prefix) + ((PAGED ? 0 : p0) * Hkv + g) * MF_ROW_BYTES;
+  const char* vp = static_cast<const char*>(h_v_prefix) + ((PAGED ? 0 : p0) * Hkv + g) * MF_ROW_BYTES;
   const char* kt = static_cast<const char*>(h_k_tree) + ((int64_t)n0 * Hkv + g) * MF_ROW_BYTES;
   const char* vt = static_cast<const char*>(h_v_tree) + ((int64_t)n0 * Hkv + g) * MF_ROW_BYTES;
   const int64_t tok_stride = (int64_t)Hkv * MF_ROW_BYTES;
@@ -245,9 +248,23 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const unsigned dma_chunk = (unsigned)(((tid & 15) ^ swz_key(dma_row)) << 4);         // swz_key(row + 32) == swz_key(row)
   const unsigned lane_off0 = (unsigned)(dma_row * (int)tok_stride) + dma_chunk;        // inside a full tile: fixed
   const unsigned lane_off1 = lane_off0 + (unsigned)(32 * (int)tok_stride);
+  // Paged caches: the pages of this split's tiles (at most 256) are staged in LDS; the requests
+  // go out here, before the Q rows are asked for, so that waiting for them waits for nothing else.
+  // A tile's page is then one LDS read.  (That read is older than every fragment read requested
+  // after it, so the windows' counted LDS waits at most wait for one fragment more than they need.)
+  if (PAGED) {
+    const int32_t* bt = a.block_table + p0 + k_lo / MF_TILE;
+    if (tid < n_ptiles) page_lds[tid] = bt[tid];
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
+  // byte offset, from kp / vp, of prefix tile t of this split
+  auto prefix_tile = [&](int t) -> int64_t {
+    if (!PAGED) return (k_lo + (int64_t)t * MF_TILE) * tok_stride;
+    return (int64_t)__builtin_amdgcn_readfirstlane(page_lds[t]) * MF_TILE * tok_stride;
+  };
   // a full tile of prefix keys into ring slot `slot`
   auto issue_full = [&](int t, int slot) {
-    const int64_t tile_off = (k_lo + (int64_t)t * MF_TILE) * tok_stride;
+    const int64_t tile_off = prefix_tile(t);
     const unsigned ring = (unsigned)slot * MF_TILE_BYTES + wave_lds;
     lds_dma_tile(kp + tile_off, vp + tile_off, lane_off0, lane_off1, lds_k_addr + ring, lds_v_addr + ring,
                  lds_k_addr + ring + MF_BLOCK_BYTES, lds_v_addr + ring + MF_BLOCK_BYTES);
@@ -267,7 +284,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     const int r0 = dma_row < rows ? dma_row : rows - 1;
     const int r1 = dma_row + 32 < rows ? dma_row + 32 : rows - 1;
     const unsigned ring = (unsigned)(t % MF_NBUF) * MF_TILE_BYTES + wave_lds;
-    lds_dma_tile(ks + base * tok_stride, vs + base * tok_stride, (unsigned)(r0 * (int)tok_stride) + dma_chunk,
+    const int64_t off = tree ? base * tok_stride : prefix_tile(t);
+    lds_dma_tile(ks + off, vs + off, (unsigned)(r0 * (int)tok_stride) + dma_chunk,
                  (unsigned)(r1 * (int)tok_stride) + dma_chunk, lds_k_addr + ring, lds_v_addr + ring,
                  lds_k_addr + ring + MF_BLOCK_BYTES, lds_v_addr + ring + MF_BLOCK_BYTES);
   };
@@ -724,7 +742,8 @@ hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t str
   const int n_rg_max = (a.G * max_tree_rows + MF_ROWS - 1) / MF_ROWS;
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);
   if (a.n_tbl > 0) grid = dim3((unsigned)a.n_items, 1u);
-  hipLaunchKernelGGL(k_attn_mfma, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
+  if (a.block_table != nullptr) hipLaunchKernelGGL(k_attn_mfma<true>, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
+  else hipLaunchKernelGGL(k_attn_mfma<false>, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
   return launch_status("tree attention (mfma)");
 }
 

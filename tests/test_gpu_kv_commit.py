@@ -183,3 +183,66 @@ def test_verify_commit_loop_over_layers(G):
             assert np.array_equal(_bits(dv[l]), vc[l])
         lens = new_lens
         assert np.array_equal(lens - (po[1:] - po[:-1]), want_acc["accept_len"] + 1)
+
+
+def _paginate(rs, dense, offs, lens, max_blocks, n_spare=5, pt=64):
+    """Scatters a packed dense cache into a page pool under a random block table."""
+    B = len(lens)
+    n_pages = B * max_blocks + n_spare
+    table = rs.permutation(n_pages)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+    pool = np.zeros((n_pages, pt) + dense.shape[1:], dense.dtype)
+    if dense.dtype == np.uint16:
+        pool[:] = 0x7fc0                                             # NaN in unused slots: must never be read
+    else:
+        pool[:] = np.nan
+    for s in range(B):
+        for t in range(int(lens[s])):
+            pool[table[s, t // pt], t % pt] = dense[offs[s] + t]
+    return pool, table
+
+
+@pytest.mark.parametrize("wid,B", [(1, 3), (2, 4), (5, 100)])
+def test_paged_attention_and_commit(G, wid, B):
+    """Attention over paged caches equals the checker's attention over the gathered dense cache; the
+    paged commit equals the checker's; two rounds."""
+    import paper_2505_13254_amd as hs
+    from oracle.kv_commit import gather_pages, kv_commit_paged
+    w = W.small(W.WORKLOADS[wid], B=B)
+    rs = np.random.RandomState(20 + wid)
+    tol = 1e-4 if w.dtype == "f32" else 2e-2
+    max_depth = 5
+    lens = np.asarray([int(x) for x in rs.randint(0, 300 if B < 50 else 80, size=B)], np.int64)
+    if B == 4:
+        lens[1] = 2700                                               # long enough to be cut into key splits
+    max_blocks = int((lens.max() + 2 * (max_depth + 1) + 63) // 64)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    fill = [W.attention_inputs(w, 1, s, int(lens[s]), 1, "unit") for s in range(B)]
+    dense_k, dense_v = (np.concatenate([p[i] for p in fill], axis=0) for i in (1, 2))
+    state = np.random.RandomState(5)
+    pool_k, table = _paginate(state, dense_k, offs, lens, max_blocks)
+    pool_v, _ = _paginate(np.random.RandomState(5), dense_v, offs, lens, max_blocks)
+    dk, dv, dt_, dl = G.dev_store(pool_k), G.dev_store(pool_v), G.dev(table), G.dev(lens)
+    for step in range(2):
+        sizes = [int(x) for x in rs.randint(0 if step else 1, 12, size=B)]
+        parents = [_random_parents(rs, n) if n else [] for n in sizes]
+        parts = [W.attention_inputs(w, 2 + step, s, 0, sizes[s], "unit", parent=np.asarray(parents[s])) for s in range(B)]
+        q, kt, vt = (np.concatenate([p[i] for p in parts], axis=0) for i in (0, 3, 4))
+        par = np.concatenate([np.asarray(p, np.int32) for p in parents]).astype(np.int32)
+        no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        gk, po = gather_pages(pool_k, table, lens)
+        gv, _ = gather_pages(pool_v, table, lens)
+        want_o, _ = tree_attention(q, gk, gv, kt, vt, par, no, po, 1.0 / np.sqrt(w.D))
+        dkt, dvt = G.dev_store(kt), G.dev_store(vt)
+        o, _ = hs.hs_tree_attention_paged(G.dev_store(q), dk, dv, dkt, dvt, G.dev(par), G.dev(no), torch.from_numpy(no),
+                                          dt_, dl, torch.from_numpy(lens.copy()), 1.0 / float(np.sqrt(w.D)))
+        assert np.abs(G.host(o).astype(np.float64) - want_o).max() <= tol, step
+        path = np.full((B, max_depth), -1, np.int32)
+        alen = np.zeros(B, np.int32)
+        for s in range(B):
+            p, n = _random_path(rs, parents[s], max_depth)
+            path[s, :n], alen[s] = p, n
+        pool_k, pool_v, lens = kv_commit_paged(kt, vt, no, path, alen, pool_k, pool_v, table, lens)
+        hs.hs_kv_commit_paged(dkt, dvt, G.dev(no), G.dev(path), G.dev(alen), dk, dv, dt_, dl)
+        assert np.array_equal(_bits(dl), lens)
+        raw = lambda x: x.view(np.uint32) if x.dtype == np.float32 else x       # (unused slots hold NaN)
+        assert np.array_equal(raw(_bits(dk)), raw(pool_k)) and np.array_equal(raw(_bits(dv)), raw(pool_v))

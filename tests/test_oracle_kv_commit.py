@@ -78,3 +78,46 @@ def test_decoding_through_commits_is_causal_attention():
     q, k, v = (torch.from_numpy(x).double().permute(1, 0, 2) for x in (Q, K, V))
     ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True, scale=0.3).permute(1, 0, 2).numpy()
     assert np.allclose(o, ref[pos:], atol=1e-12)
+
+
+def test_paged_cache_is_the_dense_cache_in_other_places():
+    """Scattering a dense cache into pages under a random block table and gathering it back is the
+    identity, and a paged commit followed by the gather equals the dense commit."""
+    from oracle.kv_commit import gather_pages, kv_commit_paged
+    rs = np.random.RandomState(3)
+    B, pt, max_blocks, Hkv, D = 3, 4, 5, 2, 8
+    lens = np.asarray([7, 0, 13], np.int64)
+    table = rs.permutation(B * max_blocks + 3)[:B * max_blocks].reshape(B, max_blocks)
+    dense_k = rs.randn(int(lens.sum()), Hkv, D).astype(np.float32)
+    dense_v = rs.randn(int(lens.sum()), Hkv, D).astype(np.float32)
+    pages_k = rs.randn(B * max_blocks + 3, pt, Hkv, D).astype(np.float32)
+    pages_v = rs.randn(B * max_blocks + 3, pt, Hkv, D).astype(np.float32)
+    row = 0
+    for s in range(B):
+        for t in range(int(lens[s])):
+            pages_k[table[s, t // pt], t % pt] = dense_k[row]
+            pages_v[table[s, t // pt], t % pt] = dense_v[row]
+            row += 1
+    gk, offs = gather_pages(pages_k, table, lens)
+    assert np.array_equal(gk, dense_k) and list(offs) == [0, 7, 7, 20]
+    sizes = [5, 2, 6]
+    no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    kt = rs.randn(int(no[-1]), Hkv, D).astype(np.float32)
+    vt = rs.randn(int(no[-1]), Hkv, D).astype(np.float32)
+    path = np.asarray([[1, 3, 4], [-1, -1, -1], [2, 5, -1]], np.int32)
+    alen = np.asarray([3, 0, 2], np.int32)
+    pk, pv, pl = kv_commit_paged(kt, vt, no, path, alen, pages_k, pages_v, table, lens)
+    # the dense commit on regions with spare capacity, for comparison
+    cap = max_blocks * pt
+    ck = np.zeros((B * cap, Hkv, D), np.float32)
+    cv = np.zeros((B * cap, Hkv, D), np.float32)
+    for s in range(B):
+        ck[s * cap:s * cap + lens[s]] = dense_k[offs[s]:offs[s + 1]]
+        cv[s * cap:s * cap + lens[s]] = dense_v[offs[s]:offs[s + 1]]
+    dk, dv, dl = kv_commit(kt, vt, no, path, alen, ck, cv, np.arange(B + 1) * cap, lens)
+    assert np.array_equal(pl, dl)
+    gk2, o2 = gather_pages(pk, table, pl)
+    gv2, _ = gather_pages(pv, table, pl)
+    for s in range(B):
+        assert np.array_equal(gk2[o2[s]:o2[s + 1]], dk[s * cap:s * cap + dl[s]])
+        assert np.array_equal(gv2[o2[s]:o2[s + 1]], dv[s * cap:s * cap + dl[s]])
