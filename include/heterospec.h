@@ -349,6 +349,22 @@ hs_status hs_kv_commit_paged(const void* k_tree, const void* v_tree, const int32
                              int32_t page_tokens, int64_t* cache_lens,
                              int32_t B, int32_t Hkv, int32_t D, hs_dtype dt, hs_stream stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * hs_time_next_attention  (measurement aid, not a step of the method)
+ *
+ * Hands two HIP events (hipEvent_t, created by the caller with timing enabled) to the next
+ * hs_tree_attention / _lens / _paged call made on the calling thread.  That call attaches them to
+ * the dispatch of its attention kernel: the runtime stamps `start_event` when the kernel begins to
+ * execute and `stop_event` when it has ended, so hipEventElapsedTime(start, stop), once the stream
+ * is synchronised, is that kernel's own duration, without the microseconds that events recorded
+ * before and after a launch add to it.  The combine kernel that follows a launch with split keys
+ * is not covered, nor is the scalar kernel that other shapes than bf16 take (the events then stay
+ * as they were).  One-shot: the call consumes the pair whether it succeeds or not.  Both NULL
+ * withdraws a pair not yet consumed; exactly one NULL gives HS_ERR_NULL.  The events stay the
+ * caller's.
+ */
+hs_status hs_time_next_attention(void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

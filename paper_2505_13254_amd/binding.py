@@ -47,6 +47,7 @@ _SIGNATURES = {
                                       _c.c_int, _vp]),
     "hs_kv_commit": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _vp]),
     "hs_tree_validate": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
+    "hs_time_next_attention": (_c.c_int, [_vp, _vp]),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
     "hs_verify_accept": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _f32, _vp, _i32,
                                     _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -391,6 +392,20 @@ def hs_verify_accept(target_logits, draft_logits, token, parent, node_offsets, m
                                 _ptr(out["bonus_token"]), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "hs_verify_accept")
     return out
+
+
+def hs_time_next_attention(start_event, stop_event) -> None:
+    """start_event, stop_event: torch.cuda.Event(enable_timing=True) that have been recorded at least once
+    (torch creates the HIP event at the first record), or both None.  The next tree-attention call of this
+    thread attaches them to its attention kernel; start_event.elapsed_time(stop_event) is then the
+    kernel's own duration."""
+    if start_event is None and stop_event is None:
+        _check(lib().hs_time_next_attention(None, None), "hs_time_next_attention")
+        return
+    h0, h1 = start_event.cuda_event, stop_event.cuda_event
+    if not h0 or not h1:
+        raise ValueError("hs_time_next_attention: record each event once before handing it over")
+    _check(lib().hs_time_next_attention(_c.c_void_p(h0), _c.c_void_p(h1)), "hs_time_next_attention")
 
 
 def hs_tree_validate(parent, token, node_offsets, *, stream=None) -> torch.Tensor:

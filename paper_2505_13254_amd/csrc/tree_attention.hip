@@ -13,7 +13,8 @@
 
 namespace hs {
 
-hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream);
+hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream, hipEvent_t ev_start,
+                           hipEvent_t ev_stop);
 bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale);
 
 constexpr int GEN_THREADS = 256;
@@ -425,6 +426,18 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
                                 lse, workspace, workspace_bytes, stream);
 }
 
+// Events that hs_time_next_attention left for this thread's next attention call.
+static thread_local hipEvent_t timing_start = nullptr, timing_stop = nullptr;
+
+extern "C" hs_status hs_time_next_attention(void* start_event, void* stop_event) {
+  clear_error();
+  HS_REQUIRE((start_event == nullptr) == (stop_event == nullptr), HS_ERR_NULL,
+             "hs_time_next_attention: give both events or neither");
+  timing_start = static_cast<hipEvent_t>(start_event);
+  timing_stop = static_cast<hipEvent_t>(stop_event);
+  return HS_OK;
+}
+
 // The three entry points in one: dense prefix regions (prefix_lens NULL), regions with spare
 // capacity (prefix_lens given), pages (block_table given: k_prefix / v_prefix are the page pools,
 // the offset arrays are absent).
@@ -436,6 +449,8 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
                                 float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
   const bool paged = block_table != nullptr;
+  hipEvent_t ev_start = timing_start, ev_stop = timing_stop;  // one-shot, whatever this call comes to
+  timing_start = timing_stop = nullptr;
   HS_REQUIRE(B >= 0, HS_ERR_SHAPE, "hs_tree_attention: B=%d", B);
   HS_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, HS_ERR_SHAPE, "hs_tree_attention: Hq=%d must be a multiple of Hkv=%d",
              Hq, Hkv);
@@ -520,7 +535,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
              workspace_bytes);
 
   if (mfma) {
-    hs_status r = attn_mfma_launch(a, max_M, st);
+    hs_status r = attn_mfma_launch(a, max_M, st, ev_start, ev_stop);
     if (r != HS_OK) return r;
   } else {
     dim3 grid((unsigned)(Hkv * plan.n_rb_max * plan.sp_max), (unsigned)B);

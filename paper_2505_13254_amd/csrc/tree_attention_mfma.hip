@@ -44,6 +44,8 @@
 // tile loads) and the workgroup barrier carries no memory fence, so outstanding loads survive it.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "attn_common.h"
 
 namespace hs {
@@ -738,12 +740,17 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
 #endif
 }
 
-hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream) {
+// `ev_start` / `ev_stop` (may be NULL): HIP events attached to this dispatch; the runtime stamps them
+// when the kernel begins and ends, so their elapsed time is the kernel's own duration.
+hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream, hipEvent_t ev_start,
+                           hipEvent_t ev_stop) {
   const int n_rg_max = (a.G * max_tree_rows + MF_ROWS - 1) / MF_ROWS;
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);
   if (a.n_tbl > 0) grid = dim3((unsigned)a.n_items, 1u);
-  if (a.block_table != nullptr) hipLaunchKernelGGL(k_attn_mfma<true>, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
-  else hipLaunchKernelGGL(k_attn_mfma<false>, grid, dim3(MF_THREADS), 0, stream, a, n_rg_max);
+  if (a.block_table != nullptr)
+    hipExtLaunchKernelGGL(k_attn_mfma<true>, grid, dim3(MF_THREADS), 0, stream, ev_start, ev_stop, 0, a, n_rg_max);
+  else
+    hipExtLaunchKernelGGL(k_attn_mfma<false>, grid, dim3(MF_THREADS), 0, stream, ev_start, ev_stop, 0, a, n_rg_max);
   return launch_status("tree attention (mfma)");
 }
 

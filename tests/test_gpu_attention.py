@@ -152,3 +152,36 @@ def test_sibling_independence_and_determinism(G):
     c, _ = G.run_attention(st2)
     others = [i for i in range(40) if i != leaf]
     assert np.array_equal(a[others], c[others]) and not np.array_equal(a[leaf], c[leaf])
+
+
+def test_events_attached_to_the_attention_kernel(G):
+    """hs_time_next_attention: the pair is consumed by one call, brackets the kernel alone, and leaves
+    the result as it is."""
+    import paper_2505_13254_amd as hs
+    w = W.WORKLOADS[2]
+    rs = np.random.RandomState(12)
+    st = _case(w, 6, [_random_parents(rs, 61)], [4096 + 5], "unit")
+    plain, _ = G.run_attention(st)
+    e0, e1, f0, f1 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+    for e in (e0, e1, f0, f1):
+        e.record()
+    torch.cuda.synchronize()
+    hs.hs_time_next_attention(e0, e1)
+    f0.record()
+    timed, _ = G.run_attention(st)           # uploads, launches, synchronises, downloads
+    f1.record()
+    torch.cuda.synchronize()
+    assert np.array_equal(plain, timed)
+    own, around = e0.elapsed_time(e1), f0.elapsed_time(f1)
+    assert 0.0 < own < around, (own, around)
+    assert own < 5.0, own                    # milliseconds: one small kernel
+    again, _ = G.run_attention(st)           # one-shot: this call leaves the pair alone
+    torch.cuda.synchronize()
+    assert e0.elapsed_time(e1) == own
+    hs.hs_time_next_attention(e0, e1)
+    hs.hs_time_next_attention(None, None)    # withdrawn
+    G.run_attention(st)
+    torch.cuda.synchronize()
+    assert e0.elapsed_time(e1) == own
+    import ctypes
+    assert hs.lib().hs_time_next_attention(None, ctypes.c_void_p(e1.cuda_event)) != 0   # half a pair is refused
