@@ -362,17 +362,21 @@ def hs_kv_commit(k_tree, v_tree, node_offsets, accept_path, accept_len, k_cache,
 def hs_verify_accept(target_logits, draft_logits, token, parent, node_offsets, mode: int, temperature: float,
                      uniforms, max_depth: int, *, out: Optional[Dict[str, torch.Tensor]] = None,
                      ws: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
-    """target_logits / draft_logits float32 [NN, V] (draft and uniforms may be None when greedy), token and
-    parent int32 [NN], node_offsets int32 [B+1], uniforms float32 [NN + B].  Returns accept_len [B],
-    accept_path [B, max_depth], bonus_token [B]."""
-    _dev(target_logits, torch.float32, "target_logits")
+    """target_logits / draft_logits float32 [NN, V] (draft and uniforms may be None when greedy; rows may be
+    padded: unit stride along the vocabulary, the same row stride in both), token and parent int32 [NN],
+    node_offsets int32 [B+1], uniforms float32 [NN + B].  Returns accept_len [B], accept_path [B, max_depth],
+    bonus_token [B]."""
+    def rows(t, name):
+        if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("%s must be a float32 [NN, V] GPU tensor with unit stride along V" % name)
+        return t.stride(0) if t.shape[0] > 1 else t.shape[1]
+    row_stride = rows(target_logits, "target_logits")
     NN, V = target_logits.shape
     B = node_offsets.numel() - 1
     dev = target_logits.device
     if draft_logits is not None:
-        _dev(draft_logits, torch.float32, "draft_logits")
-        if draft_logits.shape != target_logits.shape:
-            raise ValueError("draft_logits must have the shape of target_logits")
+        if draft_logits.shape != target_logits.shape or rows(draft_logits, "draft_logits") != row_stride:
+            raise ValueError("draft_logits must have the shape and row stride of target_logits")
     if uniforms is not None:
         _dev(uniforms, torch.float32, "uniforms")
         if uniforms.numel() != NN + B:
@@ -386,7 +390,7 @@ def hs_verify_accept(target_logits, draft_logits, token, parent, node_offsets, m
     need = lib().hs_verify_accept_workspace(B, NN, V)
     if ws is None:
         ws = workspace(need, dev)
-    st = lib().hs_verify_accept(_ptr(target_logits), _ptr(draft_logits), V, _ptr(token), _ptr(parent),
+    st = lib().hs_verify_accept(_ptr(target_logits), _ptr(draft_logits), row_stride, _ptr(token), _ptr(parent),
                                 _ptr(node_offsets), B, NN, V, int(mode), float(temperature), _ptr(uniforms),
                                 int(max_depth), _ptr(out["accept_len"]), _ptr(out["accept_path"]),
                                 _ptr(out["bonus_token"]), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))

@@ -30,6 +30,13 @@ constexpr int AC_THREADS = 1024;
 constexpr int AC_WAVES = AC_THREADS / 64;
 constexpr int AC_MAX_KIDS = 256;    // children tried per node
 constexpr int AC_MAX_ROWS = 8192;   // 64-token rows of the CDF search held in LDS (V <= 524288)
+constexpr int AC_LIST_NODES = 4096; // calls with up to this many tree rows get a list of live tokens per row
+
+// A node's list of live tokens holds one region per wave of its workgroup: the wave's share of the
+// vocabulary (float4 index tid + k * AC_THREADS, plus a lane's token of the last V % 4).
+static __host__ __device__ inline int64_t list_wave_cap(int V) {
+  return (((int64_t)(V >> 2) + AC_THREADS - 1) / AC_THREADS) * 256 + 64;
+}
 
 // ----------------------------------------------------------------------------------- greedy
 // With n_slices > 1 the target rows' argmax arrives as one (value, index) pair per row slice
@@ -173,6 +180,190 @@ __device__ __forceinline__ double residual_mass(const RowView& p, const RowView&
   return F;
 }
 
+// Sum over the workgroup of per-thread partial sums: four float32 partials per thread, then float64.
+__device__ __forceinline__ double block_total(float a0, float a1, float a2, float a3, double* red) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  double acc = wave_sum(((double)a0 + (double)a1) + ((double)a2 + (double)a3));
+  __syncthreads();  // red is free
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  double F = 0.0;
+  for (int w = 0; w < AC_WAVES; ++w) F += red[w];
+  return F;
+}
+
+// A wave's list of live tokens in global memory, written through a ring of AC_RING pairs in LDS.
+// A store instruction costs the same whether it carries 64 lanes or a few, so the pairs that pass
+// are first packed in LDS and leave for global memory 128 at a time (16 bytes per lane).  Four
+// pairs per lane are appended per call, without branches: one prefix sum over the lanes' counts
+// gives each lane its first position, and a pair that does not pass is written to a slot of the
+// lane's own behind the ring instead.  Order of the list: lane, then slot.
+constexpr int AC_RING = 512;
+struct ListWriter {
+  float2* __restrict__ wl;  // the wave's region
+  float2* ring;             // the wave's ring in LDS: AC_RING pairs and 64 more, one per lane, that are never read
+  int w;                    // pairs in global memory so far (a multiple of 128 until finish())
+  int staged;               // pairs in the ring, from position w % AC_RING on (fewer than 128 between calls)
+  __device__ __forceinline__ void append4(const bool (&live)[4], const float (&pv)[4], const float (&qv)[4]) {
+    const int lane = threadIdx.x & 63;
+    int c[4];
+    c[0] = live[0] ? 1 : 0;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) c[k] = c[k - 1] + (live[k] ? 1 : 0);
+    const int incl = wave_prefix_sum(c[3]);
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    const int first = w + staged + incl - c[3];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int at = (first + (k ? c[k - 1] : 0)) & (AC_RING - 1);
+      ring[live[k] ? at : AC_RING + lane] = make_float2(pv[k], qv[k]);
+    }
+    staged += total;
+    while (staged >= 128) {  // (the same decision in every lane; at most three rounds)
+      __builtin_amdgcn_wave_barrier();
+      const float4 v = *reinterpret_cast<const float4*>(&ring[(w & (AC_RING - 1)) + 2 * lane]);
+      *reinterpret_cast<float4*>(&wl[w + 2 * lane]) = v;
+      w += 128;
+      staged -= 128;
+    }
+  }
+  __device__ __forceinline__ void finish() {
+    __builtin_amdgcn_wave_barrier();
+    for (int i = threadIdx.x & 63; i < staged; i += 64) wl[w + i] = ring[(w + i) & (AC_RING - 1)];
+    w += staged;
+    staged = 0;
+  }
+};
+
+// residual_mass for the first rejection at a node that has more to come: the same sum, and every
+// token whose term is positive leaves its pair (p(v), q(v)) in its wave's list.  beta only grows
+// along a chain, so a token whose term has reached zero stays out of every later sum: the later
+// passes (residual_mass_list) read the lists instead of the two vocabulary rows and evaluate no
+// exponentials.  Both rows must be 16-byte aligned and V >= 4 * AC_THREADS.  The order of a list is
+// fixed by the data (iteration, component, lane), so the sums are the same from run to run.
+// The logits of the next four iterations are requested before the current four are worked on (all
+// loads unconditional, out-of-range lanes re-read the last element): the stores into the list keep
+// the compiler from moving loads, so the overlap has to be written out.
+__device__ __forceinline__ double residual_mass_build(const RowView& p, const RowView& q, double beta, int V,
+                                                      double* red, float2* __restrict__ wl, float2* ring,
+                                                      int& wcount) {
+  const int tid = threadIdx.x;
+  const float bf = (float)beta;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  const int n4 = V >> 2;
+  const int n_it = (n4 + AC_THREADS - 1) / AC_THREADS;  // the same for every thread: the ballots need whole waves
+  const float4* __restrict__ px = reinterpret_cast<const float4*>(p.x);
+  const float4* __restrict__ qx = reinterpret_cast<const float4*>(q.x);
+  float4 fp[4], fq[4], np_[4], nq_[4];
+  auto fetch = [&](int k0, float4 (&dp)[4], float4 (&dq)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = min(tid + (k0 + u) * AC_THREADS, n4 - 1);
+      dp[u] = px[i];
+      dq[u] = qx[i];
+    }
+  };
+  ListWriter out{wl, ring, 0, 0};
+  fetch(0, fp, fq);
+  for (int k0 = 0; k0 < n_it; k0 += 4) {
+    fetch(k0 + 4, np_, nq_);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (k0 + u < n_it) {
+        const bool in = tid + (k0 + u) * AC_THREADS < n4;
+        const float4 pp = make_float4(
+            __expf(fmaf(fp[u].x - p.m, p.inv_t, p.lz)), __expf(fmaf(fp[u].y - p.m, p.inv_t, p.lz)),
+            __expf(fmaf(fp[u].z - p.m, p.inv_t, p.lz)), __expf(fmaf(fp[u].w - p.m, p.inv_t, p.lz)));
+        const float4 qq = make_float4(
+            __expf(fmaf(fq[u].x - q.m, q.inv_t, q.lz)), __expf(fmaf(fq[u].y - q.m, q.inv_t, q.lz)),
+            __expf(fmaf(fq[u].z - q.m, q.inv_t, q.lz)), __expf(fmaf(fq[u].w - q.m, q.inv_t, q.lz)));
+        const float t0 = in ? fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) : 0.f;
+        const float t1 = in ? fmaxf(fmaf(-bf, qq.y, pp.y), 0.f) : 0.f;
+        const float t2 = in ? fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) : 0.f;
+        const float t3 = in ? fmaxf(fmaf(-bf, qq.w, pp.w), 0.f) : 0.f;
+        a0 += t0;
+        a1 += t1;
+        a2 += t2;
+        a3 += t3;
+        const bool live[4] = {t0 > 0.f, t1 > 0.f, t2 > 0.f, t3 > 0.f};
+        const float pv[4] = {pp.x, pp.y, pp.z, pp.w}, qv[4] = {qq.x, qq.y, qq.z, qq.w};
+        out.append4(live, pv, qv);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      fp[u] = np_[u];
+      fq[u] = nq_[u];
+    }
+  }
+  {  // the last V % 4 tokens
+    const int v = (n4 << 2) + tid;
+    float pv = 0.f, qv = 0.f, t = 0.f;
+    if (v < V) {
+      pv = p.prob(v);
+      qv = q.prob(v);
+      t = fmaxf(fmaf(-bf, qv, pv), 0.f);
+    }
+    a0 += t;
+    const bool live[4] = {t > 0.f, false, false, false};
+    const float pv4[4] = {pv, 0.f, 0.f, 0.f}, qv4[4] = {qv, 0.f, 0.f, 0.f};
+    out.append4(live, pv4, qv4);
+  }
+  out.finish();
+  wcount = out.w;
+  return block_total(a0, a1, a2, a3, red);
+}
+
+// residual_mass over the lists that residual_mass_build left (two pairs per lane and load).  With
+// `compact` the pairs whose term is still positive move to the front of the list, in place: a pair
+// reaches global memory at or before the position it was read from, and the group of pairs that is
+// read ahead lies behind every position written meanwhile.
+__device__ __forceinline__ double residual_mass_list(double beta, double* red, float2* __restrict__ wl, float2* ring,
+                                                     int& wcount, bool compact) {
+  constexpr int LU = 4;  // loads per lane and group: 512 pairs per wave
+  const int lane = threadIdx.x & 63;
+  const float bf = (float)beta;
+  float a[4] = {0.f, 0.f, 0.f, 0.f};
+  const int n = wcount;
+  const int last2 = n > 1 ? (n - 1) >> 1 : 0;  // last float4 that holds a pair (the region holds 64 pairs at least)
+  const float4* __restrict__ src = reinterpret_cast<const float4*>(wl);
+  float4 cur[LU], nxt[LU];
+  auto fetch = [&](int base, float4 (&e)[LU]) {  // unconditional: lanes past the end re-read the last pairs
+#pragma unroll
+    for (int u = 0; u < LU; ++u) e[u] = src[min((base >> 1) + u * 64 + lane, last2)];
+  };
+  ListWriter out{wl, ring, 0, 0};
+  fetch(0, cur);
+  for (int base = 0; base < n; base += LU * 128) {
+    fetch(base + LU * 128, nxt);
+#pragma unroll
+    for (int u = 0; u < LU; u += 2) {
+      const int i0 = base + u * 128 + 2 * lane, i1 = i0 + 128;
+      const float t0 = i0 < n ? fmaxf(fmaf(-bf, cur[u].y, cur[u].x), 0.f) : 0.f;
+      const float t1 = i0 + 1 < n ? fmaxf(fmaf(-bf, cur[u].w, cur[u].z), 0.f) : 0.f;
+      const float t2 = i1 < n ? fmaxf(fmaf(-bf, cur[u + 1].y, cur[u + 1].x), 0.f) : 0.f;
+      const float t3 = i1 + 1 < n ? fmaxf(fmaf(-bf, cur[u + 1].w, cur[u + 1].z), 0.f) : 0.f;
+      a[0] += t0;
+      a[1] += t1;
+      a[2] += t2;
+      a[3] += t3;
+      if (compact) {
+        const bool live[4] = {t0 > 0.f, t1 > 0.f, t2 > 0.f, t3 > 0.f};
+        const float pv[4] = {cur[u].x, cur[u].z, cur[u + 1].x, cur[u + 1].z};
+        const float qv[4] = {cur[u].y, cur[u].w, cur[u + 1].y, cur[u + 1].w};
+        out.append4(live, pv, qv);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < LU; ++u) cur[u] = nxt[u];
+  }
+  if (compact) {
+    out.finish();
+    wcount = out.w;
+  }
+  return block_total(a[0], a[1], a[2], a[3], red);
+}
+
 // The same term for one token, as residual_mass forms it (used to take a frozen token's live term
 // out of the sum again).
 __device__ __forceinline__ double residual_term(const RowView& p, const RowView& q, double beta, int v) {
@@ -222,12 +413,13 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
     const float* __restrict__ target, const float* __restrict__ draft, int64_t row_stride,
     const int32_t* __restrict__ token, const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets,
     int B, int V, float inv_t, int max_depth, const int32_t* __restrict__ t_arg, const float* __restrict__ t_lz,
-    const int32_t* __restrict__ d_arg, const float* __restrict__ d_lz, ChainOut out) {
+    const int32_t* __restrict__ d_arg, const float* __restrict__ d_lz, ChainOut out, float2* __restrict__ lists) {
   __shared__ int kids[AC_MAX_KIDS];
   __shared__ int kids_sorted[AC_MAX_KIDS];
   __shared__ int n_kids;
-  __shared__ int rej_tok[AC_MAX_KIDS];
   __shared__ double rej_w[AC_MAX_KIDS];
+  __shared__ float kid_p[AC_MAX_KIDS], kid_q[AC_MAX_KIDS];  // p(x), q(x) of each child's token
+  __shared__ __attribute__((aligned(16))) float2 rings[AC_WAVES][AC_RING + 64];  // see ListWriter
   __shared__ double red[AC_WAVES];
   const int g = blockIdx.x, tid = threadIdx.x;
   int lo = 0, hi = B;  // sequence of this row: last s with node_offsets[s] <= g
@@ -239,20 +431,35 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
   const int n = node_offsets[lo + 1] - o;
   const int cur = g - o;
   if (cur >= n) return;  // (an empty sequence before this row's: cannot happen, offsets are monotone)
+  // (row statistics first: these loads do not depend on the tree)
+  const float p_lz = t_lz[g], q_lz = d_lz[g];
+  const int p_arg = t_arg[g], q_arg = d_arg[g];
   int depth = 0;
   for (int j = parent[o + cur]; j >= 0; j = parent[o + j]) ++depth;
   const int nk = gather_children(parent, o, n, cur, depth < max_depth, kids, kids_sorted, &n_kids);
   if (nk == 0) return;
-  RowView p{target + (int64_t)(o + cur) * row_stride, 0.f, t_lz[o + cur], inv_t};
-  p.m = p.x[t_arg[o + cur]];
-  RowView q{draft + (int64_t)(o + cur) * row_stride, 0.f, d_lz[o + cur], inv_t};
-  q.m = q.x[d_arg[o + cur]];
+  RowView p{target + (int64_t)g * row_stride, 0.f, p_lz, inv_t};
+  p.m = p.x[p_arg];
+  RowView q{draft + (int64_t)g * row_stride, 0.f, q_lz, inv_t};
+  q.m = q.x[q_arg];
+  // every child's token and its two probabilities, fetched side by side: the chain below is serial,
+  // and a round trip to memory per step would dominate it
+  if (tid < nk) {
+    const int x = token[o + kids_sorted[tid]];
+    kid_p[tid] = p.prob(x);
+    kid_q[tid] = q.prob(x);
+  }
+  __syncthreads();
+  // lists of live tokens (`lists` may be NULL): worth their stores when a second rejection follows
+  const bool use_list = lists != nullptr && nk >= 2 && V >= 4 * AC_THREADS && p.aligned16() && q.aligned16();
+  float2* __restrict__ wl = use_list ? lists + ((int64_t)g * AC_WAVES + (tid >> 6)) * list_wave_cap(V) : nullptr;
+  float2* ring = rings[tid >> 6];
+  int wcount = 0;
   double beta = 0.0, Z = 1.0, sumq = 0.0;
   for (int j = 0; j < nk; ++j) {
     const int c = kids_sorted[j];
-    const int x = token[o + c];
-    const double px = (double)p.prob(x);
-    const double qx = (double)q.prob(x);
+    const double px = (double)kid_p[j];
+    const double qx = (double)kid_q[j];
     const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
     const double qc = qx / (1.0 - sumq);              // current q(x)
     // rejected: p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)
@@ -263,11 +470,15 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
       out.child_p[o + c] = pc;
       out.child_q[o + c] = qc;
       out.child_frozen[o + c] = frozen;
-      rej_tok[j] = x;
       rej_w[j] = frozen;
     }
-    double F = residual_mass(p, q, beta, V, red);  // (its barriers also publish rej_*)
-    for (int i = 0; i <= j; ++i) F += rej_w[i] - residual_term(p, q, beta, rej_tok[i]);
+    double F;  // (the barriers of a pass also publish rej_w)
+    if (!use_list) F = residual_mass(p, q, beta, V, red);
+    else if (j == 0) F = residual_mass_build(p, q, beta, V, red, wl, ring, wcount);
+    else F = residual_mass_list(beta, red, wl, ring, wcount, j + 1 < nk);
+    // a rejected token's weight is frozen: its live term (as the passes form it) leaves the sum
+    const float bf = (float)beta;
+    for (int i = 0; i <= j; ++i) F += rej_w[i] - (double)fmaxf(fmaf(-bf, kid_q[i], kid_p[i]), 0.f);
     Z = F;
   }
   if (tid == 0) {
@@ -288,6 +499,8 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
   __shared__ int n_kids;
   __shared__ int rej_tok[AC_MAX_KIDS];
   __shared__ double rej_w[AC_MAX_KIDS];  // frozen weight of each rejected token
+  __shared__ float kid_u[AC_MAX_KIDS];    // the child's uniform
+  __shared__ double kid_a[AC_MAX_KIDS], kid_b[AC_MAX_KIDS];  // its current p(x) (and q(x) under the ratio rule)
   __shared__ double rowsum[AC_MAX_ROWS];
 
   const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -317,40 +530,44 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
       q.m = q.x[d_arg[o + cur]];
     }
 
+    // ---- what the tests of the children need, fetched side by side (a round trip to memory per
+    // child would dominate the walk).  The rejected children are a prefix of the list, so entry i of
+    // rej_tok / rej_w belongs to child i.
+    if (tid < nk) {
+      const int c = kids_sorted[tid];
+      const int x = token[o + c];
+      rej_tok[tid] = x;
+      kid_u[tid] = uniforms[o + c];
+      if (ratio_mode) {  // the node's chain of rejections was run ahead of the walk (k_accept_chain)
+        kid_a[tid] = chain.child_p[o + c];
+        kid_b[tid] = chain.child_q[o + c];
+        rej_w[tid] = chain.child_frozen[o + c];
+      } else {
+        kid_a[tid] = (double)p.prob(x);
+        rej_w[tid] = 0.0;
+      }
+    }
+    __syncthreads();
     // ---- try the children in order (every thread runs the same scalar logic)
     double beta = 0.0, Z = 1.0, rem = 1.0;
     int n_rej = 0, accepted = -1;
     for (int j = 0; j < nk; ++j) {
-      const int c = kids_sorted[j];
-      const int x = token[o + c];
-      const double u = (double)uniforms[o + c];
-      const double px = (double)p.prob(x);
+      const double u = (double)kid_u[j];
       if (!ratio_mode) {
+        const double px = kid_a[j];
         if (u * rem < px) {  // u < p(x) / rem
-          accepted = c;
+          accepted = kids_sorted[j];
           break;
         }
         rem -= px;
-        if (tid == 0) {
-          rej_tok[n_rej] = x;
-          rej_w[n_rej] = 0.0;
+      } else {
+        const double pc = kid_a[j], qc = kid_b[j];
+        if (pc >= qc || u * qc < pc) {
+          accepted = kids_sorted[j];
+          break;
         }
-        ++n_rej;
-        __syncthreads();
-        continue;
-      }
-      // the node's chain of rejections was run ahead of the walk (k_accept_chain)
-      const double pc = chain.child_p[o + c], qc = chain.child_q[o + c];
-      if (pc >= qc || u * qc < pc) {
-        accepted = c;
-        break;
-      }
-      if (tid == 0) {
-        rej_tok[n_rej] = x;
-        rej_w[n_rej] = chain.child_frozen[o + c];
       }
       ++n_rej;
-      __syncthreads();
     }
     if (ratio_mode && accepted < 0 && n_rej > 0) {
       beta = chain.node_beta[o + cur];
@@ -459,7 +676,11 @@ extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
   const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
   // five doubles per row: what the rejection chains hand to the walk
   const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256);
-  return 2 * per_set + chain + hs::row_topk_workspace(NN, V, 1);
+  // the rejection chains' lists of live tokens: a pair of floats per token and row
+  const size_t lists = NN <= hs::AC_LIST_NODES
+                           ? hs::align_up((size_t)NN * hs::AC_WAVES * hs::list_wave_cap(V) * sizeof(float2), 256)
+                           : 0;
+  return 2 * per_set + chain + lists + hs::row_topk_workspace(NN, V, 1);
 }
 
 extern "C" hs_status hs_verify_accept(const float* target_logits, const float* draft_logits, int64_t row_stride,
@@ -497,6 +718,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   float *t_lz = nullptr, *d_lz = nullptr;
   hs::ScanSlices slices{nullptr, nullptr, 1};
   hs::ChainOut chain{nullptr, nullptr, nullptr, nullptr, nullptr};
+  float2* lists = nullptr;
   if (NN > 0) {
     hs::Carver c(workspace);
     t_arg = c.take<int32_t>(NN);
@@ -510,6 +732,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     chain.child_frozen = c.take<double>(NN);
     chain.node_beta = c.take<double>(NN);
     chain.node_Z = c.take<double>(NN);
+    if (NN <= hs::AC_LIST_NODES) lists = c.take<float2>((size_t)NN * hs::AC_WAVES * hs::list_wave_cap(V));
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
     // greedy: the merge of the row slices is done by the accept kernel (one launch less)
@@ -530,7 +753,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   if (mode == HS_ACCEPT_STOCHASTIC && NN > 0) {
     hipLaunchKernelGGL(hs::k_accept_chain, dim3(NN), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits,
                        row_stride, token, parent, node_offsets, B, V, 1.0f / temperature, max_depth, t_arg, t_lz,
-                       d_arg, d_lz, chain);
+                       d_arg, d_lz, chain, lists);
     hs_status r = hs::launch_status("accept (rejection chains)");
     if (r != HS_OK) return r;
   }

@@ -195,7 +195,8 @@ def test_accept_greedy(G, wid, small):
 
 
 @pytest.mark.parametrize("mode", [1, 2])
-@pytest.mark.parametrize("wid,small", [(1, {}), (2, dict(V=8192)), (4, dict(V=4099)), (5, dict(V=2048, B=5))])
+@pytest.mark.parametrize("wid,small", [(1, {}), (2, dict(V=8192)), (2, dict(V=12292)), (4, dict(V=4099)),
+                                       (5, dict(V=2048, B=5)), (5, dict(V=20480, B=3))])
 def test_accept_stochastic(G, mode, wid, small):
     w = W.small(W.WORKLOADS[wid], **small)
     lens = []
@@ -207,3 +208,36 @@ def test_accept_stochastic(G, mode, wid, small):
         lens += list(want["accept_len"])
     if wid != 1:                                             # (the tiny workload keeps 3 unlikely nodes)
         assert max(lens) >= 1                                # some walk went below the root
+
+
+@pytest.mark.parametrize("V,pad", [(12290, 2), (8193, 3), (8190, 1)])
+def test_accept_stochastic_padded_rows(G, V, pad):
+    """Rows with a stride above V: 16-byte aligned rows whose length is no multiple of four (the
+    rejection chains' lists of live tokens take the last V % 4 tokens separately) and unaligned rows."""
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[2], V=V)
+    for seed in range(2):
+        st = P.build_step(w, seed, with_attention=False)
+        u, want = P.safe_uniforms(st, 1)
+        D = max(1, int(P.tree_depth(st["parent"], st["node_offsets"]).max()))
+        NN = st["target_logits"].shape[0]
+        bufs = []
+        for name in ("target_logits", "draft_logits"):
+            b = torch.full((NN, V + pad), float("nan"), dtype=torch.float32, device="cuda:0")
+            b[:, :V] = torch.from_numpy(st[name]).to("cuda:0")
+            bufs.append(b[:, :V])
+        out = hs.hs_verify_accept(bufs[0], bufs[1], G.dev(st["token"], torch.int32), G.dev(st["parent"], torch.int32),
+                                  G.dev(st["node_offsets"], torch.int32), 1, w.temperature,
+                                  G.dev(u, torch.float32), D)
+        _accept_equal({k: G.host(v) for k, v in out.items()}, want)
+
+
+def test_accept_stochastic_is_deterministic(G):
+    w = W.small(W.WORKLOADS[2], V=16384)
+    st = P.build_step(w, 3, with_attention=False)
+    u, want = P.safe_uniforms(st, 1)
+    D = max(1, int(P.tree_depth(st["parent"], st["node_offsets"]).max()))
+    first = G.run_accept(st, 1, u, D)
+    _accept_equal(first, want)
+    for _ in range(3):
+        _accept_equal(G.run_accept(st, 1, u, D), first)

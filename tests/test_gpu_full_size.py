@@ -66,7 +66,8 @@ def _check_step(st, rs, n_rows=6, n_heads=3, accept_mode=0):
         assert err <= 6e-3 * np.abs(wo).max() + 1e-6, (b, hq, err, np.abs(wo).max())
     # ---- stage 4, whole walk (argmax rows are cheap; the stochastic modes read only visited rows)
     tl = _np(t["target_logits"])
-    dl = _np(t["draft_logits"]) if accept_mode == 1 else None
+    # (the point-mass rule never uses the draft rows; the checker still wants an array there)
+    dl = _np(t["draft_logits"]) if accept_mode == 1 else (tl if accept_mode == 2 else None)
     wa = verify_accept(tl, dl, _np(t["token"]), s2["out_parent"][:n], s2["out_offsets"], accept_mode, w.temperature,
                        _np(t["uniforms"]) if accept_mode else None, h["max_depth"])
     ga = {k: _np(v) for k, v in t["s4_out"].items()}
@@ -106,3 +107,13 @@ def test_workload5_ragged_batch(H):
     assert len(sizes) == 16 and sizes.min() >= 2 and sizes.max() <= 129
     res = _check_step(st, np.random.RandomState(3), n_rows=4, n_heads=5)
     assert res["accept_len"].shape == (16,)
+
+
+@pytest.mark.parametrize("wid,mode", [(2, 1), (2, 2), (4, 1)])
+def test_stochastic_accept_at_full_vocabulary(H, wid, mode):
+    """The sampling modes on the 128256-token vocabulary (workload 2: ratio rule and point-mass rule;
+    workload 4 is specified with the ratio rule), one attention layer."""
+    w = W.WORKLOADS[wid]
+    st = H.build_step(w, 0, layers=1, accept_mode=mode)
+    res = _check_step(st, np.random.RandomState(10 + wid + mode), n_rows=2, n_heads=1, accept_mode=mode)
+    assert res["bonus_token"].min() >= 0
