@@ -118,18 +118,21 @@ __global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(int32_t* __restric
 }
 
 // ----------------------------------------------------------------------------------- stochastic
+// A row of logits as probabilities: p(v) = exp((x[v] - m) / T + lz) with m the row's maximum and
+// lz = -ln(sum exp((x - m) / T)), evaluated as exp2((x[v] - m) * c1 + c2): a subtraction, a fused
+// multiply-add and the exponential instruction per token.
 struct RowView {
   const float* x;  // logits row
   float m;         // its maximum
-  float lz;        // -ln(sum exp((x - m) / T))
-  float inv_t;
-  __device__ __forceinline__ float prob(int v) const { return __expf(fmaf(x[v] - m, inv_t, lz)); }
+  float c1;        // log2(e) / T
+  float c2;        // log2(e) * lz
+  __device__ __forceinline__ RowView(const float* row, float max_logit, float lz, float inv_t)
+      : x(row), m(max_logit), c1(inv_t * 1.4426950408889634f), c2(lz * 1.4426950408889634f) {}
+  __device__ __forceinline__ float of(float logit) const { return exp2_fast(fmaf(logit - m, c1, c2)); }
+  __device__ __forceinline__ float prob(int v) const { return of(x[v]); }
+  __device__ __forceinline__ float4 of4(const float4 f) const { return make_float4(of(f.x), of(f.y), of(f.z), of(f.w)); }
   // tokens 4 i .. 4 i + 3 with one 16-byte load (the row must be 16-byte aligned)
-  __device__ __forceinline__ float4 prob4(int i) const {
-    const float4 f = reinterpret_cast<const float4*>(x)[i];
-    return make_float4(__expf(fmaf(f.x - m, inv_t, lz)), __expf(fmaf(f.y - m, inv_t, lz)),
-                       __expf(fmaf(f.z - m, inv_t, lz)), __expf(fmaf(f.w - m, inv_t, lz)));
-  }
+  __device__ __forceinline__ float4 prob4(int i) const { return of4(reinterpret_cast<const float4*>(x)[i]); }
   __device__ __forceinline__ bool aligned16() const { return reinterpret_cast<uintptr_t>(x) % 16 == 0; }
 };
 
@@ -181,12 +184,14 @@ __device__ __forceinline__ double residual_mass(const RowView& p, const RowView&
 }
 
 // Sum over the workgroup of per-thread partial sums: four float32 partials per thread, then float64.
+// The two barriers order LDS traffic only (they do not wait for global stores: a wave's list is
+// read by that wave alone, and what thread 0 writes for the walk is read by a later kernel).
 __device__ __forceinline__ double block_total(float a0, float a1, float a2, float a3, double* red) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double acc = wave_sum(((double)a0 + (double)a1) + ((double)a2 + (double)a3));
-  __syncthreads();  // red is free
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // red is free
   if (lane == 0) red[wave] = acc;
-  __syncthreads();
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   double F = 0.0;
   for (int w = 0; w < AC_WAVES; ++w) F += red[w];
   return F;
@@ -198,12 +203,13 @@ __device__ __forceinline__ double block_total(float a0, float a1, float a2, floa
 // pairs per lane are appended per call, without branches: one prefix sum over the lanes' counts
 // gives each lane its first position, and a pair that does not pass is written to a slot of the
 // lane's own behind the ring instead.  Order of the list: lane, then slot.
-constexpr int AC_RING = 512;
+constexpr int AC_RING = 1024;
 struct ListWriter {
   float2* __restrict__ wl;  // the wave's region
   float2* ring;             // the wave's ring in LDS: AC_RING pairs and 64 more, one per lane, that are never read
   int w;                    // pairs in global memory so far (a multiple of 128 until finish())
   int staged;               // pairs in the ring, from position w % AC_RING on (fewer than 128 between calls)
+  bool keep;                // the whole list (at most AC_RING pairs) stays in the ring: nothing goes to global memory
   __device__ __forceinline__ void append4(const bool (&live)[4], const float (&pv)[4], const float (&qv)[4]) {
     const int lane = threadIdx.x & 63;
     int c[4];
@@ -219,7 +225,7 @@ struct ListWriter {
       ring[live[k] ? at : AC_RING + lane] = make_float2(pv[k], qv[k]);
     }
     staged += total;
-    while (staged >= 128) {  // (the same decision in every lane; at most three rounds)
+    while (!keep && staged >= 128) {  // (the same decision in every lane; at most three rounds)
       __builtin_amdgcn_wave_barrier();
       const float4 v = *reinterpret_cast<const float4*>(&ring[(w & (AC_RING - 1)) + 2 * lane]);
       *reinterpret_cast<float4*>(&wl[w + 2 * lane]) = v;
@@ -229,6 +235,7 @@ struct ListWriter {
   }
   __device__ __forceinline__ void finish() {
     __builtin_amdgcn_wave_barrier();
+    if (keep) return;
     for (int i = threadIdx.x & 63; i < staged; i += 64) wl[w + i] = ring[(w + i) & (AC_RING - 1)];
     w += staged;
     staged = 0;
@@ -263,7 +270,7 @@ __device__ __forceinline__ double residual_mass_build(const RowView& p, const Ro
       dq[u] = qx[i];
     }
   };
-  ListWriter out{wl, ring, 0, 0};
+  ListWriter out{wl, ring, 0, 0, false};
   fetch(0, fp, fq);
   for (int k0 = 0; k0 < n_it; k0 += 4) {
     fetch(k0 + 4, np_, nq_);
@@ -271,12 +278,7 @@ __device__ __forceinline__ double residual_mass_build(const RowView& p, const Ro
     for (int u = 0; u < 4; ++u) {
       if (k0 + u < n_it) {
         const bool in = tid + (k0 + u) * AC_THREADS < n4;
-        const float4 pp = make_float4(
-            __expf(fmaf(fp[u].x - p.m, p.inv_t, p.lz)), __expf(fmaf(fp[u].y - p.m, p.inv_t, p.lz)),
-            __expf(fmaf(fp[u].z - p.m, p.inv_t, p.lz)), __expf(fmaf(fp[u].w - p.m, p.inv_t, p.lz)));
-        const float4 qq = make_float4(
-            __expf(fmaf(fq[u].x - q.m, q.inv_t, q.lz)), __expf(fmaf(fq[u].y - q.m, q.inv_t, q.lz)),
-            __expf(fmaf(fq[u].z - q.m, q.inv_t, q.lz)), __expf(fmaf(fq[u].w - q.m, q.inv_t, q.lz)));
+        const float4 pp = p.of4(fp[u]), qq = q.of4(fq[u]);
         const float t0 = in ? fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) : 0.f;
         const float t1 = in ? fmaxf(fmaf(-bf, qq.y, pp.y), 0.f) : 0.f;
         const float t2 = in ? fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) : 0.f;
@@ -316,23 +318,27 @@ __device__ __forceinline__ double residual_mass_build(const RowView& p, const Ro
 
 // residual_mass over the lists that residual_mass_build left (two pairs per lane and load).  With
 // `compact` the pairs whose term is still positive move to the front of the list, in place: a pair
-// reaches global memory at or before the position it was read from, and the group of pairs that is
-// read ahead lies behind every position written meanwhile.
-__device__ __forceinline__ double residual_mass_list(double beta, double* red, float2* __restrict__ wl, float2* ring,
-                                                     int& wcount, bool compact) {
+// is written at or before the position it was read from, and the group of pairs that is read ahead
+// lies behind every position written meanwhile.  A list of at most AC_RING pairs moves into the
+// wave's ring in LDS and stays there (IN_LDS: it is read from the ring), which takes the round trips
+// to memory out of the short passes at the end of a long chain.
+// This is the wave's own part of the pass (a[] receives the lanes' four partial sums): waves of a
+// workgroup may take different instantiations, so the workgroup's barriers stay with the caller.
+template <bool IN_LDS>
+__device__ __forceinline__ void residual_mass_list(double beta, float2* __restrict__ wl, float2* ring, int& wcount,
+                                                   bool& in_lds, bool compact, float (&a)[4]) {
   constexpr int LU = 4;  // loads per lane and group: 512 pairs per wave
   const int lane = threadIdx.x & 63;
   const float bf = (float)beta;
-  float a[4] = {0.f, 0.f, 0.f, 0.f};
   const int n = wcount;
-  const int last2 = n > 1 ? (n - 1) >> 1 : 0;  // last float4 that holds a pair (the region holds 64 pairs at least)
-  const float4* __restrict__ src = reinterpret_cast<const float4*>(wl);
+  const int last2 = n > 1 ? (n - 1) >> 1 : 0;  // last float4 that holds a pair (list and ring hold 64 pairs at least)
+  const float4* src = IN_LDS ? reinterpret_cast<const float4*>(ring) : reinterpret_cast<const float4*>(wl);
   float4 cur[LU], nxt[LU];
   auto fetch = [&](int base, float4 (&e)[LU]) {  // unconditional: lanes past the end re-read the last pairs
 #pragma unroll
     for (int u = 0; u < LU; ++u) e[u] = src[min((base >> 1) + u * 64 + lane, last2)];
   };
-  ListWriter out{wl, ring, 0, 0};
+  ListWriter out{wl, ring, 0, 0, n <= AC_RING};
   fetch(0, cur);
   for (int base = 0; base < n; base += LU * 128) {
     fetch(base + LU * 128, nxt);
@@ -359,9 +365,9 @@ __device__ __forceinline__ double residual_mass_list(double beta, double* red, f
   }
   if (compact) {
     out.finish();
-    wcount = out.w;
+    wcount = out.keep ? out.staged : out.w;
+    in_lds = out.keep;
   }
-  return block_total(a[0], a[1], a[2], a[3], red);
 }
 
 // The same term for one token, as residual_mass forms it (used to take a frozen token's live term
@@ -438,10 +444,10 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
   for (int j = parent[o + cur]; j >= 0; j = parent[o + j]) ++depth;
   const int nk = gather_children(parent, o, n, cur, depth < max_depth, kids, kids_sorted, &n_kids);
   if (nk == 0) return;
-  RowView p{target + (int64_t)g * row_stride, 0.f, p_lz, inv_t};
-  p.m = p.x[p_arg];
-  RowView q{draft + (int64_t)g * row_stride, 0.f, q_lz, inv_t};
-  q.m = q.x[q_arg];
+  const float* p_row = target + (int64_t)g * row_stride;
+  const float* q_row = draft + (int64_t)g * row_stride;
+  const RowView p(p_row, p_row[p_arg], p_lz, inv_t);
+  const RowView q(q_row, q_row[q_arg], q_lz, inv_t);
   // every child's token and its two probabilities, fetched side by side: the chain below is serial,
   // and a round trip to memory per step would dominate it
   if (tid < nk) {
@@ -455,6 +461,7 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
   float2* __restrict__ wl = use_list ? lists + ((int64_t)g * AC_WAVES + (tid >> 6)) * list_wave_cap(V) : nullptr;
   float2* ring = rings[tid >> 6];
   int wcount = 0;
+  bool in_lds = false;  // (per wave)
   double beta = 0.0, Z = 1.0, sumq = 0.0;
   for (int j = 0; j < nk; ++j) {
     const int c = kids_sorted[j];
@@ -475,7 +482,12 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
     double F;  // (the barriers of a pass also publish rej_w)
     if (!use_list) F = residual_mass(p, q, beta, V, red);
     else if (j == 0) F = residual_mass_build(p, q, beta, V, red, wl, ring, wcount);
-    else F = residual_mass_list(beta, red, wl, ring, wcount, j + 1 < nk);
+    else {
+      float a[4] = {0.f, 0.f, 0.f, 0.f};
+      if (__builtin_amdgcn_readfirstlane((int)in_lds)) residual_mass_list<true>(beta, wl, ring, wcount, in_lds, j + 1 < nk, a);
+      else residual_mass_list<false>(beta, wl, ring, wcount, in_lds, j + 1 < nk, a);
+      F = block_total(a[0], a[1], a[2], a[3], red);
+    }
     // a rejected token's weight is frozen: its live term (as the passes form it) leaves the sum
     const float bf = (float)beta;
     for (int i = 0; i <= j; ++i) F += rej_w[i] - (double)fmaxf(fmaf(-bf, kid_q[i], kid_p[i]), 0.f);
@@ -520,14 +532,13 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
   for (;;) {
     const int nk = gather_children(parent, o, n, cur, len < max_depth, kids, kids_sorted, &n_kids);
 
-    RowView p{target + (int64_t)(o + cur) * row_stride, 0.f, t_lz[o + cur], inv_t};
-    p.m = p.x[t_arg[o + cur]];
+    const float* p_row = target + (int64_t)(o + cur) * row_stride;
+    const RowView p(p_row, p_row[t_arg[o + cur]], t_lz[o + cur], inv_t);
     RowView q = p;
     const bool use_q = ratio_mode && nk > 0;
     if (use_q) {
-      q.x = draft + (int64_t)(o + cur) * row_stride;
-      q.lz = d_lz[o + cur];
-      q.m = q.x[d_arg[o + cur]];
+      const float* q_row = draft + (int64_t)(o + cur) * row_stride;
+      q = RowView(q_row, q_row[d_arg[o + cur]], d_lz[o + cur], inv_t);
     }
 
     // ---- what the tests of the children need, fetched side by side (a round trip to memory per
