@@ -241,3 +241,39 @@ def test_accept_stochastic_is_deterministic(G):
     _accept_equal(first, want)
     for _ in range(3):
         _accept_equal(G.run_accept(st, 1, u, D), first)
+
+
+@pytest.mark.parametrize("V,n_kids", [(16384, 14), (40000, 9), (6000, 24)])
+def test_accept_long_rejection_chains(G, V, n_kids):
+    """A root whose many children are (nearly) all rejected, so that the bonus token depends on every
+    pass of the root's chain: the list of live tokens is built, compacted in memory, and ends in LDS."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(V + n_kids)
+    done, rejected_all = 0, 0
+    for attempt in range(40):
+        draft = (rs.normal(size=(1 + n_kids, V)) * 2.5).astype(np.float32)
+        target = (0.8 * draft + rs.normal(size=draft.shape) * 1.5).astype(np.float32)
+        parent = np.asarray([-1] + [0] * n_kids, np.int32)
+        token = np.zeros(1 + n_kids, np.int32)
+        token[1:] = np.argsort(-draft[0], kind="stable")[:n_kids]          # the draft's best tokens, distinct
+        offs = np.asarray([0, 1 + n_kids], np.int32)
+        u = np.concatenate([0.9 + 0.0999 * rs.rand(1 + n_kids), rs.rand(1)]).astype(np.float32)
+        from oracle import verify_accept
+        base = verify_accept(target, draft, token, parent, offs, 1, 1.0, u, 1)
+        ok = True
+        for sgn in (-1.0, 1.0):
+            un = u.astype(np.float64).copy()
+            un[:1 + n_kids] *= 1.0 + sgn * 1e-4
+            un[1 + n_kids:] = np.clip(un[1 + n_kids:] + sgn * 1e-5, 0.0, 1.0 - 1e-12)
+            alt = verify_accept(target, draft, token, parent, offs, 1, 1.0, un, 1)
+            ok = ok and all(np.array_equal(alt[k], base[k]) for k in base)
+        if not ok:
+            continue
+        out = hs.hs_verify_accept(G.dev(target), G.dev(draft), G.dev(token, torch.int32), G.dev(parent, torch.int32),
+                                  G.dev(offs, torch.int32), 1, 1.0, G.dev(u, torch.float32), 1)
+        _accept_equal({k: G.host(v) for k, v in out.items()}, base)
+        done += 1
+        rejected_all += int(base["accept_len"][0] == 0)
+        if done >= 6 and rejected_all >= 2:
+            break
+    assert done >= 6 and rejected_all >= 2, (done, rejected_all)
