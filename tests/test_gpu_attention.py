@@ -185,3 +185,22 @@ def test_events_attached_to_the_attention_kernel(G):
     assert e0.elapsed_time(e1) == own
     import ctypes
     assert hs.lib().hs_time_next_attention(None, ctypes.c_void_p(e1.cuda_event)) != 0   # half a pair is refused
+
+
+@pytest.mark.parametrize("M,L", [(256, 200), (257, 100), (1024, 70)])
+def test_tree_row_limits(G, M, L):
+    """256 rows per tree is what the matrix-core kernel takes (four row groups per KV head at G = 4);
+    one row more goes to the scalar kernel, whose limit is 1024 rows."""
+    w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
+    rs = np.random.RandomState(M)
+    _compare(G, _case(w, 13, [_random_parents(rs, M, back=12)], [L], "unit"), "bf16")
+
+
+def test_more_tree_rows_than_supported_is_an_error(G):
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
+    rs = np.random.RandomState(1)
+    st = _case(w, 14, [_random_parents(rs, 1025)], [10], "unit")
+    with pytest.raises(hs.HsError) as e:
+        G.run_attention(st)
+    assert e.value.status == 3 and "1025" in str(e.value)    # HS_ERR_UNSUPPORTED, names the size
