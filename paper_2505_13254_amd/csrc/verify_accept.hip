@@ -30,13 +30,13 @@ constexpr int AC_THREADS = 1024;
 constexpr int AC_WAVES = AC_THREADS / 64;
 constexpr int AC_MAX_KIDS = 256;    // children tried per node
 constexpr int AC_MAX_ROWS = 8192;   // 64-token rows of the CDF search held in LDS (V <= 524288)
-constexpr int AC_LIST_NODES = 4096; // calls with up to this many tree rows get a list of live tokens per row
-
-// A node's list of live tokens holds one region per wave of its workgroup: the wave's share of the
-// vocabulary (float4 index tid + k * AC_THREADS, plus a lane's token of the last V % 4).
-static __host__ __device__ inline int64_t list_wave_cap(int V) {
-  return (((int64_t)(V >> 2) + AC_THREADS - 1) / AC_THREADS) * 256 + 64;
-}
+constexpr int BK_NODES = 4096;      // calls with up to this many tree rows get the sorted residual (below)
+constexpr int BK_SLICES = 16;       // vocabulary slices per row in the kernels that build it
+constexpr int BK_N = 256;           // buckets of the ratio p / q: BK_PER_OCTAVE per factor of two, from 1 upwards
+constexpr int BK_THREADS = 256;     // (one thread per bucket in the scan)
+constexpr float BK_PER_OCTAVE = 16.f;
+constexpr float FIX_SCALE = 0x1p62f;   // probabilities are summed as 64-bit integers in units of 2^-62:
+constexpr double FIX_UNIT = 0x1p-62;   // the sums do not depend on the order of their terms
 
 // ----------------------------------------------------------------------------------- greedy
 // With n_slices > 1 the target rows' argmax arrives as one (value, index) pair per row slice
@@ -128,7 +128,8 @@ struct RowView {
   float c2;        // log2(e) * lz
   __device__ __forceinline__ RowView(const float* row, float max_logit, float lz, float inv_t)
       : x(row), m(max_logit), c1(inv_t * 1.4426950408889634f), c2(lz * 1.4426950408889634f) {}
-  __device__ __forceinline__ float of(float logit) const { return exp2_fast(fmaf(logit - m, c1, c2)); }
+  __device__ __forceinline__ float arg(float logit) const { return fmaf(logit - m, c1, c2); }  // log2 p
+  __device__ __forceinline__ float of(float logit) const { return exp2_fast(arg(logit)); }
   __device__ __forceinline__ float prob(int v) const { return of(x[v]); }
   __device__ __forceinline__ float4 of4(const float4 f) const { return make_float4(of(f.x), of(f.y), of(f.z), of(f.w)); }
   // tokens 4 i .. 4 i + 3 with one 16-byte load (the row must be 16-byte aligned)
@@ -183,193 +184,6 @@ __device__ __forceinline__ double residual_mass(const RowView& p, const RowView&
   return F;
 }
 
-// Sum over the workgroup of per-thread partial sums: four float32 partials per thread, then float64.
-// The two barriers order LDS traffic only (they do not wait for global stores: a wave's list is
-// read by that wave alone, and what thread 0 writes for the walk is read by a later kernel).
-__device__ __forceinline__ double block_total(float a0, float a1, float a2, float a3, double* red) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  double acc = wave_sum(((double)a0 + (double)a1) + ((double)a2 + (double)a3));
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // red is free
-  if (lane == 0) red[wave] = acc;
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  double F = 0.0;
-  for (int w = 0; w < AC_WAVES; ++w) F += red[w];
-  return F;
-}
-
-// A wave's list of live tokens in global memory, written through a ring of AC_RING pairs in LDS.
-// A store instruction costs the same whether it carries 64 lanes or a few, so the pairs that pass
-// are first packed in LDS and leave for global memory 128 at a time (16 bytes per lane).  Four
-// pairs per lane are appended per call, without branches: one prefix sum over the lanes' counts
-// gives each lane its first position, and a pair that does not pass is written to a slot of the
-// lane's own behind the ring instead.  Order of the list: lane, then slot.
-constexpr int AC_RING = 1024;
-struct ListWriter {
-  float2* __restrict__ wl;  // the wave's region
-  float2* ring;             // the wave's ring in LDS: AC_RING pairs and 64 more, one per lane, that are never read
-  int w;                    // pairs in global memory so far (a multiple of 128 until finish())
-  int staged;               // pairs in the ring, from position w % AC_RING on (fewer than 128 between calls)
-  bool keep;                // the whole list (at most AC_RING pairs) stays in the ring: nothing goes to global memory
-  __device__ __forceinline__ void append4(const bool (&live)[4], const float (&pv)[4], const float (&qv)[4]) {
-    const int lane = threadIdx.x & 63;
-    int c[4];
-    c[0] = live[0] ? 1 : 0;
-#pragma unroll
-    for (int k = 1; k < 4; ++k) c[k] = c[k - 1] + (live[k] ? 1 : 0);
-    const int incl = wave_prefix_sum(c[3]);
-    const int total = __builtin_amdgcn_readlane(incl, 63);
-    const int first = w + staged + incl - c[3];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int at = (first + (k ? c[k - 1] : 0)) & (AC_RING - 1);
-      ring[live[k] ? at : AC_RING + lane] = make_float2(pv[k], qv[k]);
-    }
-    staged += total;
-    while (!keep && staged >= 128) {  // (the same decision in every lane; at most three rounds)
-      __builtin_amdgcn_wave_barrier();
-      const float4 v = *reinterpret_cast<const float4*>(&ring[(w & (AC_RING - 1)) + 2 * lane]);
-      *reinterpret_cast<float4*>(&wl[w + 2 * lane]) = v;
-      w += 128;
-      staged -= 128;
-    }
-  }
-  __device__ __forceinline__ void finish() {
-    __builtin_amdgcn_wave_barrier();
-    if (keep) return;
-    for (int i = threadIdx.x & 63; i < staged; i += 64) wl[w + i] = ring[(w + i) & (AC_RING - 1)];
-    w += staged;
-    staged = 0;
-  }
-};
-
-// residual_mass for the first rejection at a node that has more to come: the same sum, and every
-// token whose term is positive leaves its pair (p(v), q(v)) in its wave's list.  beta only grows
-// along a chain, so a token whose term has reached zero stays out of every later sum: the later
-// passes (residual_mass_list) read the lists instead of the two vocabulary rows and evaluate no
-// exponentials.  Both rows must be 16-byte aligned and V >= 4 * AC_THREADS.  The order of a list is
-// fixed by the data (iteration, component, lane), so the sums are the same from run to run.
-// The logits of the next four iterations are requested before the current four are worked on (all
-// loads unconditional, out-of-range lanes re-read the last element): the stores into the list keep
-// the compiler from moving loads, so the overlap has to be written out.
-__device__ __forceinline__ double residual_mass_build(const RowView& p, const RowView& q, double beta, int V,
-                                                      double* red, float2* __restrict__ wl, float2* ring,
-                                                      int& wcount) {
-  const int tid = threadIdx.x;
-  const float bf = (float)beta;
-  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-  const int n4 = V >> 2;
-  const int n_it = (n4 + AC_THREADS - 1) / AC_THREADS;  // the same for every thread: the ballots need whole waves
-  const float4* __restrict__ px = reinterpret_cast<const float4*>(p.x);
-  const float4* __restrict__ qx = reinterpret_cast<const float4*>(q.x);
-  float4 fp[4], fq[4], np_[4], nq_[4];
-  auto fetch = [&](int k0, float4 (&dp)[4], float4 (&dq)[4]) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = min(tid + (k0 + u) * AC_THREADS, n4 - 1);
-      dp[u] = px[i];
-      dq[u] = qx[i];
-    }
-  };
-  ListWriter out{wl, ring, 0, 0, false};
-  fetch(0, fp, fq);
-  for (int k0 = 0; k0 < n_it; k0 += 4) {
-    fetch(k0 + 4, np_, nq_);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (k0 + u < n_it) {
-        const bool in = tid + (k0 + u) * AC_THREADS < n4;
-        const float4 pp = p.of4(fp[u]), qq = q.of4(fq[u]);
-        const float t0 = in ? fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) : 0.f;
-        const float t1 = in ? fmaxf(fmaf(-bf, qq.y, pp.y), 0.f) : 0.f;
-        const float t2 = in ? fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) : 0.f;
-        const float t3 = in ? fmaxf(fmaf(-bf, qq.w, pp.w), 0.f) : 0.f;
-        a0 += t0;
-        a1 += t1;
-        a2 += t2;
-        a3 += t3;
-        const bool live[4] = {t0 > 0.f, t1 > 0.f, t2 > 0.f, t3 > 0.f};
-        const float pv[4] = {pp.x, pp.y, pp.z, pp.w}, qv[4] = {qq.x, qq.y, qq.z, qq.w};
-        out.append4(live, pv, qv);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      fp[u] = np_[u];
-      fq[u] = nq_[u];
-    }
-  }
-  {  // the last V % 4 tokens
-    const int v = (n4 << 2) + tid;
-    float pv = 0.f, qv = 0.f, t = 0.f;
-    if (v < V) {
-      pv = p.prob(v);
-      qv = q.prob(v);
-      t = fmaxf(fmaf(-bf, qv, pv), 0.f);
-    }
-    a0 += t;
-    const bool live[4] = {t > 0.f, false, false, false};
-    const float pv4[4] = {pv, 0.f, 0.f, 0.f}, qv4[4] = {qv, 0.f, 0.f, 0.f};
-    out.append4(live, pv4, qv4);
-  }
-  out.finish();
-  wcount = out.w;
-  return block_total(a0, a1, a2, a3, red);
-}
-
-// residual_mass over the lists that residual_mass_build left (two pairs per lane and load).  With
-// `compact` the pairs whose term is still positive move to the front of the list, in place: a pair
-// is written at or before the position it was read from, and the group of pairs that is read ahead
-// lies behind every position written meanwhile.  A list of at most AC_RING pairs moves into the
-// wave's ring in LDS and stays there (IN_LDS: it is read from the ring), which takes the round trips
-// to memory out of the short passes at the end of a long chain.
-// This is the wave's own part of the pass (a[] receives the lanes' four partial sums): waves of a
-// workgroup may take different instantiations, so the workgroup's barriers stay with the caller.
-template <bool IN_LDS>
-__device__ __forceinline__ void residual_mass_list(double beta, float2* __restrict__ wl, float2* ring, int& wcount,
-                                                   bool& in_lds, bool compact, float (&a)[4]) {
-  constexpr int LU = 4;  // loads per lane and group: 512 pairs per wave
-  const int lane = threadIdx.x & 63;
-  const float bf = (float)beta;
-  const int n = wcount;
-  const int last2 = n > 1 ? (n - 1) >> 1 : 0;  // last float4 that holds a pair (list and ring hold 64 pairs at least)
-  const float4* src = IN_LDS ? reinterpret_cast<const float4*>(ring) : reinterpret_cast<const float4*>(wl);
-  float4 cur[LU], nxt[LU];
-  auto fetch = [&](int base, float4 (&e)[LU]) {  // unconditional: lanes past the end re-read the last pairs
-#pragma unroll
-    for (int u = 0; u < LU; ++u) e[u] = src[min((base >> 1) + u * 64 + lane, last2)];
-  };
-  ListWriter out{wl, ring, 0, 0, n <= AC_RING};
-  fetch(0, cur);
-  for (int base = 0; base < n; base += LU * 128) {
-    fetch(base + LU * 128, nxt);
-#pragma unroll
-    for (int u = 0; u < LU; u += 2) {
-      const int i0 = base + u * 128 + 2 * lane, i1 = i0 + 128;
-      const float t0 = i0 < n ? fmaxf(fmaf(-bf, cur[u].y, cur[u].x), 0.f) : 0.f;
-      const float t1 = i0 + 1 < n ? fmaxf(fmaf(-bf, cur[u].w, cur[u].z), 0.f) : 0.f;
-      const float t2 = i1 < n ? fmaxf(fmaf(-bf, cur[u + 1].y, cur[u + 1].x), 0.f) : 0.f;
-      const float t3 = i1 + 1 < n ? fmaxf(fmaf(-bf, cur[u + 1].w, cur[u + 1].z), 0.f) : 0.f;
-      a[0] += t0;
-      a[1] += t1;
-      a[2] += t2;
-      a[3] += t3;
-      if (compact) {
-        const bool live[4] = {t0 > 0.f, t1 > 0.f, t2 > 0.f, t3 > 0.f};
-        const float pv[4] = {cur[u].x, cur[u].z, cur[u + 1].x, cur[u + 1].z};
-        const float qv[4] = {cur[u].y, cur[u].w, cur[u + 1].y, cur[u + 1].w};
-        out.append4(live, pv, qv);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < LU; ++u) cur[u] = nxt[u];
-  }
-  if (compact) {
-    out.finish();
-    wcount = out.keep ? out.staged : out.w;
-    in_lds = out.keep;
-  }
-}
-
 // The same term for one token, as residual_mass forms it (used to take a frozen token's live term
 // out of the sum again).
 __device__ __forceinline__ double residual_term(const RowView& p, const RowView& q, double beta, int v) {
@@ -404,6 +218,238 @@ __device__ __forceinline__ int gather_children(const int32_t* __restrict__ paren
   return nk;
 }
 
+// ------------------------------------------------------------------ the sorted residual
+// Along a node's chain of rejections only beta changes: F(beta) = sum_v max(p(v) - beta q(v), 0),
+// taken at an increasing sequence of beta >= 1 that is not known in advance.  A token contributes
+// p - beta q while its ratio p / q exceeds beta and nothing afterwards.  So, for every node with
+// at least two children, three small kernels that run on the whole chip sort the tokens with
+// p > q by their ratio into BK_N buckets (a counting sort: count per vocabulary slice and bucket,
+// scan, scatter) and keep, per bucket, the sums of p and of q.  F(beta) is then
+//     sum over the buckets well above beta of (P_b - beta Q_b)      two suffix sums, read once
+//   + sum over the tokens of the three buckets around beta of max(p - beta q, 0)
+// which is what k_accept_chain evaluates per rejection: a few thousand pairs instead of two
+// vocabulary rows.  A token's bucket is floor(BK_PER_OCTAVE * log2(p / q)), taken from the two
+// exponent arguments (p = exp2(a_p)): the rounding of that difference is many orders below a
+// bucket's width, and one bucket to either side of beta's own is still treated token by token, so
+// no token is ever taken for live or dead by its bucket alone when it is not.  All sums are 64-bit
+// integers in units of 2^-62 (LDS and per-slice partial sums), so neither the order in which the
+// lanes' atomic additions arrive nor the order of the tokens inside a bucket changes a result.
+struct BucketWs {
+  uint32_t* count;            // [NN][BK_SLICES][BK_N] live tokens per (slice, bucket); after the scan: first position
+  unsigned long long* psum;   // [NN][BK_SLICES][BK_N] their p, summed
+  unsigned long long* qsum;   // [NN][BK_SLICES][BK_N] their q
+  uint32_t* start;            // [NN][BK_N + 1] first position of a bucket in `pairs` (ascending ratio)
+  unsigned long long* sp;     // [NN][BK_N + 1] sum of p over the buckets >= b
+  unsigned long long* sq;     // [NN][BK_N + 1] sum of q over them
+  float2* pairs;              // [NN][V] (p, q) of the live tokens, bucket by bucket
+  int32_t* nk;                // [NN] number of children the chain will try
+};
+
+__device__ __forceinline__ int bucket_of(float ap, float aq) {
+  return (int)fminf(fmaxf((ap - aq) * BK_PER_OCTAVE, 0.f), (float)(BK_N - 1));
+}
+__device__ __forceinline__ unsigned long long to_fixed(float x) { return (unsigned long long)(x * FIX_SCALE); }
+
+// Sequence, local row and number of children to try of global row g (all threads; one barrier).
+struct NodeRef {
+  int o, n, cur, nk;
+};
+__device__ __forceinline__ NodeRef node_ref(int g, const int32_t* __restrict__ parent,
+                                            const int32_t* __restrict__ node_offsets, int B, int max_depth,
+                                            int* lds_count) {
+  int lo = 0, hi = B;  // sequence of this row: last s with node_offsets[s] <= g
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (node_offsets[mid] <= g) lo = mid; else hi = mid;
+  }
+  NodeRef r;
+  r.o = node_offsets[lo];
+  r.n = node_offsets[lo + 1] - r.o;
+  r.cur = g - r.o;
+  r.nk = 0;
+  if (r.cur >= r.n) return r;  // (an empty sequence before this row's: cannot happen, offsets are monotone)
+  int depth = 0;
+  for (int j = parent[r.o + r.cur]; j >= 0; j = parent[r.o + j]) ++depth;
+  if (threadIdx.x == 0) *lds_count = 0;
+  __syncthreads();
+  if (depth < max_depth) {
+    int c = 0;
+    for (int i = 1 + threadIdx.x; i < r.n; i += blockDim.x) c += parent[r.o + i] == r.cur ? 1 : 0;
+    if (c) atomicAdd(lds_count, c);
+  }
+  __syncthreads();
+  r.nk = *lds_count < AC_MAX_KIDS ? *lds_count : AC_MAX_KIDS;
+  return r;
+}
+
+// grid (BK_SLICES, NN).  SCATTER false: counts and sums of slice blockIdx.x of row blockIdx.y;
+// SCATTER true (after k_bucket_scan): the same pass again, now placing every live pair.
+template <bool SCATTER>
+__global__ __launch_bounds__(BK_THREADS) void k_bucket_pass(
+    const float* __restrict__ target, const float* __restrict__ draft, int64_t row_stride,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets, int B, int V, float inv_t,
+    int max_depth, const int32_t* __restrict__ t_arg, const float* __restrict__ t_lz,
+    const int32_t* __restrict__ d_arg, const float* __restrict__ d_lz, BucketWs ws) {
+  __shared__ unsigned cnt[BK_N];  // SCATTER: the next free position of each bucket
+  __shared__ unsigned long long ps[BK_N], qs[BK_N];
+  __shared__ int n_kids;
+  const int slice = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+  int nk;
+  if (SCATTER) {
+    nk = ws.nk[g];
+  } else {
+    nk = node_ref(g, parent, node_offsets, B, max_depth, &n_kids).nk;
+    if (slice == 0 && tid == 0) ws.nk[g] = nk;
+  }
+  if (nk < 2) return;  // a single rejection is one plain pass of the chain kernel
+  const int64_t slot = ((int64_t)g * BK_SLICES + slice) * BK_N;
+  for (int b = tid; b < BK_N; b += BK_THREADS) {
+    cnt[b] = SCATTER ? ws.count[slot + b] : 0u;
+    ps[b] = 0ull;
+    qs[b] = 0ull;
+  }
+  const float* p_row = target + (int64_t)g * row_stride;
+  const float* q_row = draft + (int64_t)g * row_stride;
+  const RowView p(p_row, p_row[t_arg[g]], t_lz[g], inv_t);
+  const RowView q(q_row, q_row[d_arg[g]], d_lz[g], inv_t);
+  float2* __restrict__ pairs = ws.pairs + (int64_t)g * V;
+  __syncthreads();
+  auto token = [&](float xp, float xq) {
+    const float ap = p.arg(xp), aq = q.arg(xq);
+    const float pv = exp2_fast(ap), qv = exp2_fast(aq);
+    if (pv > qv) {  // live at beta = 1, where every chain starts
+      const int b = bucket_of(ap, aq);
+      if (SCATTER) {
+        pairs[atomicAdd(&cnt[b], 1u)] = make_float2(pv, qv);
+      } else {
+        atomicAdd(&cnt[b], 1u);
+        atomicAdd(&ps[b], to_fixed(pv));
+        atomicAdd(&qs[b], to_fixed(qv));
+      }
+    }
+  };
+  const int n4 = V >> 2;
+  const int per = (n4 + BK_SLICES - 1) / BK_SLICES;
+  const int i1 = min(n4, (slice + 1) * per);
+  const float4* __restrict__ px = reinterpret_cast<const float4*>(p_row);
+  const float4* __restrict__ qx = reinterpret_cast<const float4*>(q_row);
+#pragma unroll 2
+  for (int i = slice * per + tid; i < i1; i += BK_THREADS) {
+    const float4 fp = px[i], fq = qx[i];
+    token(fp.x, fq.x);
+    token(fp.y, fq.y);
+    token(fp.z, fq.z);
+    token(fp.w, fq.w);
+  }
+  if (slice == BK_SLICES - 1) {  // the last V % 4 tokens
+    const int v = (n4 << 2) + tid;
+    if (v < V) token(p_row[v], q_row[v]);
+  }
+  if (!SCATTER) {
+    __syncthreads();
+    for (int b = tid; b < BK_N; b += BK_THREADS) {
+      ws.count[slot + b] = cnt[b];
+      ws.psum[slot + b] = ps[b];
+      ws.qsum[slot + b] = qs[b];
+    }
+  }
+}
+
+// grid NN, one thread per bucket: per-slice counts become first positions, bucket totals become
+// the suffix sums the chain reads.
+__global__ __launch_bounds__(BK_N) void k_bucket_scan(BucketWs ws) {
+  __shared__ unsigned s_cnt[BK_N];
+  __shared__ unsigned long long s_p[BK_N], s_q[BK_N];
+  const int g = blockIdx.x, b = threadIdx.x;
+  if (ws.nk[g] < 2) return;
+  unsigned off[BK_SLICES], total = 0u;
+  unsigned long long tp = 0ull, tq = 0ull;
+#pragma unroll
+  for (int sl = 0; sl < BK_SLICES; ++sl) {
+    const int64_t at = ((int64_t)g * BK_SLICES + sl) * BK_N + b;
+    off[sl] = total;
+    total += ws.count[at];
+    tp += ws.psum[at];
+    tq += ws.qsum[at];
+  }
+  s_cnt[b] = total;
+  s_p[b] = tp;
+  s_q[b] = tq;
+  __syncthreads();
+  // inclusive prefix counts (ascending) and inclusive suffix sums (descending), log-step
+  for (int d = 1; d < BK_N; d <<= 1) {
+    const unsigned c = b >= d ? s_cnt[b - d] : 0u;
+    const unsigned long long ap = b + d < BK_N ? s_p[b + d] : 0ull, aq = b + d < BK_N ? s_q[b + d] : 0ull;
+    __syncthreads();
+    s_cnt[b] += c;
+    s_p[b] += ap;
+    s_q[b] += aq;
+    __syncthreads();
+  }
+  const unsigned first = s_cnt[b] - total;
+#pragma unroll
+  for (int sl = 0; sl < BK_SLICES; ++sl) ws.count[((int64_t)g * BK_SLICES + sl) * BK_N + b] = first + off[sl];
+  const int64_t row = (int64_t)g * (BK_N + 1);
+  ws.start[row + b] = first;
+  ws.sp[row + b] = s_p[b];
+  ws.sq[row + b] = s_q[b];
+  if (b == BK_N - 1) {
+    ws.start[row + BK_N] = first + total;
+    ws.sp[row + BK_N] = 0ull;
+    ws.sq[row + BK_N] = 0ull;
+  }
+}
+
+// A row's bucket tables, staged in LDS once per chain (the chain is serial: what it reads per
+// rejection should not be a round trip to memory).
+struct BucketTables {
+  unsigned start[BK_N + 1];
+  unsigned long long sp[BK_N + 1], sq[BK_N + 1];
+};
+__device__ __forceinline__ void load_bucket_tables(const BucketWs& ws, int g, BucketTables& t) {
+  const int64_t row = (int64_t)g * (BK_N + 1);
+  for (int b = threadIdx.x; b <= BK_N; b += blockDim.x) {
+    t.start[b] = ws.start[row + b];
+    t.sp[b] = ws.sp[row + b];
+    t.sq[b] = ws.sq[row + b];
+  }
+}
+
+// What the first wave hands to the others for one rejection, and what they hand back.
+struct BucketStep {
+  double beta;
+  int lo, hi;                          // positions in `pairs` of the tokens to take one by one
+  unsigned long long part[AC_WAVES];   // their terms, summed per wave
+};
+
+// beta's own bucket with one bucket to either side: [b_lo, b_hi).  NaN and infinity end up at valid
+// indices as well; float32 is enough to pick the bucket, as it is for the tokens' buckets.
+__device__ __forceinline__ void near_buckets(double beta, int& b_lo, int& b_hi) {
+  const int own = (int)fminf(fmaxf(__log2f((float)beta) * BK_PER_OCTAVE, 0.f), (float)(BK_N - 1));
+  b_lo = own > 0 ? own - 1 : 0;
+  b_hi = own + 2 < BK_N ? own + 2 : BK_N;
+}
+
+// The terms max(p - beta q, 0) of pairs [lo, hi), all threads of the workgroup, summed per wave into
+// step.part.  They are formed in float64 and summed as integers in units of 2^-52 (the fraction
+// bits of 1 + term, term < 1): the order of the pairs inside a bucket, which the scatter's atomic
+// additions decide, does not reach the result.
+__device__ __forceinline__ void near_terms(const float2* __restrict__ pairs, BucketStep& step) {
+  const int tid = threadIdx.x;
+  const double beta = step.beta;
+  const int hi = step.hi;
+  unsigned long long acc = 0ull;
+#pragma unroll 4
+  for (int i = step.lo + tid; i < hi; i += AC_THREADS) {
+    const float2 e = pairs[i];
+    const double term = fmin(fmax((double)e.x - beta * (double)e.y, 0.0), 0x1.fffffffffffffp-1);
+    acc += (unsigned long long)__double_as_longlong(1.0 + term) & 0xfffffffffffffull;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+  if ((tid & 63) == 0) step.part[tid >> 6] = acc;
+}
+
 // What the stochastic walk needs from a node's chain of rejections.
 struct ChainOut {
   double* child_p;       // [NN] current target probability of the child's token when its turn comes
@@ -419,14 +465,15 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
     const float* __restrict__ target, const float* __restrict__ draft, int64_t row_stride,
     const int32_t* __restrict__ token, const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets,
     int B, int V, float inv_t, int max_depth, const int32_t* __restrict__ t_arg, const float* __restrict__ t_lz,
-    const int32_t* __restrict__ d_arg, const float* __restrict__ d_lz, ChainOut out, float2* __restrict__ lists) {
+    const int32_t* __restrict__ d_arg, const float* __restrict__ d_lz, ChainOut out, BucketWs bk) {
   __shared__ int kids[AC_MAX_KIDS];
   __shared__ int kids_sorted[AC_MAX_KIDS];
   __shared__ int n_kids;
   __shared__ double rej_w[AC_MAX_KIDS];
   __shared__ float kid_p[AC_MAX_KIDS], kid_q[AC_MAX_KIDS];  // p(x), q(x) of each child's token
-  __shared__ __attribute__((aligned(16))) float2 rings[AC_WAVES][AC_RING + 64];  // see ListWriter
   __shared__ double red[AC_WAVES];
+  __shared__ BucketTables tables;
+  __shared__ BucketStep step;
   const int g = blockIdx.x, tid = threadIdx.x;
   int lo = 0, hi = B;  // sequence of this row: last s with node_offsets[s] <= g
   while (hi - lo > 1) {
@@ -450,48 +497,79 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
   const RowView q(q_row, q_row[q_arg], q_lz, inv_t);
   // every child's token and its two probabilities, fetched side by side: the chain below is serial,
   // and a round trip to memory per step would dominate it
+  // the sorted residual (bk.pairs may be NULL) exists for the rows with at least two children
+  const bool sorted = bk.pairs != nullptr && nk >= 2;
+  if (sorted) load_bucket_tables(bk, g, tables);
   if (tid < nk) {
     const int x = token[o + kids_sorted[tid]];
     kid_p[tid] = p.prob(x);
     kid_q[tid] = q.prob(x);
   }
   __syncthreads();
-  // lists of live tokens (`lists` may be NULL): worth their stores when a second rejection follows
-  const bool use_list = lists != nullptr && nk >= 2 && V >= 4 * AC_THREADS && p.aligned16() && q.aligned16();
-  float2* __restrict__ wl = use_list ? lists + ((int64_t)g * AC_WAVES + (tid >> 6)) * list_wave_cap(V) : nullptr;
-  float2* ring = rings[tid >> 6];
-  int wcount = 0;
-  bool in_lds = false;  // (per wave)
+  const float2* __restrict__ pairs = sorted ? bk.pairs + (int64_t)g * V : nullptr;
   double beta = 0.0, Z = 1.0, sumq = 0.0;
-  for (int j = 0; j < nk; ++j) {
-    const int c = kids_sorted[j];
-    const double px = (double)kid_p[j];
-    const double qx = (double)kid_q[j];
-    const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
-    const double qc = qx / (1.0 - sumq);              // current q(x)
-    // rejected: p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)
-    beta += Z / (1.0 - sumq);
-    sumq += qx;
-    const double frozen = fmax(px - beta * qx, 0.0);
-    if (tid == 0) {
-      out.child_p[o + c] = pc;
-      out.child_q[o + c] = qc;
-      out.child_frozen[o + c] = frozen;
-      rej_w[j] = frozen;
+  if (sorted) {
+    // The first wave keeps the chain's scalars; the others only help with the tokens around beta.
+    // (Sixteen waves that all repeat the scalar part take issue slots from one another: 4 us a step.)
+    const bool lead = tid < 64;
+    for (int j = 0; j < nk; ++j) {
+      int b_hi = 0;
+      if (lead) {
+        const int c = kids_sorted[j];
+        const double px = (double)kid_p[j];
+        const double qx = (double)kid_q[j];
+        const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
+        const double qc = qx / (1.0 - sumq);              // current q(x)
+        beta += Z / (1.0 - sumq);
+        sumq += qx;
+        const double frozen = fmax(px - beta * qx, 0.0);
+        int b_lo;
+        near_buckets(beta, b_lo, b_hi);
+        rej_w[j] = frozen;  // (every lane of the wave stores the same value; LDS keeps a wave's order)
+        if (tid == 0) {
+          out.child_p[o + c] = pc;
+          out.child_q[o + c] = qc;
+          out.child_frozen[o + c] = frozen;
+          step.beta = beta;
+          step.lo = (int)tables.start[b_lo];
+          step.hi = (int)tables.start[b_hi];
+        }
+      }
+      __syncthreads();
+      near_terms(pairs, step);
+      __syncthreads();
+      if (lead) {
+        unsigned long long near = 0ull;
+        for (int w = 0; w < AC_WAVES; ++w) near += step.part[w];
+        double F = ((double)tables.sp[b_hi] - beta * (double)tables.sq[b_hi]) * FIX_UNIT + (double)near * 0x1p-52;
+        // a rejected token's weight is frozen: its live term leaves the sum
+        for (int i = 0; i <= j; ++i) F += rej_w[i] - fmax((double)kid_p[i] - beta * (double)kid_q[i], 0.0);
+        Z = F;
+      }
     }
-    double F;  // (the barriers of a pass also publish rej_w)
-    if (!use_list) F = residual_mass(p, q, beta, V, red);
-    else if (j == 0) F = residual_mass_build(p, q, beta, V, red, wl, ring, wcount);
-    else {
-      float a[4] = {0.f, 0.f, 0.f, 0.f};
-      if (__builtin_amdgcn_readfirstlane((int)in_lds)) residual_mass_list<true>(beta, wl, ring, wcount, in_lds, j + 1 < nk, a);
-      else residual_mass_list<false>(beta, wl, ring, wcount, in_lds, j + 1 < nk, a);
-      F = block_total(a[0], a[1], a[2], a[3], red);
+  } else {
+    for (int j = 0; j < nk; ++j) {
+      const int c = kids_sorted[j];
+      const double px = (double)kid_p[j];
+      const double qx = (double)kid_q[j];
+      const double pc = fmax(px - beta * qx, 0.0) / Z;  // current p(x)
+      const double qc = qx / (1.0 - sumq);              // current q(x)
+      // rejected: p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)
+      beta += Z / (1.0 - sumq);
+      sumq += qx;
+      const double frozen = fmax(px - beta * qx, 0.0);
+      if (tid == 0) {
+        out.child_p[o + c] = pc;
+        out.child_q[o + c] = qc;
+        out.child_frozen[o + c] = frozen;
+        rej_w[j] = frozen;
+      }
+      double F = residual_mass(p, q, beta, V, red);  // (its barriers also publish rej_w)
+      // a rejected token's weight is frozen: its live term, as the pass formed it, leaves the sum
+      const float bf = (float)beta;
+      for (int i = 0; i <= j; ++i) F += rej_w[i] - (double)fmaxf(fmaf(-bf, kid_q[i], kid_p[i]), 0.f);
+      Z = F;
     }
-    // a rejected token's weight is frozen: its live term (as the passes form it) leaves the sum
-    const float bf = (float)beta;
-    for (int i = 0; i <= j; ++i) F += rej_w[i] - (double)fmaxf(fmaf(-bf, kid_q[i], kid_p[i]), 0.f);
-    Z = F;
   }
   if (tid == 0) {
     out.node_beta[o + cur] = beta;
@@ -679,6 +757,25 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
   }
 }
 
+// Bytes of the sorted residual's arrays for NN rows (0 beyond BK_NODES rows); with a carver, also
+// takes them.
+static size_t bucket_workspace(int NN, int V, Carver* c, BucketWs* ws) {
+  if (NN > BK_NODES) return 0;
+  const size_t n_sb = (size_t)NN * BK_SLICES * BK_N, n_b = (size_t)NN * (BK_N + 1);
+  if (c != nullptr) {
+    ws->count = c->take<uint32_t>(n_sb);
+    ws->psum = c->take<unsigned long long>(n_sb);
+    ws->qsum = c->take<unsigned long long>(n_sb);
+    ws->start = c->take<uint32_t>(n_b);
+    ws->sp = c->take<unsigned long long>(n_b);
+    ws->sq = c->take<unsigned long long>(n_b);
+    ws->pairs = c->take<float2>((size_t)NN * V);
+    ws->nk = c->take<int32_t>(NN);
+  }
+  return align_up(n_sb * 4, 256) + 2 * align_up(n_sb * 8, 256) + align_up(n_b * 4, 256) + 2 * align_up(n_b * 8, 256) +
+         align_up((size_t)NN * V * sizeof(float2), 256) + align_up((size_t)NN * 4, 256);
+}
+
 }  // namespace hs
 
 extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
@@ -687,11 +784,7 @@ extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
   const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
   // five doubles per row: what the rejection chains hand to the walk
   const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256);
-  // the rejection chains' lists of live tokens: a pair of floats per token and row
-  const size_t lists = NN <= hs::AC_LIST_NODES
-                           ? hs::align_up((size_t)NN * hs::AC_WAVES * hs::list_wave_cap(V) * sizeof(float2), 256)
-                           : 0;
-  return 2 * per_set + chain + lists + hs::row_topk_workspace(NN, V, 1);
+  return 2 * per_set + chain + hs::bucket_workspace(NN, V, nullptr, nullptr) + hs::row_topk_workspace(NN, V, 1);
 }
 
 extern "C" hs_status hs_verify_accept(const float* target_logits, const float* draft_logits, int64_t row_stride,
@@ -729,7 +822,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   float *t_lz = nullptr, *d_lz = nullptr;
   hs::ScanSlices slices{nullptr, nullptr, 1};
   hs::ChainOut chain{nullptr, nullptr, nullptr, nullptr, nullptr};
-  float2* lists = nullptr;
+  hs::BucketWs bk{};  // (all NULL: no sorted residual)
   if (NN > 0) {
     hs::Carver c(workspace);
     t_arg = c.take<int32_t>(NN);
@@ -743,7 +836,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     chain.child_frozen = c.take<double>(NN);
     chain.node_beta = c.take<double>(NN);
     chain.node_Z = c.take<double>(NN);
-    if (NN <= hs::AC_LIST_NODES) lists = c.take<float2>((size_t)NN * hs::AC_WAVES * hs::list_wave_cap(V));
+    hs::bucket_workspace(NN, V, &c, &bk);
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
     // greedy: the merge of the row slices is done by the accept kernel (one launch less)
@@ -762,9 +855,27 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     return hs::launch_status("accept (greedy)");
   }
   if (mode == HS_ACCEPT_STOCHASTIC && NN > 0) {
+    // the sorted residual pays from a few thousand tokens on and needs 16-byte aligned rows
+    const bool sorted = bk.pairs != nullptr && V >= 4096 && row_stride % 4 == 0 &&
+                        reinterpret_cast<uintptr_t>(target_logits) % 16 == 0 &&
+                        reinterpret_cast<uintptr_t>(draft_logits) % 16 == 0;
+    if (sorted) {
+      const dim3 grid(hs::BK_SLICES, NN);
+      hipLaunchKernelGGL(hs::k_bucket_pass<false>, grid, dim3(hs::BK_THREADS), 0, st, target_logits, draft_logits,
+                         row_stride, parent, node_offsets, B, V, 1.0f / temperature, max_depth, t_arg, t_lz, d_arg,
+                         d_lz, bk);
+      hipLaunchKernelGGL(hs::k_bucket_scan, dim3(NN), dim3(hs::BK_N), 0, st, bk);
+      hipLaunchKernelGGL(hs::k_bucket_pass<true>, grid, dim3(hs::BK_THREADS), 0, st, target_logits, draft_logits,
+                         row_stride, parent, node_offsets, B, V, 1.0f / temperature, max_depth, t_arg, t_lz, d_arg,
+                         d_lz, bk);
+      hs_status r = hs::launch_status("accept (sorted residual)");
+      if (r != HS_OK) return r;
+    } else {
+      bk.pairs = nullptr;
+    }
     hipLaunchKernelGGL(hs::k_accept_chain, dim3(NN), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits,
                        row_stride, token, parent, node_offsets, B, V, 1.0f / temperature, max_depth, t_arg, t_lz,
-                       d_arg, d_lz, chain, lists);
+                       d_arg, d_lz, chain, bk);
     hs_status r = hs::launch_status("accept (rejection chains)");
     if (r != HS_OK) return r;
   }
