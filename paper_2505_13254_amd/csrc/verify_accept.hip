@@ -8,14 +8,17 @@
 //               target's argmax; the deepest confirmed node is the end of the accepted path.
 //   stochastic  the walk is serial by nature, but what a node's children face is not: the state
 //               after j rejections at a node depends on the node and j alone, not on the path that
-//               led there.  Per rejection the normaliser of the residual distribution needs one
-//               cooperative pass over the node's two vocabulary rows; the residual itself is never
-//               materialised: after j rejections it is max(p(v) - beta_j q(v), 0) for every token
-//               not yet rejected (beta_j a scalar that accumulates Z_i / (1 - sum of rejected q)),
-//               and frozen at its value of the time for a rejected token.  So one workgroup per
-//               node with children runs that node's chain of rejections ahead of the walk, all
-//               nodes in parallel (k_accept_chain), and leaves each child's pair of current
-//               probabilities; the walk itself (k_accept_walk, one workgroup per sequence) then
+//               led there.  The residual itself is never materialised: after j rejections it is
+//               max(p(v) - beta_j q(v), 0) for every token not yet rejected (beta_j a scalar that
+//               accumulates Z_i / (1 - sum of rejected q)), and frozen at its value of the time
+//               for a rejected token; only its normaliser is needed per rejection.  A node with
+//               one child gets it from one cooperative pass over its two vocabulary rows; for a
+//               node with several children the tokens with p > q are first sorted by p / q into
+//               buckets with their sums (three kernels on the whole chip), after which every
+//               normaliser of the chain is two suffix sums plus the tokens of three buckets.  One
+//               workgroup per node with children runs that node's chain of rejections ahead of
+//               the walk, all nodes in parallel (k_accept_chain), and leaves each child's pair of
+//               current probabilities; the walk itself (k_accept_walk, one workgroup per sequence) then
 //               only compares uniforms with them, and draws the bonus token at the node where it
 //               stops: an inverse-CDF search done as row sums of 64 tokens, a scan of the row sums,
 //               and a scan inside the one row that is hit.
