@@ -271,7 +271,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
                                                             int32_t* __restrict__ topk_idx,
                                                             float* __restrict__ topk_logp,
                                                             float* __restrict__ ent_topk,
-                                                            float* __restrict__ ent_full, float* __restrict__ lse) {
+                                                            float* __restrict__ ent_full, float* __restrict__ lse,
+                                                            const uint8_t* __restrict__ row_active) {
+  if (row_active != nullptr && row_active[blockIdx.y] == 0) return;  // (the whole workgroup: a row nobody will read)
   constexpr int SCAN_WAVES = SCAN_THREADS / 64;
   constexpr int SCAN_GROUPS = SCAN_WAVES * 4 < 64 ? SCAN_WAVES * 4 : 64;  // rows of 16 lanes, at most one per lane
   constexpr int SCAN_TILE = scan_tile(SCAN_THREADS);
@@ -507,10 +509,12 @@ __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __r
                                                                float* __restrict__ topk_logp,
                                                                float* __restrict__ ent_topk,
                                                                float* __restrict__ ent_full,
-                                                               float* __restrict__ lse) {
+                                                               float* __restrict__ lse,
+                                                               const uint8_t* __restrict__ row_active) {
   __shared__ MergeScratch<FIN_CAP> sm;
   const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
+  if (row_active != nullptr && row_active[row] == 0) return;
   merge_slices(part_stats + row * S, part_val + row * S * K, part_idx + row * S * K, S, K, inv_t, sm, tid, FIN_THREADS);
   write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
 }
@@ -524,7 +528,7 @@ size_t row_topk_workspace(int R, int V, int K) {
 
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
-                          void* workspace, hipStream_t stream, ScanSlices* slices) {
+                          void* workspace, hipStream_t stream, ScanSlices* slices, const uint8_t* row_active) {
   ScanPlan p = plan_scan(R, V);
   Carver c(workspace);
   size_t n = (size_t)R * p.splits;
@@ -536,7 +540,7 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   dim3 grid(p.splits, R);
 #define HS_SCAN_LAUNCH(VEC, T)                                                                                      \
   hipLaunchKernelGGL((k_scan_rows<VEC, T>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
-                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse)
+                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active)
   if (p.threads == SCAN_BIG) {
     if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG);
     else HS_SCAN_LAUNCH(false, SCAN_BIG);
@@ -549,7 +553,7 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   if (slices != nullptr) *slices = ScanSlices{part_val, part_idx, p.splits};
   if (st != HS_OK || p.splits == 1 || slices != nullptr) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,
-                     p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse);
+                     p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active);
   return launch_status("row scan merge");
 }
 

@@ -40,6 +40,8 @@ size_t row_topk_workspace(int R, int V, int K);
 // caller, who receives the per-slice results instead: entry (row * count + slice) * K + k of
 // val / idx is the slice's k-th best pair (an unused entry has index INT_MAX).  count == 1 means
 // the outputs were written in full.
+// `row_active` (device, may be NULL): one byte per row; a row whose byte is 0 is neither read nor
+// written.
 struct ScanSlices {
   const float* val;
   const int32_t* idx;
@@ -47,7 +49,8 @@ struct ScanSlices {
 };
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
-                          void* workspace, hipStream_t stream, ScanSlices* slices = nullptr);
+                          void* workspace, hipStream_t stream, ScanSlices* slices = nullptr,
+                          const uint8_t* row_active = nullptr);
 
 #define HS_REQUIRE(cond, st, ...) \
   do {                            \

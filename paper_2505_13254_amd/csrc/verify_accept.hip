@@ -453,6 +453,19 @@ __device__ __forceinline__ void near_terms(const float2* __restrict__ pairs, Buc
   if ((tid & 63) == 0) step.part[tid >> 6] = acc;
 }
 
+// One workgroup per sequence: has_child[row] = 1 for the rows that are somebody's parent, 0 for
+// the others (whose draft rows nobody reads).
+__global__ __launch_bounds__(GR_THREADS) void k_mark_parents(const int32_t* __restrict__ parent,
+                                                             const int32_t* __restrict__ node_offsets,
+                                                             uint8_t* __restrict__ has_child) {
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const int o = node_offsets[s];
+  const int n = node_offsets[s + 1] - o;
+  for (int i = tid; i < n; i += GR_THREADS) has_child[o + i] = 0;
+  __syncthreads();
+  for (int i = 1 + tid; i < n; i += GR_THREADS) has_child[o + parent[o + i]] = 1;
+}
+
 // What the stochastic walk needs from a node's chain of rejections.
 struct ChainOut {
   double* child_p;       // [NN] current target probability of the child's token when its turn comes
@@ -786,7 +799,7 @@ extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
   // per row: argmax, -ln Z and an unused Top-1 entropy, for the target and for the draft rows
   const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
   // five doubles per row: what the rejection chains hand to the walk
-  const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256);
+  const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256) + hs::align_up((size_t)NN, 256);
   return 2 * per_set + chain + hs::bucket_workspace(NN, V, nullptr, nullptr) + hs::row_topk_workspace(NN, V, 1);
 }
 
@@ -839,6 +852,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     chain.child_frozen = c.take<double>(NN);
     chain.node_beta = c.take<double>(NN);
     chain.node_Z = c.take<double>(NN);
+    uint8_t* has_child = c.take<uint8_t>(NN);
     hs::bucket_workspace(NN, V, &c, &bk);
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
@@ -847,8 +861,10 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
                                       scan_ws, st, stochastic ? nullptr : &slices);
     if (r != HS_OK) return r;
     if (mode == HS_ACCEPT_STOCHASTIC) {
+      // draft rows are read where a row has children, and nowhere else
+      hipLaunchKernelGGL(hs::k_mark_parents, dim3(B), dim3(hs::GR_THREADS), 0, st, parent, node_offsets, has_child);
       r = hs::row_topk_launch(draft_logits, row_stride, NN, V, 1, T, d_arg, d_lz, d_ent, nullptr, nullptr, scan_ws,
-                              st);
+                              st, nullptr, has_child);
       if (r != HS_OK) return r;
     }
   }

@@ -277,3 +277,22 @@ def test_accept_long_rejection_chains(G, V, n_kids):
         if done >= 6 and rejected_all >= 2:
             break
     assert done >= 6 and rejected_all >= 2, (done, rejected_all)
+
+
+def test_accept_draft_rows_of_leaves_are_not_read(G):
+    """Only rows that have children carry a draft distribution: the others may hold anything."""
+    w = W.small(W.WORKLOADS[2], V=8192)
+    st = P.build_step(w, 1, with_attention=False)
+    u, want = P.safe_uniforms(st, 1)
+    D = max(1, int(P.tree_depth(st["parent"], st["node_offsets"]).max()))
+    has_child = np.zeros(len(st["parent"]), bool)
+    no = st["node_offsets"]
+    for s in range(len(no) - 1):
+        o, n = int(no[s]), int(no[s + 1] - no[s])
+        for i in range(1, n):
+            has_child[o + int(st["parent"][o + i])] = True
+    assert has_child.any() and not has_child.all()
+    st2 = dict(st)
+    st2["draft_logits"] = st["draft_logits"].copy()
+    st2["draft_logits"][~has_child] = np.nan
+    _accept_equal(G.run_accept(st2, 1, u, D), want)
