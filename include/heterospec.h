@@ -111,6 +111,16 @@ hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stride, int32_t
                                 float* ent_full, float* lse,
                                 void* workspace, size_t workspace_bytes, hs_stream stream);
 
+/* hs_draft_entropy_topk_rows: the same, with the rows picked out of a larger array: result row r
+ * (0 <= r < R) comes from logits row row_index[r] (device, int32 [R]; the rows a level-by-level
+ * expansion wants next, as hs_tree_expand lists them in frontier_rows).  A negative entry leaves
+ * the results of row r as they are.  The entries are trusted, like all device-side data. */
+hs_status hs_draft_entropy_topk_rows(const float* logits, int64_t row_stride, const int32_t* row_index,
+                                     int32_t R, int32_t V, int32_t K, float temperature,
+                                     int32_t* topk_idx, float* topk_logp, float* ent_topk,
+                                     float* ent_full, float* lse,
+                                     void* workspace, size_t workspace_bytes, hs_stream stream);
+
 /* ------------------------------------------------------------------------------------------------
  * hs_tree_prune  (Section 2.2: the value of node i is the product of the confidences on the path
  * root -> i, and the best nodes by value form the verified subtree; Section 4.3: the node budget

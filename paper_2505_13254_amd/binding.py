@@ -29,6 +29,8 @@ _SIGNATURES = {
     "hs_version": (_c.c_char_p, []),
     "hs_draft_entropy_topk_workspace": (_sz, [_i32, _i32, _i32]),
     "hs_draft_entropy_topk": (_c.c_int, [_vp, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "hs_draft_entropy_topk_rows": (_c.c_int, [_vp, _i64, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                              _vp]),
     "hs_tree_prune_workspace": (_sz, [_i32, _i32]),
     "hs_tree_prune": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "hs_tree_prune_counted": (_c.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -110,11 +112,17 @@ def workspace(nbytes: int, device) -> Optional[torch.Tensor]:
 
 def hs_draft_entropy_topk(logits: torch.Tensor, K: int, temperature: float = 1.0, *, want_full: bool = True,
                           out: Optional[Dict[str, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
-                          stream=None) -> Dict[str, torch.Tensor]:
-    """logits float32 [R, V] (row stride may exceed V).  Returns topk_idx, topk_logp, ent_topk, ent_full, lse."""
+                          row_index: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
+    """logits float32 [N, V] (row stride may exceed V).  Returns topk_idx, topk_logp, ent_topk, ent_full, lse
+    for its N rows, or, with row_index int32 [R] (GPU), for the R rows that row_index names
+    (hs_draft_entropy_topk_rows; a negative entry leaves that result row untouched)."""
     if logits.dim() != 2 or logits.dtype != torch.float32 or not logits.is_cuda or logits.stride(1) != 1:
         raise ValueError("logits must be a float32 [R, V] GPU tensor with unit inner stride")
-    R, V = logits.shape
+    N, V = logits.shape
+    R = N
+    if row_index is not None:
+        _dev(row_index, torch.int32, "row_index")
+        R = row_index.numel()
     dev = logits.device
     if out is None:
         out = dict(topk_idx=torch.empty((R, K), dtype=torch.int32, device=dev),
@@ -126,10 +134,13 @@ def hs_draft_entropy_topk(logits: torch.Tensor, K: int, temperature: float = 1.0
     need = lib().hs_draft_entropy_topk_workspace(R, V, K)
     if ws is None:
         ws = workspace(need, dev)
-    st = lib().hs_draft_entropy_topk(_ptr(logits), logits.stride(0) if R > 1 else max(V, logits.stride(0)), R, V, K,
-                                     float(temperature), _ptr(out["topk_idx"]), _ptr(out["topk_logp"]),
-                                     _ptr(out["ent_topk"]), _ptr(out.get("ent_full")), _ptr(out.get("lse")),
-                                     _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
+    stride = logits.stride(0) if N > 1 else max(V, logits.stride(0))
+    tail = (_ptr(out["topk_idx"]), _ptr(out["topk_logp"]), _ptr(out["ent_topk"]), _ptr(out.get("ent_full")),
+            _ptr(out.get("lse")), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
+    if row_index is None:
+        st = lib().hs_draft_entropy_topk(_ptr(logits), stride, R, V, K, float(temperature), *tail)
+    else:
+        st = lib().hs_draft_entropy_topk_rows(_ptr(logits), stride, _ptr(row_index), R, V, K, float(temperature), *tail)
     _check(st, "hs_draft_entropy_topk")
     return out
 

@@ -272,8 +272,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
                                                             float* __restrict__ topk_logp,
                                                             float* __restrict__ ent_topk,
                                                             float* __restrict__ ent_full, float* __restrict__ lse,
-                                                            const uint8_t* __restrict__ row_active) {
+                                                            const uint8_t* __restrict__ row_active,
+                                                            const int32_t* __restrict__ row_index) {
   if (row_active != nullptr && row_active[blockIdx.y] == 0) return;  // (the whole workgroup: a row nobody will read)
+  // (both arms as int64: mixed with the unsigned block index a negative entry would turn positive)
+  const int64_t src_row = row_index != nullptr ? (int64_t)row_index[blockIdx.y] : (int64_t)blockIdx.y;
+  if (src_row < 0) return;
   constexpr int SCAN_WAVES = SCAN_THREADS / 64;
   constexpr int SCAN_GROUPS = SCAN_WAVES * 4 < 64 ? SCAN_WAVES * 4 : 64;  // rows of 16 lanes, at most one per lane
   constexpr int SCAN_TILE = scan_tile(SCAN_THREADS);
@@ -284,7 +288,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x, S = gridDim.x, row = blockIdx.y;
-  const float* __restrict__ x = logits + (int64_t)row * row_stride;
+  const float* __restrict__ x = logits + src_row * row_stride;
 
   // this wave's K best pairs so far, best first, entry l in lane l; the rest holds a pair that
   // loses against every real one
@@ -510,11 +514,13 @@ __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __r
                                                                float* __restrict__ ent_topk,
                                                                float* __restrict__ ent_full,
                                                                float* __restrict__ lse,
-                                                               const uint8_t* __restrict__ row_active) {
+                                                               const uint8_t* __restrict__ row_active,
+                                                               const int32_t* __restrict__ row_index) {
   __shared__ MergeScratch<FIN_CAP> sm;
   const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
   if (row_active != nullptr && row_active[row] == 0) return;
+  if (row_index != nullptr && row_index[row] < 0) return;
   merge_slices(part_stats + row * S, part_val + row * S * K, part_idx + row * S * K, S, K, inv_t, sm, tid, FIN_THREADS);
   write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
 }
@@ -528,7 +534,8 @@ size_t row_topk_workspace(int R, int V, int K) {
 
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
-                          void* workspace, hipStream_t stream, ScanSlices* slices, const uint8_t* row_active) {
+                          void* workspace, hipStream_t stream, ScanSlices* slices, const uint8_t* row_active,
+                          const int32_t* row_index) {
   ScanPlan p = plan_scan(R, V);
   Carver c(workspace);
   size_t n = (size_t)R * p.splits;
@@ -540,7 +547,7 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   dim3 grid(p.splits, R);
 #define HS_SCAN_LAUNCH(VEC, T)                                                                                      \
   hipLaunchKernelGGL((k_scan_rows<VEC, T>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
-                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active)
+                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index)
   if (p.threads == SCAN_BIG) {
     if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG);
     else HS_SCAN_LAUNCH(false, SCAN_BIG);
@@ -553,7 +560,7 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   if (slices != nullptr) *slices = ScanSlices{part_val, part_idx, p.splits};
   if (st != HS_OK || p.splits == 1 || slices != nullptr) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,
-                     p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active);
+                     p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index);
   return launch_status("row scan merge");
 }
 
@@ -564,10 +571,10 @@ extern "C" size_t hs_draft_entropy_topk_workspace(int32_t R, int32_t V, int32_t 
   return hs::row_topk_workspace(R, V, K);
 }
 
-extern "C" hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stride, int32_t R, int32_t V, int32_t K,
-                                           float temperature, int32_t* topk_idx, float* topk_logp, float* ent_topk,
-                                           float* ent_full, float* lse, void* workspace, size_t workspace_bytes,
-                                           hs_stream stream) {
+static hs_status entropy_topk_impl(const float* logits, int64_t row_stride, const int32_t* row_index, int32_t R,
+                                   int32_t V, int32_t K, float temperature, int32_t* topk_idx, float* topk_logp,
+                                   float* ent_topk, float* ent_full, float* lse, void* workspace,
+                                   size_t workspace_bytes, hs_stream stream) {
   hs::clear_error();
   HS_REQUIRE(R >= 0 && V >= 1, HS_ERR_SHAPE, "hs_draft_entropy_topk: R=%d V=%d", R, V);
   HS_REQUIRE(K >= 1 && K <= V, HS_ERR_SHAPE, "hs_draft_entropy_topk: K=%d must be in 1..V=%d", K, V);
@@ -582,5 +589,23 @@ extern "C" hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stri
              HS_ERR_WORKSPACE, "hs_draft_entropy_topk: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
              workspace_bytes);
   return hs::row_topk_launch(logits, row_stride, R, V, K, temperature, topk_idx, topk_logp, ent_topk, ent_full, lse,
-                             workspace, static_cast<hipStream_t>(stream));
+                             workspace, static_cast<hipStream_t>(stream), nullptr, nullptr, row_index);
+}
+
+extern "C" hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stride, int32_t R, int32_t V, int32_t K,
+                                           float temperature, int32_t* topk_idx, float* topk_logp, float* ent_topk,
+                                           float* ent_full, float* lse, void* workspace, size_t workspace_bytes,
+                                           hs_stream stream) {
+  return entropy_topk_impl(logits, row_stride, nullptr, R, V, K, temperature, topk_idx, topk_logp, ent_topk, ent_full,
+                           lse, workspace, workspace_bytes, stream);
+}
+
+extern "C" hs_status hs_draft_entropy_topk_rows(const float* logits, int64_t row_stride, const int32_t* row_index,
+                                                int32_t R, int32_t V, int32_t K, float temperature,
+                                                int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full,
+                                                float* lse, void* workspace, size_t workspace_bytes,
+                                                hs_stream stream) {
+  HS_REQUIRE(R <= 0 || row_index != nullptr, HS_ERR_NULL, "hs_draft_entropy_topk_rows: row_index is NULL");
+  return entropy_topk_impl(logits, row_stride, row_index, R, V, K, temperature, topk_idx, topk_logp, ent_topk,
+                           ent_full, lse, workspace, workspace_bytes, stream);
 }

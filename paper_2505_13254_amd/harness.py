@@ -317,13 +317,13 @@ class AdaptiveStep:
     # ---- pieces, each a few library calls on device-resident data
     def _level(self, first: bool):
         t, w, h = self.t, self.w, self.host
+        # The draft model's pass over the frontier is not part of this build: its logits rows exist for
+        # all candidates beforehand, and the scan reads the frontier's rows where they lie.
         if first:
-            x = t["x_root"]
+            r = hs.hs_draft_entropy_topk(t["x_root"], w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"])
         else:
-            # stands in for the draft model's pass over the frontier: its logits rows are gathered
-            # from the pre-generated rows of all candidates
-            x = torch.index_select(t["draft_all"], 0, t["state"]["frontier_rows"], out=t["x_slots"])
-        r = hs.hs_draft_entropy_topk(x, w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"])
+            r = hs.hs_draft_entropy_topk(t["draft_all"], w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"],
+                                         row_index=t["state"]["frontier_rows"])
         hs.hs_tree_expand(t["state"], r["topk_idx"], r["topk_logp"], r["ent_topk"], None, 1, h["cap"], w.frontier,
                           w.topk, first=first)
 
@@ -429,7 +429,6 @@ def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, e
         t["draft_all"][i0:i0 + len(ids)] = _dev(W.logits_rows(w, seed, "draft", 0, ids), device=device)
         t["target_all"][i0:i0 + len(ids)] = _dev(W.logits_rows(w, seed, "target", 0, ids), device=device)
     t["x_root"] = t["draft_all"][:1].repeat(F, 1).contiguous()
-    t["x_slots"] = torch.empty((F, w.V), dtype=torch.float32, device=device)
     t["s1_out"] = dict(topk_idx=torch.empty((F, K), **i32),
                        topk_logp=torch.empty((F, K), dtype=torch.float32, device=device),
                        ent_topk=torch.empty(F, dtype=torch.float32, device=device))

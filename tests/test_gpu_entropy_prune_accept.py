@@ -296,3 +296,31 @@ def test_accept_draft_rows_of_leaves_are_not_read(G):
     st2["draft_logits"] = st["draft_logits"].copy()
     st2["draft_logits"][~has_child] = np.nan
     _accept_equal(G.run_accept(st2, 1, u, D), want)
+
+
+def test_entropy_rows_picked_by_index(G):
+    """hs_draft_entropy_topk_rows: result rows come from the rows an index list names (repeats
+    allowed); a negative entry leaves its result row untouched."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(77)
+    N, V, K = 40, 6000, 10
+    x = (rs.normal(size=(N, V)) * 3).astype(np.float32)
+    pick = np.asarray([7, 0, 39, 7, -1, 12, 39, 3, -5, 21, 1], np.int32)
+    R = len(pick)
+    out = dict(topk_idx=torch.full((R, K), -7, dtype=torch.int32, device="cuda:0"),
+               topk_logp=torch.full((R, K), 5.0, dtype=torch.float32, device="cuda:0"),
+               ent_topk=torch.full((R,), 5.0, dtype=torch.float32, device="cuda:0"),
+               ent_full=torch.full((R,), 5.0, dtype=torch.float32, device="cuda:0"),
+               lse=torch.full((R,), 5.0, dtype=torch.float32, device="cuda:0"))
+    hs.hs_draft_entropy_topk(G.dev(x), K, 0.8, out=out, row_index=G.dev(pick))
+    got = {k: G.host(v) for k, v in out.items()}
+    live = pick >= 0
+    want = draft_entropy_topk(x[pick[live]], K, 0.8)
+    assert np.array_equal(got["topk_idx"][live], want["topk_idx"])
+    assert G.entropy_err(got["ent_topk"][live], want["ent_topk"]) <= 1.0
+    assert G.entropy_err(got["ent_full"][live], want["ent_full"]) <= 1.0
+    assert np.all(np.abs(got["topk_logp"][live] - want["topk_logp"]) <= 2e-5 * np.abs(want["topk_logp"]) + 1e-6)
+    assert np.all(got["topk_idx"][~live] == -7) and np.all(got["ent_topk"][~live] == 5.0)   # untouched
+    # one picked row by itself (few rows: the short-slice plan)
+    one = hs.hs_draft_entropy_topk(G.dev(x), K, 0.8, row_index=G.dev(np.asarray([33], np.int32)))
+    assert np.array_equal(G.host(one["topk_idx"]), draft_entropy_topk(x[33:34], K, 0.8)["topk_idx"])
