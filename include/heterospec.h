@@ -230,13 +230,15 @@ hs_status hs_tree_attention_paged(const void* q, const void* k_pages, const void
  * Outputs: accept_len [B] (number of accepted rows), accept_path [B,max_depth] local row indices
  *   padded with -1, bonus_token [B] (-1 for an empty sequence).  The walk stops after max_depth
  *   accepted rows.
- * Workspace: the query does not know the mode, so it always covers the stochastic one: besides a
- *   few arrays of NN entries, a pair of floats per row and vocabulary entry plus 80 KiB of bucket
- *   tables per row (about 8 * NN * V bytes; left out for NN > 4096, where every rejection
- *   re-reads the two rows instead).  Rows whose address is a multiple of 16 bytes (base and
- *   row_stride * 4) take the faster paths.
+ * Workspace: hs_verify_accept_workspace_mode gives what a call in `mode` needs; the query without
+ *   a mode gives the largest of the three, that of HS_ACCEPT_STOCHASTIC: besides a few arrays of
+ *   NN entries, a pair of floats per row and vocabulary entry plus 80 KiB of bucket tables per
+ *   row (about 8 * NN * V bytes; left out for NN > 4096, where every rejection re-reads the two
+ *   rows instead).  Rows whose address is a multiple of 16 bytes (base and row_stride * 4) take
+ *   the faster paths.
  */
 size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V);
+size_t hs_verify_accept_workspace_mode(int32_t B, int32_t NN, int32_t V, hs_accept_mode mode);
 hs_status hs_verify_accept(const float* target_logits, const float* draft_logits,
                            int64_t row_stride, const int32_t* token, const int32_t* parent,
                            const int32_t* node_offsets,

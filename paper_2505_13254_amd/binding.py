@@ -51,6 +51,7 @@ _SIGNATURES = {
     "hs_tree_validate": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "hs_time_next_attention": (_c.c_int, [_vp, _vp]),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
+    "hs_verify_accept_workspace_mode": (_sz, [_i32, _i32, _i32, _c.c_int]),
     "hs_verify_accept": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _f32, _vp, _i32,
                                     _vp, _vp, _vp, _vp, _sz, _vp]),
 }
@@ -398,7 +399,7 @@ def hs_verify_accept(target_logits, draft_logits, token, parent, node_offsets, m
         out = dict(accept_len=torch.empty(B, dtype=torch.int32, device=dev),
                    accept_path=torch.empty((B, max_depth), dtype=torch.int32, device=dev),
                    bonus_token=torch.empty(B, dtype=torch.int32, device=dev))
-    need = lib().hs_verify_accept_workspace(B, NN, V)
+    need = lib().hs_verify_accept_workspace_mode(B, NN, V, int(mode))
     if ws is None:
         ws = workspace(need, dev)
     st = lib().hs_verify_accept(_ptr(target_logits), _ptr(draft_logits), row_stride, _ptr(token), _ptr(parent),

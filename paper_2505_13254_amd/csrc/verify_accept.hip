@@ -794,13 +794,19 @@ static size_t bucket_workspace(int NN, int V, Carver* c, BucketWs* ws) {
 
 }  // namespace hs
 
-extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
+extern "C" size_t hs_verify_accept_workspace_mode(int32_t B, int32_t NN, int32_t V, hs_accept_mode mode) {
   if (B <= 0 || NN <= 0 || V <= 0) return 0;
   // per row: argmax, -ln Z and an unused Top-1 entropy, for the target and for the draft rows
   const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
-  // five doubles per row: what the rejection chains hand to the walk
+  // five doubles per row: what the rejection chains hand to the walk; a byte per row: has children
   const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256) + hs::align_up((size_t)NN, 256);
-  return 2 * per_set + chain + hs::bucket_workspace(NN, V, nullptr, nullptr) + hs::row_topk_workspace(NN, V, 1);
+  // the sorted residual belongs to the ratio rule alone
+  const size_t sorted = mode == HS_ACCEPT_STOCHASTIC ? hs::bucket_workspace(NN, V, nullptr, nullptr) : 0;
+  return 2 * per_set + chain + sorted + hs::row_topk_workspace(NN, V, 1);
+}
+
+extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
+  return hs_verify_accept_workspace_mode(B, NN, V, HS_ACCEPT_STOCHASTIC);  // the largest of the three
 }
 
 extern "C" hs_status hs_verify_accept(const float* target_logits, const float* draft_logits, int64_t row_stride,
@@ -830,7 +836,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
                  "hs_verify_accept: stochastic modes support V <= %d", hs::AC_MAX_ROWS * 64);
     }
   }
-  const size_t need = hs_verify_accept_workspace(B, NN, V);
+  const size_t need = hs_verify_accept_workspace_mode(B, NN, V, mode);
   HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
              HS_ERR_WORKSPACE, "hs_verify_accept: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
              workspace_bytes);
@@ -853,7 +859,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     chain.node_beta = c.take<double>(NN);
     chain.node_Z = c.take<double>(NN);
     uint8_t* has_child = c.take<uint8_t>(NN);
-    hs::bucket_workspace(NN, V, &c, &bk);
+    if (mode == HS_ACCEPT_STOCHASTIC) hs::bucket_workspace(NN, V, &c, &bk);
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
     // greedy: the merge of the row slices is done by the accept kernel (one launch less)

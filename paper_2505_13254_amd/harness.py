@@ -258,7 +258,7 @@ def build_step(w: W.Workload, seed: int = 0, layers: Optional[int] = None, accep
     t["s4_out"] = dict(accept_len=torch.empty(B, dtype=torch.int32, device=device),
                        accept_path=torch.empty((B, h["max_depth"]), dtype=torch.int32, device=device),
                        bonus_token=torch.empty(B, dtype=torch.int32, device=device))
-    t["s4_ws"] = hs.workspace(hs.lib().hs_verify_accept_workspace(B, NNp, w.V), device)
+    t["s4_ws"] = hs.workspace(hs.lib().hs_verify_accept_workspace_mode(B, NNp, w.V, accept_mode), device)
     # stage 3 inputs
     L = W.prefix_lengths(w, seed)
     if layers > 1:
@@ -471,7 +471,7 @@ def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, e
                                                                    dt), device)
         a["s4_out"] = dict(accept_len=torch.empty(1, **i32), bonus_token=torch.empty(1, **i32),
                            accept_path=torch.empty((1, d_base + alpha), **i32))
-        a["s4_ws"] = hs.workspace(hs.lib().hs_verify_accept_workspace(1, M, w.V), device)
+        a["s4_ws"] = hs.workspace(hs.lib().hs_verify_accept_workspace_mode(1, M, w.V, 0), device)
         t["attn"][M] = a
     h["sizes"] = sizes
     return st

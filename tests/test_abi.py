@@ -94,3 +94,25 @@ def test_argument_validation_needs_no_gpu(lib):
                   [ctypes.c_size_t, ctypes.c_void_p]
     assert va(None, None, 10, None, None, None, 1, 4, 10, 0, 1.0, None, 0, None, None, None, None, 0, None) == 2  # max_depth
     assert va(None, None, 10, None, None, None, 1, 4, 10, 7, 1.0, None, 3, None, None, None, None, 0, None) == 2  # mode
+
+
+def test_accept_workspace_depends_on_the_mode(lib):
+    q = lib.hs_verify_accept_workspace
+    q.restype, q.argtypes = ctypes.c_size_t, [ctypes.c_int32] * 3
+    qm = lib.hs_verify_accept_workspace_mode
+    qm.restype, qm.argtypes = ctypes.c_size_t, [ctypes.c_int32] * 3 + [ctypes.c_int]
+    greedy, ratio, point = (qm(1, 61, 128256, m) for m in (0, 1, 2))
+    assert greedy == point < ratio == q(1, 61, 128256)
+    assert ratio - greedy >= 61 * 128256 * 8                  # a pair of floats per row and token
+    assert greedy < 64 * 1024 * 1024 and greedy % 256 == 0 and ratio % 256 == 0
+    assert qm(1, 5000, 128256, 1) == qm(1, 5000, 128256, 0)   # too many rows for the sorted residual
+    # a workspace of the greedy size is refused by the ratio rule and the other way round it is fine;
+    # both are decided on the host
+    va = lib.hs_verify_accept
+    va.restype = ctypes.c_int
+    va.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int64] + [ctypes.c_void_p] * 3 + [ctypes.c_int32] * 3 + \
+                  [ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_int32] + [ctypes.c_void_p] * 4 + \
+                  [ctypes.c_size_t, ctypes.c_void_p]
+    d = ctypes.c_void_p(256)
+    assert va(d, d, 128256, d, d, d, 1, 61, 128256, 1, 1.0, d, 6, d, d, d, d, greedy, None) == 4
+    assert va(d, d, 128256, d, d, d, 1, 61, 128256, 0, 1.0, d, 6, d, d, d, d, greedy - 256, None) == 4
