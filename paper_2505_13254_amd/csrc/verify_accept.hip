@@ -146,6 +146,20 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
+// Sum over each row of 16 lanes; the row's last lane holds it.  DPP moves of the two halves of the
+// double: a lane without a source takes 0.
+__device__ __forceinline__ double row16_sum(double x) {
+#define HS_DPP_ADD(ctrl, banks)                                                                              \
+  x += __hiloint2double(__builtin_amdgcn_update_dpp(0, __double2hiint(x), ctrl, 0xf, banks, false),          \
+                        __builtin_amdgcn_update_dpp(0, __double2loint(x), ctrl, 0xf, banks, false))
+  HS_DPP_ADD(0x111, 0xf);  // row_shr:1
+  HS_DPP_ADD(0x112, 0xf);  // row_shr:2
+  HS_DPP_ADD(0x114, 0xe);  // row_shr:4
+  HS_DPP_ADD(0x118, 0xc);  // row_shr:8
+#undef HS_DPP_ADD
+  return x;
+}
+
 __device__ __forceinline__ double wave_incl_scan(double v, int lane) {
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -691,27 +705,39 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
     const double goal = (double)uniforms[NN + s] * total;
     const int n_rows = (V + 63) / 64;
     int first_row = 0;  // rows below it were summed with 16-byte loads
-    if (p.aligned16() && (!sub_q || q.aligned16())) {
-      // a lane takes four tokens, 16 lanes a row of 64, a wave four rows per trip
+    if (p.aligned16() && (!sub_q || q.aligned16()) && V >= 64) {
+      // a lane takes four tokens, 16 lanes a row of 64, a wave four rows per trip; the loads of four
+      // trips are requested together (lanes past the last row re-read it), and a row's 16 partial
+      // sums meet in its last lane by DPP moves (no trip through LDS)
+      constexpr int TRIPS = 4;
       const int full_rows = V >> 6;
       const int sub = lane >> 4, l16 = lane & 15;
       const float bf = (float)beta;
-      for (int r0 = wave * 4; r0 < full_rows; r0 += AC_WAVES * 4) {
-        const int r = r0 + sub;
-        double w = 0.0;
-        if (r < full_rows) {
-          const float4 pp = p.prob4(r * 16 + l16);
+      const float4* __restrict__ px = reinterpret_cast<const float4*>(p.x);
+      const float4* __restrict__ qx = reinterpret_cast<const float4*>(q.x);
+      for (int r0 = wave * 4; r0 < full_rows; r0 += AC_WAVES * 4 * TRIPS) {
+        float4 fp[TRIPS], fq[TRIPS];
+#pragma unroll
+        for (int u = 0; u < TRIPS; ++u) {
+          const int r = min(r0 + u * AC_WAVES * 4 + sub, full_rows - 1);
+          fp[u] = px[r * 16 + l16];
+          fq[u] = sub_q ? qx[r * 16 + l16] : fp[u];
+        }
+#pragma unroll
+        for (int u = 0; u < TRIPS; ++u) {
+          const int r = r0 + u * AC_WAVES * 4 + sub;
+          const float4 pp = p.of4(fp[u]);
+          double w;
           if (sub_q) {
-            const float4 qq = q.prob4(r * 16 + l16);
+            const float4 qq = q.of4(fq[u]);
             w = ((double)fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) + (double)fmaxf(fmaf(-bf, qq.y, pp.y), 0.f)) +
                 ((double)fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) + (double)fmaxf(fmaf(-bf, qq.w, pp.w), 0.f));
           } else {
             w = ((double)pp.x + (double)pp.y) + ((double)pp.z + (double)pp.w);
           }
+          w = row16_sum(w);
+          if (l16 == 15 && r < full_rows) rowsum[r] = w;
         }
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) w += __shfl_xor(w, off);
-        if (l16 == 0 && r < full_rows) rowsum[r] = w;
       }
       first_row = full_rows;
     }
