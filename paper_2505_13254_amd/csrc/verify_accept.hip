@@ -622,6 +622,8 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
   __shared__ float kid_u[AC_MAX_KIDS];    // the child's uniform
   __shared__ double kid_a[AC_MAX_KIDS], kid_b[AC_MAX_KIDS];  // its current p(x) (and q(x) under the ratio rule)
   __shared__ double rowsum[AC_MAX_ROWS];
+  __shared__ double chunk_tot[AC_MAX_ROWS / 64];  // sums of 64 rows
+  __shared__ int chunk_last[AC_MAX_ROWS / 64];
 
   const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int o = node_offsets[s];
@@ -753,23 +755,52 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
         rowsum[rej_tok[i] >> 6] += rej_w[i] - token_weight(p, q, sub_q, beta, rej_tok[i]);
     }
     __syncthreads();
+    // two levels: the sixteen waves sum chunks of 64 rows side by side, one wave then looks for the
+    // chunk, the row inside it and the token inside the row
+    const int n_chunks = (n_rows + 63) >> 6;
+    for (int c = wave; c < n_chunks; c += AC_WAVES) {
+      const int r = c * 64 + lane;
+      const double val = r < n_rows ? rowsum[r] : 0.0;
+      const double tot = wave_sum(val);
+      const unsigned long long pos = __ballot(r < n_rows && val > 0.0);
+      if (lane == 0) {
+        chunk_tot[c] = tot;
+        chunk_last[c] = pos != 0ull ? c * 64 + 63 - __clzll((long long)pos) : -1;  // its last row with mass
+      }
+    }
+    __syncthreads();
     if (wave == 0) {
-      double carry = 0.0;
-      int row = -1, last_pos = -1;
-      double excl = 0.0;
-      for (int base = 0; base < n_rows && row < 0; base += 64) {
-        const int r = base + lane;
-        const double val = r < n_rows ? rowsum[r] : 0.0;
+      double carry = 0.0, chunk_excl = 0.0;
+      int chunk = -1, last_pos = -1;
+      for (int cb = 0; cb < n_chunks && chunk < 0; cb += 64) {
+        const int c = cb + lane;
+        const double val = c < n_chunks ? chunk_tot[c] : 0.0;
+        const int lp = c < n_chunks ? chunk_last[c] : -1;
         const double incl = wave_incl_scan(val, lane) + carry;
-        const unsigned long long hit = __ballot(r < n_rows && incl > goal);
-        const unsigned long long pos = __ballot(r < n_rows && val > 0.0);
+        const unsigned long long hit = __ballot(c < n_chunks && incl > goal);
         if (hit != 0ull) {
           const int l = __ffsll((long long)hit) - 1;
-          row = base + l;
+          chunk = cb + l;
+          chunk_excl = __shfl(incl - val, l);
+        } else {
+          const unsigned long long pos = __ballot(lp >= 0);
+          if (pos != 0ull) last_pos = __shfl(lp, 63 - __clzll((long long)pos));
+          carry = __shfl(incl, 63);
+        }
+      }
+      int row = -1;
+      double excl = 0.0;
+      if (chunk >= 0) {
+        const int r = chunk * 64 + lane;
+        const double val = r < n_rows ? rowsum[r] : 0.0;
+        const double incl = wave_incl_scan(val, lane) + chunk_excl;
+        const unsigned long long hit = __ballot(r < n_rows && incl > goal);
+        if (hit != 0ull) {
+          const int l = __ffsll((long long)hit) - 1;
+          row = chunk * 64 + l;
           excl = __shfl(incl - val, l);
         } else {
-          if (pos != 0ull) last_pos = base + 63 - __clzll((long long)pos);
-          carry = __shfl(incl, 63);
+          last_pos = chunk_last[chunk];  // (the two orders of summation differ by a rounding: the chunk's last row with mass)
         }
       }
       double row_goal = goal - excl;
