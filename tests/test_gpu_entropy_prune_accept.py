@@ -243,8 +243,9 @@ def test_accept_stochastic_is_deterministic(G):
         _accept_equal(G.run_accept(st, 1, u, D), first)
 
 
-@pytest.mark.parametrize("V,n_kids", [(16384, 14), (40000, 9), (6000, 24)])
-def test_accept_long_rejection_chains(G, V, n_kids):
+@pytest.mark.parametrize("V,n_kids,T", [(16384, 14, 1.0), (40000, 9, 1.0), (6000, 24, 1.0), (12288, 12, 0.7),
+                                        (9000, 10, 1.6)])
+def test_accept_long_rejection_chains(G, V, n_kids, T):
     """A root whose many children are (nearly) all rejected, so that the bonus token depends on every
     pass of the root's chain: the list of live tokens is built, compacted in memory, and ends in LDS."""
     import paper_2505_13254_amd as hs
@@ -259,18 +260,18 @@ def test_accept_long_rejection_chains(G, V, n_kids):
         offs = np.asarray([0, 1 + n_kids], np.int32)
         u = np.concatenate([0.9 + 0.0999 * rs.rand(1 + n_kids), rs.rand(1)]).astype(np.float32)
         from oracle import verify_accept
-        base = verify_accept(target, draft, token, parent, offs, 1, 1.0, u, 1)
+        base = verify_accept(target, draft, token, parent, offs, 1, T, u, 1)
         ok = True
         for sgn in (-1.0, 1.0):
             un = u.astype(np.float64).copy()
             un[:1 + n_kids] *= 1.0 + sgn * 1e-4
             un[1 + n_kids:] = np.clip(un[1 + n_kids:] + sgn * 1e-5, 0.0, 1.0 - 1e-12)
-            alt = verify_accept(target, draft, token, parent, offs, 1, 1.0, un, 1)
+            alt = verify_accept(target, draft, token, parent, offs, 1, T, un, 1)
             ok = ok and all(np.array_equal(alt[k], base[k]) for k in base)
         if not ok:
             continue
         out = hs.hs_verify_accept(G.dev(target), G.dev(draft), G.dev(token, torch.int32), G.dev(parent, torch.int32),
-                                  G.dev(offs, torch.int32), 1, 1.0, G.dev(u, torch.float32), 1)
+                                  G.dev(offs, torch.int32), 1, T, G.dev(u, torch.float32), 1)
         _accept_equal({k: G.host(v) for k, v in out.items()}, base)
         done += 1
         rejected_all += int(base["accept_len"][0] == 0)
