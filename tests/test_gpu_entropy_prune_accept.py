@@ -325,3 +325,58 @@ def test_entropy_rows_picked_by_index(G):
     # one picked row by itself (few rows: the short-slice plan)
     one = hs.hs_draft_entropy_topk(G.dev(x), K, 0.8, row_index=G.dev(np.asarray([33], np.int32)))
     assert np.array_equal(G.host(one["topk_idx"]), draft_entropy_topk(x[33:34], K, 0.8)["topk_idx"])
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_accept_random_trees(G, seed):
+    """Forty random cases per seed: both sampling rules, 1 to 3 sequences of up to 25 rows, vocabularies
+    on both sides of the sorted residual's conditions (size, alignment), three temperatures, walks cut
+    by max_depth; uniforms with a margin to every decision."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(seed)
+    done, lens = 0, []
+    for attempt in range(200):
+        mode = int(rs.choice([1, 1, 2]))
+        V = int(rs.choice([4096, 4100, 5000, 8192, 12290, 20000]))
+        B = int(rs.randint(1, 4))
+        T = float(rs.choice([0.7, 1.0, 1.3]))
+        sizes = [int(rs.randint(1, 26)) for _ in range(B)]
+        NN = sum(sizes)
+        draft = (rs.normal(size=(NN, V)) * 2.5).astype(np.float32)
+        corr = rs.choice([0.5, 0.8, 0.95])
+        target = (corr * draft + rs.normal(size=draft.shape) * (1.5 * (1 - corr) + 0.3)).astype(np.float32)
+        parent, token, offs, o = np.zeros(NN, np.int32), np.zeros(NN, np.int32), [0], 0
+        for n in sizes:
+            parent[o] = -1
+            kids = {}
+            for i in range(1, n):
+                p = int(rs.randint(max(0, i - 5), i))
+                parent[o + i] = p
+                kids.setdefault(p, []).append(i)
+            for p, ks in kids.items():       # siblings carry the draft's best tokens, distinct
+                for c, tk in zip(ks, np.argsort(-draft[o + p], kind="stable")[:len(ks)]):
+                    token[o + c] = tk
+            o += n
+            offs.append(o)
+        offs = np.asarray(offs, np.int32)
+        u = np.concatenate([0.3 + 0.6999 * rs.rand(NN), rs.rand(B)]).astype(np.float32)
+        D = int(rs.randint(1, 7))
+        base = verify_accept(target, draft, token, parent, offs, mode, T, u, D)
+        safe = True
+        for sgn in (-1.0, 1.0):
+            un = u.astype(np.float64).copy()
+            un[:NN] *= 1.0 + sgn * 1e-4
+            un[NN:] = np.clip(un[NN:] + sgn * 1e-5, 0.0, 1.0 - 1e-12)
+            alt = verify_accept(target, draft, token, parent, offs, mode, T, un, D)
+            safe = safe and all(np.array_equal(alt[k], base[k]) for k in base)
+        if not safe:
+            continue
+        out = hs.hs_verify_accept(G.dev(target), G.dev(draft) if mode == 1 else None, G.dev(token, torch.int32),
+                                  G.dev(parent, torch.int32), G.dev(offs, torch.int32), mode, T,
+                                  G.dev(u, torch.float32), D)
+        _accept_equal({k: G.host(v) for k, v in out.items()}, base)
+        lens += list(base["accept_len"])
+        done += 1
+        if done == 40:
+            break
+    assert done == 40 and max(lens) >= 2

@@ -63,7 +63,7 @@ def _check_step(st, rs, n_rows=6, n_heads=3, accept_mode=0):
                                _np(t["v_tree"][n0:n1, g:g + 1]), parent[n0:n1], [0, n1 - n0], [0, p1 - p0], h["scale"])
         err = np.abs(o[n0:n1, hq] - wo[:, 0]).max()
         assert err <= (2e-2 if w.dtype == "bf16" else 1e-4), (b, hq, err)
-        assert err <= 6e-3 * np.abs(wo).max() + 1e-6, (b, hq, err, np.abs(wo).max())
+        assert err <= 1e-2 * np.abs(wo).max() + 1e-6, (b, hq, err, np.abs(wo).max())
     # ---- stage 4, whole walk (argmax rows are cheap; the stochastic modes read only visited rows)
     tl = _np(t["target_logits"])
     # (the point-mass rule never uses the draft rows; the checker still wants an array there)
