@@ -273,7 +273,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
                                                             float* __restrict__ ent_topk,
                                                             float* __restrict__ ent_full, float* __restrict__ lse,
                                                             const uint8_t* __restrict__ row_active,
-                                                            const int32_t* __restrict__ row_index) {
+                                                            const int32_t* __restrict__ row_index,
+                                                            const float* __restrict__ logits2, int rows1) {
   if (row_active != nullptr && row_active[blockIdx.y] == 0) return;  // (the whole workgroup: a row nobody will read)
   // (both arms as int64: mixed with the unsigned block index a negative entry would turn positive)
   const int64_t src_row = row_index != nullptr ? (int64_t)row_index[blockIdx.y] : (int64_t)blockIdx.y;
@@ -288,7 +289,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x, S = gridDim.x, row = blockIdx.y;
-  const float* __restrict__ x = logits + src_row * row_stride;
+  // (rows from rows1 on may lie in a second array)
+  const float* __restrict__ x = (logits2 != nullptr && src_row >= rows1) ? logits2 + (src_row - rows1) * row_stride
+                                                                         : logits + src_row * row_stride;
 
   // this wave's K best pairs so far, best first, entry l in lane l; the rest holds a pair that
   // loses against every real one
@@ -535,7 +538,7 @@ size_t row_topk_workspace(int R, int V, int K) {
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
                           void* workspace, hipStream_t stream, ScanSlices* slices, const uint8_t* row_active,
-                          const int32_t* row_index) {
+                          const int32_t* row_index, const float* logits2, int rows1) {
   ScanPlan p = plan_scan(R, V);
   Carver c(workspace);
   size_t n = (size_t)R * p.splits;
@@ -543,11 +546,12 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   float* part_val = c.take<float>(n * K);
   int* part_idx = c.take<int>(n * K);
   const float inv_t = 1.0f / temperature;
-  const bool vec = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 4 == 0);
+  const bool vec = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 4 == 0) &&
+                   (reinterpret_cast<uintptr_t>(logits2) % 16 == 0);
   dim3 grid(p.splits, R);
 #define HS_SCAN_LAUNCH(VEC, T)                                                                                      \
   hipLaunchKernelGGL((k_scan_rows<VEC, T>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
-                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index)
+                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index, logits2, rows1)
   if (p.threads == SCAN_BIG) {
     if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG);
     else HS_SCAN_LAUNCH(false, SCAN_BIG);

@@ -467,15 +467,20 @@ __device__ __forceinline__ void near_terms(const float2* __restrict__ pairs, Buc
   if ((tid & 63) == 0) step.part[tid >> 6] = acc;
 }
 
-// One workgroup per sequence: has_child[row] = 1 for the rows that are somebody's parent, 0 for
-// the others (whose draft rows nobody reads).
+// One workgroup per sequence: the rows the scan of [target rows ; draft rows] has to read: every
+// target row (wanted[row] = 1) and the draft rows of the rows that are somebody's parent
+// (has_child = wanted + NN; nobody reads the draft row of a row without children).
 __global__ __launch_bounds__(GR_THREADS) void k_mark_parents(const int32_t* __restrict__ parent,
-                                                             const int32_t* __restrict__ node_offsets,
-                                                             uint8_t* __restrict__ has_child) {
+                                                             const int32_t* __restrict__ node_offsets, int NN,
+                                                             uint8_t* __restrict__ wanted) {
   const int s = blockIdx.x, tid = threadIdx.x;
   const int o = node_offsets[s];
   const int n = node_offsets[s + 1] - o;
-  for (int i = tid; i < n; i += GR_THREADS) has_child[o + i] = 0;
+  uint8_t* __restrict__ has_child = wanted + NN;
+  for (int i = tid; i < n; i += GR_THREADS) {
+    wanted[o + i] = 1;
+    has_child[o + i] = 0;
+  }
   __syncthreads();
   for (int i = 1 + tid; i < n; i += GR_THREADS) has_child[o + parent[o + i]] = 1;
 }
@@ -853,13 +858,16 @@ static size_t bucket_workspace(int NN, int V, Carver* c, BucketWs* ws) {
 
 extern "C" size_t hs_verify_accept_workspace_mode(int32_t B, int32_t NN, int32_t V, hs_accept_mode mode) {
   if (B <= 0 || NN <= 0 || V <= 0) return 0;
-  // per row: argmax, -ln Z and an unused Top-1 entropy, for the target and for the draft rows
-  const size_t per_set = 3 * hs::align_up((size_t)NN * sizeof(float), 256);
-  // five doubles per row: what the rejection chains hand to the walk; a byte per row: has children
-  const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256) + hs::align_up((size_t)NN, 256);
-  // the sorted residual belongs to the ratio rule alone
-  const size_t sorted = mode == HS_ACCEPT_STOCHASTIC ? hs::bucket_workspace(NN, V, nullptr, nullptr) : 0;
-  return 2 * per_set + chain + sorted + hs::row_topk_workspace(NN, V, 1);
+  // per row: argmax, -ln Z and an unused Top-1 entropy, for the target and for the draft rows (the
+  // two sets back to back: the ratio rule scans [target rows ; draft rows] in one launch)
+  const size_t sets = 3 * hs::align_up((size_t)2 * NN * sizeof(float), 256);
+  // five doubles per row: what the rejection chains hand to the walk; two bytes per row: rows to scan
+  const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256) + hs::align_up((size_t)2 * NN, 256);
+  // the sorted residual belongs to the ratio rule alone, and so does the scan of twice the rows
+  const bool ratio = mode == HS_ACCEPT_STOCHASTIC;
+  const size_t sorted = ratio ? hs::bucket_workspace(NN, V, nullptr, nullptr) : 0;
+  const size_t scan1 = hs::row_topk_workspace(NN, V, 1), scan2 = ratio ? hs::row_topk_workspace(2 * NN, V, 1) : 0;
+  return sets + chain + sorted + (scan1 > scan2 ? scan1 : scan2);
 }
 
 extern "C" size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V) {
@@ -904,32 +912,33 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   hs::BucketWs bk{};  // (all NULL: no sorted residual)
   if (NN > 0) {
     hs::Carver c(workspace);
-    t_arg = c.take<int32_t>(NN);
-    t_lz = c.take<float>(NN);
-    float* t_ent = c.take<float>(NN);
-    d_arg = c.take<int32_t>(NN);
-    d_lz = c.take<float>(NN);
-    float* d_ent = c.take<float>(NN);
+    t_arg = c.take<int32_t>(2 * (size_t)NN);
+    t_lz = c.take<float>(2 * (size_t)NN);
+    float* t_ent = c.take<float>(2 * (size_t)NN);
+    d_arg = t_arg + NN;  // (the draft rows' results follow the target rows')
+    d_lz = t_lz + NN;
     chain.child_p = c.take<double>(NN);
     chain.child_q = c.take<double>(NN);
     chain.child_frozen = c.take<double>(NN);
     chain.node_beta = c.take<double>(NN);
     chain.node_Z = c.take<double>(NN);
-    uint8_t* has_child = c.take<uint8_t>(NN);
+    uint8_t* wanted = c.take<uint8_t>(2 * (size_t)NN);
     if (mode == HS_ACCEPT_STOCHASTIC) hs::bucket_workspace(NN, V, &c, &bk);
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
-    // greedy: the merge of the row slices is done by the accept kernel (one launch less)
-    hs_status r = hs::row_topk_launch(target_logits, row_stride, NN, V, 1, T, t_arg, t_lz, t_ent, nullptr, nullptr,
-                                      scan_ws, st, stochastic ? nullptr : &slices);
-    if (r != HS_OK) return r;
+    hs_status r;
     if (mode == HS_ACCEPT_STOCHASTIC) {
-      // draft rows are read where a row has children, and nowhere else
-      hipLaunchKernelGGL(hs::k_mark_parents, dim3(B), dim3(hs::GR_THREADS), 0, st, parent, node_offsets, has_child);
-      r = hs::row_topk_launch(draft_logits, row_stride, NN, V, 1, T, d_arg, d_lz, d_ent, nullptr, nullptr, scan_ws,
-                              st, nullptr, has_child);
-      if (r != HS_OK) return r;
+      // one scan over [target rows ; draft rows]; draft rows are read where a row has children, and
+      // nowhere else
+      hipLaunchKernelGGL(hs::k_mark_parents, dim3(B), dim3(hs::GR_THREADS), 0, st, parent, node_offsets, NN, wanted);
+      r = hs::row_topk_launch(target_logits, row_stride, 2 * NN, V, 1, T, t_arg, t_lz, t_ent, nullptr, nullptr,
+                              scan_ws, st, nullptr, wanted, nullptr, draft_logits, NN);
+    } else {
+      // greedy: the merge of the row slices is done by the accept kernel (one launch less)
+      r = hs::row_topk_launch(target_logits, row_stride, NN, V, 1, T, t_arg, t_lz, t_ent, nullptr, nullptr, scan_ws,
+                              st, stochastic ? nullptr : &slices);
     }
+    if (r != HS_OK) return r;
   }
   if (!stochastic) {
     hipLaunchKernelGGL(hs::k_accept_greedy, dim3(B), dim3(hs::GR_THREADS), 0, st, t_arg, slices.val, slices.idx,

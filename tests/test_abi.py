@@ -105,7 +105,7 @@ def test_accept_workspace_depends_on_the_mode(lib):
     assert greedy == point < ratio == q(1, 61, 128256)
     assert ratio - greedy >= 61 * 128256 * 8                  # a pair of floats per row and token
     assert greedy < 64 * 1024 * 1024 and greedy % 256 == 0 and ratio % 256 == 0
-    assert qm(1, 5000, 128256, 1) == qm(1, 5000, 128256, 0)   # too many rows for the sorted residual
+    assert qm(1, 5000, 128256, 1) - qm(1, 5000, 128256, 0) < 1 << 20   # too many rows for the sorted residual
     # a workspace of the greedy size is refused by the ratio rule and the other way round it is fine;
     # both are decided on the host
     va = lib.hs_verify_accept
