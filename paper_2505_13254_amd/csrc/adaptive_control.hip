@@ -94,13 +94,21 @@ __device__ __forceinline__ void control_sequence(const ControlArgs& a, int s, in
   }
   if (lane == 0) red_k[wave] = best;
   __syncthreads();
-  if (tid != 0) return;
+  if (tid >= 64) return;  // the first wave finishes (no barrier from here on)
   for (int w = 1; w < CTL_THREADS / 64; ++w) best = red_k[w] > best ? red_k[w] : best;
   const int p = 0x7fffffff - (int)(unsigned)(best & 0xffffffffull);
 
-  // Eq. 1 along the path to P*: the rows of its strict ancestors, root first
+  // Eq. 1 along the path to P*: the rows of its strict ancestors, root first.  The lanes fetch 64
+  // path entries at a time side by side (one round trip instead of one per level); the float32 sum
+  // still takes them one by one in path order.
   float acc = 0.f;
-  for (int t = 0; t < D; ++t) acc = acc + ent[ancestor(par, p, D - t)];
+  for (int t0 = 0; t0 < D; t0 += 64) {
+    const int t = t0 + lane;
+    const float e = t < D ? ent[ancestor(par, p, D - t)] : 0.f;
+    const int m = D - t0 < 64 ? D - t0 : 64;
+    for (int l = 0; l < m; ++l) acc = acc + __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, e), l));
+  }
+  if (lane != 0) return;
   int b = 0;
   for (int e = 0; e < a.n_edges; ++e) b += acc >= a.edges[e] ? 1 : 0;
   const bool low = b < a.n_low;
