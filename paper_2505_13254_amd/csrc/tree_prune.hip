@@ -118,8 +118,12 @@ __device__ __forceinline__ void prune_sequence(
         const int incl = wave_prefix_sum(mine_c);      // matching keys with digit >= 63 - l
         const int l_hit = __ffsll((long long)__ballot(incl >= need)) - 1;  // never empty: need <= matching keys
         const int above = __builtin_amdgcn_readlane(incl - mine_c, l_hit);
+        const int here = __builtin_amdgcn_readlane(mine_c, l_hit);  // matching keys with exactly this digit
         need -= above;
         x |= (unsigned long long)(63 - l_hit) << shift;
+        // all of them are wanted: the digits fixed so far, followed by zeros, already separate the kept
+        // keys from the others (the same values in every thread: the workgroup leaves the loop together)
+        if (here == need) break;
       }
       for (int i = tid; i < n; i += PR_THREADS) nxt[i] = (i == 0) ? 1 : ((keys[i] != 0ull && keys[i] >= x) ? 1 : 0);
     } else {
