@@ -232,9 +232,10 @@ hs_status hs_tree_attention_paged(const void* q, const void* k_pages, const void
  *   accepted rows.
  * Workspace: hs_verify_accept_workspace_mode gives what a call in `mode` needs; the query without
  *   a mode gives the largest of the three, that of HS_ACCEPT_STOCHASTIC: besides a few arrays of
- *   NN entries, a pair of floats per row and vocabulary entry plus 80 KiB of bucket tables per
- *   row (about 8 * NN * V bytes; left out for NN > 4096, where every rejection re-reads the two
- *   rows instead).  Rows whose address is a multiple of 16 bytes (base and row_stride * 4) take
+ *   NN entries, a pair of floats per row and vocabulary entry, 80 KiB of bucket tables per row
+ *   and a double per row and 64 vocabulary entries (about 8.2 * NN * V bytes; left out for
+ *   NN > 4096, where every rejection re-reads the two rows and the walk sums the rows of its stop
+ *   node itself).  Rows whose address is a multiple of 16 bytes (base and row_stride * 4) take
  *   the faster paths.
  */
 size_t hs_verify_accept_workspace(int32_t B, int32_t NN, int32_t V);

@@ -33,6 +33,8 @@ constexpr int AC_THREADS = 1024;
 constexpr int AC_WAVES = AC_THREADS / 64;
 constexpr int AC_MAX_KIDS = 256;    // children tried per node
 constexpr int AC_MAX_ROWS = 8192;   // 64-token rows of the CDF search held in LDS (V <= 524288)
+constexpr int BR_SLICES = 16;     // workgroups per tree row that sum the bonus distribution's rows ahead of the walk
+constexpr int BR_THREADS = 512;
 constexpr int BK_NODES = 4096;      // calls with up to this many tree rows get the sorted residual (below)
 constexpr int BK_SLICES = 16;       // vocabulary slices per row in the kernels that build it
 constexpr int BK_N = 256;           // buckets of the ratio p / q: BK_PER_OCTAVE per factor of two, from 1 upwards
@@ -492,7 +494,61 @@ struct ChainOut {
   double* child_frozen;  // [NN] its weight in the residual after its own rejection
   double* node_beta;     // [NN] beta and normaliser after all of the node's children were rejected
   double* node_Z;
+  int32_t* n_tried;      // [NN] number of children the node's chain tried (0: the node's residual is p itself)
+  double* bonus_rows;    // [NN][ceil(V / 64)] row sums of the residual a bonus token would be drawn from
+                         // if the walk stopped at the node (NULL: the walk sums the rows of its stop node)
 };
+
+// Sums of the bonus distribution's weights over rows of 64 tokens, rows [r_begin, r_end) of a node,
+// by all waves of the workgroup: dst[r] for each of them.  A lane takes four tokens, 16 lanes a row, a
+// wave four rows per trip; the loads of four trips are requested together (lanes past the last row
+// re-read it), and a row's 16 partial sums meet in its last lane by DPP moves.  Rows that are not
+// whole, or rows of arrays that are not 16-byte aligned, are summed a token per lane.  A row's sum
+// does not depend on who computes it: the walk and k_bonus_rows give the same bits.
+__device__ __forceinline__ void bonus_row_sums(const RowView& p, const RowView& q, bool sub_q, double beta, int V,
+                                               int r_begin, int r_end, double* __restrict__ dst) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
+  int first_row = r_begin;  // rows below it were summed with 16-byte loads
+  if (p.aligned16() && (!sub_q || q.aligned16()) && V >= 64) {
+    constexpr int TRIPS = 4;
+    const int full_end = min(V >> 6, r_end);
+    const int sub = lane >> 4, l16 = lane & 15;
+    const float bf = (float)beta;
+    const float4* __restrict__ px = reinterpret_cast<const float4*>(p.x);
+    const float4* __restrict__ qx = reinterpret_cast<const float4*>(q.x);
+    for (int r0 = r_begin + wave * 4; r0 < full_end; r0 += n_waves * 4 * TRIPS) {
+      float4 fp[TRIPS], fq[TRIPS];
+#pragma unroll
+      for (int u = 0; u < TRIPS; ++u) {
+        const int r = min(r0 + u * n_waves * 4 + sub, full_end - 1);
+        fp[u] = px[r * 16 + l16];
+        fq[u] = sub_q ? qx[r * 16 + l16] : fp[u];
+      }
+#pragma unroll
+      for (int u = 0; u < TRIPS; ++u) {
+        const int r = r0 + u * n_waves * 4 + sub;
+        const float4 pp = p.of4(fp[u]);
+        double w;
+        if (sub_q) {
+          const float4 qq = q.of4(fq[u]);
+          w = ((double)fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) + (double)fmaxf(fmaf(-bf, qq.y, pp.y), 0.f)) +
+              ((double)fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) + (double)fmaxf(fmaf(-bf, qq.w, pp.w), 0.f));
+        } else {
+          w = ((double)pp.x + (double)pp.y) + ((double)pp.z + (double)pp.w);
+        }
+        w = row16_sum(w);
+        if (l16 == 15 && r < full_end) dst[r] = w;
+      }
+    }
+    first_row = max(full_end, r_begin);
+  }
+  for (int r = first_row + wave; r < r_end; r += n_waves) {
+    const int v = r * 64 + lane;
+    double w = v < V ? token_weight(p, q, sub_q, beta, v) : 0.0;
+    w = wave_sum(w);
+    if (lane == 0) dst[r] = w;
+  }
+}
 
 // One workgroup per tree row that has children (others leave at once): the chain of rejections at
 // that node under the ratio rule, every child rejected in turn.
@@ -525,10 +581,17 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
   int depth = 0;
   for (int j = parent[o + cur]; j >= 0; j = parent[o + j]) ++depth;
   const int nk = gather_children(parent, o, n, cur, depth < max_depth, kids, kids_sorted, &n_kids);
-  if (nk == 0) return;
+  if (tid == 0) out.n_tried[g] = nk;
   const float* p_row = target + (int64_t)g * row_stride;
-  const float* q_row = draft + (int64_t)g * row_stride;
   const RowView p(p_row, p_row[p_arg], p_lz, inv_t);
+  if (nk == 0) {
+    // no chain to run: this workgroup sums the rows of p, the distribution a bonus token is drawn from
+    // if the walk stops here (done long before the longest chain of the launch)
+    const int n_rows = (V + 63) / 64;
+    if (out.bonus_rows != nullptr) bonus_row_sums(p, p, false, 0.0, V, 0, n_rows, out.bonus_rows + (int64_t)g * n_rows);
+    return;
+  }
+  const float* q_row = draft + (int64_t)g * row_stride;
   const RowView q(q_row, q_row[q_arg], q_lz, inv_t);
   // every child's token and its two probabilities, fetched side by side: the chain below is serial,
   // and a round trip to memory per step would dominate it
@@ -610,6 +673,31 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_chain(
     out.node_beta[o + cur] = beta;
     out.node_Z[o + cur] = Z;
   }
+}
+
+// grid (BR_SLICES, NN), after the chains: the row sums the walk would need if it stopped at row
+// blockIdx.y, for every row with children at once (the walk visits a few rows one after the other and
+// knows its stop row last; summing that row's vocabulary on its single compute unit took 15 us).  The
+// residual at a row is fixed before the walk: max(p - beta q, 0) with the chain's final beta where all
+// children were rejected (summed here), p itself where no child is tried (summed by the row's own
+// workgroup of k_accept_chain, which has nothing else to do); the rejected tokens' frozen weights are
+// the walk's corrections, as before.
+__global__ __launch_bounds__(BR_THREADS) void k_bonus_rows(const float* __restrict__ target,
+                                                           const float* __restrict__ draft, int64_t row_stride, int V,
+                                                           float inv_t, const int32_t* __restrict__ t_arg,
+                                                           const float* __restrict__ t_lz,
+                                                           const int32_t* __restrict__ d_arg,
+                                                           const float* __restrict__ d_lz, ChainOut chain) {
+  const int slice = blockIdx.x, g = blockIdx.y;
+  const int n_rows = (V + 63) / 64;
+  const int per = (n_rows + BR_SLICES - 1) / BR_SLICES;
+  const int r_begin = slice * per, r_end = min(n_rows, r_begin + per);
+  if (r_begin >= r_end || chain.n_tried[g] == 0) return;  // (a row without children: summed by its chain workgroup)
+  const float* p_row = target + (int64_t)g * row_stride;
+  const float* q_row = draft + (int64_t)g * row_stride;
+  const RowView p(p_row, p_row[t_arg[g]], t_lz[g], inv_t);
+  const RowView q(q_row, q_row[d_arg[g]], d_lz[g], inv_t);
+  bonus_row_sums(p, q, true, chain.node_beta[g], V, r_begin, r_end, chain.bonus_rows + (int64_t)g * n_rows);
 }
 
 __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
@@ -711,48 +799,11 @@ __global__ __launch_bounds__(AC_THREADS) void k_accept_walk(
     const double total = ratio_mode ? Z : rem;
     const double goal = (double)uniforms[NN + s] * total;
     const int n_rows = (V + 63) / 64;
-    int first_row = 0;  // rows below it were summed with 16-byte loads
-    if (p.aligned16() && (!sub_q || q.aligned16()) && V >= 64) {
-      // a lane takes four tokens, 16 lanes a row of 64, a wave four rows per trip; the loads of four
-      // trips are requested together (lanes past the last row re-read it), and a row's 16 partial
-      // sums meet in its last lane by DPP moves (no trip through LDS)
-      constexpr int TRIPS = 4;
-      const int full_rows = V >> 6;
-      const int sub = lane >> 4, l16 = lane & 15;
-      const float bf = (float)beta;
-      const float4* __restrict__ px = reinterpret_cast<const float4*>(p.x);
-      const float4* __restrict__ qx = reinterpret_cast<const float4*>(q.x);
-      for (int r0 = wave * 4; r0 < full_rows; r0 += AC_WAVES * 4 * TRIPS) {
-        float4 fp[TRIPS], fq[TRIPS];
-#pragma unroll
-        for (int u = 0; u < TRIPS; ++u) {
-          const int r = min(r0 + u * AC_WAVES * 4 + sub, full_rows - 1);
-          fp[u] = px[r * 16 + l16];
-          fq[u] = sub_q ? qx[r * 16 + l16] : fp[u];
-        }
-#pragma unroll
-        for (int u = 0; u < TRIPS; ++u) {
-          const int r = r0 + u * AC_WAVES * 4 + sub;
-          const float4 pp = p.of4(fp[u]);
-          double w;
-          if (sub_q) {
-            const float4 qq = q.of4(fq[u]);
-            w = ((double)fmaxf(fmaf(-bf, qq.x, pp.x), 0.f) + (double)fmaxf(fmaf(-bf, qq.y, pp.y), 0.f)) +
-                ((double)fmaxf(fmaf(-bf, qq.z, pp.z), 0.f) + (double)fmaxf(fmaf(-bf, qq.w, pp.w), 0.f));
-          } else {
-            w = ((double)pp.x + (double)pp.y) + ((double)pp.z + (double)pp.w);
-          }
-          w = row16_sum(w);
-          if (l16 == 15 && r < full_rows) rowsum[r] = w;
-        }
-      }
-      first_row = full_rows;
-    }
-    for (int r = first_row + wave; r < n_rows; r += AC_WAVES) {
-      const int v = r * 64 + lane;
-      double w = v < V ? token_weight(p, q, sub_q, beta, v) : 0.0;
-      w = wave_sum(w);
-      if (lane == 0) rowsum[r] = w;
+    if (chain.bonus_rows != nullptr) {  // summed ahead of the walk, for every row (k_bonus_rows)
+      const double* __restrict__ pre = chain.bonus_rows + (int64_t)(o + cur) * n_rows;
+      for (int r = tid; r < n_rows; r += AC_THREADS) rowsum[r] = pre[r];
+    } else {
+      bonus_row_sums(p, q, sub_q, beta, V, 0, n_rows, rowsum);
     }
     __syncthreads();
     if (tid == 0) {
@@ -854,6 +905,12 @@ static size_t bucket_workspace(int NN, int V, Carver* c, BucketWs* ws) {
          align_up((size_t)NN * V * sizeof(float2), 256) + align_up((size_t)NN * 4, 256);
 }
 
+// Bytes of the row sums k_bonus_rows leaves for the walk (0 beyond BK_NODES rows: the walk then sums
+// the rows of its stop node itself).
+static size_t bonus_rows_bytes(int NN, int V) {
+  return NN <= BK_NODES ? align_up((size_t)NN * ((V + 63) / 64) * sizeof(double), 256) : 0;
+}
+
 }  // namespace hs
 
 extern "C" size_t hs_verify_accept_workspace_mode(int32_t B, int32_t NN, int32_t V, hs_accept_mode mode) {
@@ -865,7 +922,9 @@ extern "C" size_t hs_verify_accept_workspace_mode(int32_t B, int32_t NN, int32_t
   const size_t chain = 5 * hs::align_up((size_t)NN * sizeof(double), 256) + hs::align_up((size_t)2 * NN, 256);
   // the sorted residual belongs to the ratio rule alone, and so does the scan of twice the rows
   const bool ratio = mode == HS_ACCEPT_STOCHASTIC;
-  const size_t sorted = ratio ? hs::bucket_workspace(NN, V, nullptr, nullptr) : 0;
+  size_t sorted = ratio ? hs::bucket_workspace(NN, V, nullptr, nullptr) : 0;
+  // the ratio rule's children counts, and the bonus distribution's row sums of every tree row
+  if (ratio) sorted += hs::align_up((size_t)NN * sizeof(int32_t), 256) + hs::bonus_rows_bytes(NN, V);
   const size_t scan1 = hs::row_topk_workspace(NN, V, 1), scan2 = ratio ? hs::row_topk_workspace(2 * NN, V, 1) : 0;
   return sets + chain + sorted + (scan1 > scan2 ? scan1 : scan2);
 }
@@ -908,7 +967,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   int32_t *t_arg = nullptr, *d_arg = nullptr;
   float *t_lz = nullptr, *d_lz = nullptr;
   hs::ScanSlices slices{nullptr, nullptr, 1};
-  hs::ChainOut chain{nullptr, nullptr, nullptr, nullptr, nullptr};
+  hs::ChainOut chain{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   hs::BucketWs bk{};  // (all NULL: no sorted residual)
   if (NN > 0) {
     hs::Carver c(workspace);
@@ -923,7 +982,11 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
     chain.node_beta = c.take<double>(NN);
     chain.node_Z = c.take<double>(NN);
     uint8_t* wanted = c.take<uint8_t>(2 * (size_t)NN);
-    if (mode == HS_ACCEPT_STOCHASTIC) hs::bucket_workspace(NN, V, &c, &bk);
+    if (mode == HS_ACCEPT_STOCHASTIC) {
+      hs::bucket_workspace(NN, V, &c, &bk);
+      chain.n_tried = c.take<int32_t>(NN);
+      if (hs::bonus_rows_bytes(NN, V) > 0) chain.bonus_rows = c.take<double>((size_t)NN * ((V + 63) / 64));
+    }
     void* scan_ws = c.take<char>(0);
     const float T = stochastic ? temperature : 1.0f;
     hs_status r;
@@ -969,6 +1032,12 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
                        d_arg, d_lz, chain, bk);
     hs_status r = hs::launch_status("accept (rejection chains)");
     if (r != HS_OK) return r;
+    if (chain.bonus_rows != nullptr) {
+      hipLaunchKernelGGL(hs::k_bonus_rows, dim3(hs::BR_SLICES, NN), dim3(hs::BR_THREADS), 0, st, target_logits,
+                         draft_logits, row_stride, V, 1.0f / temperature, t_arg, t_lz, d_arg, d_lz, chain);
+      r = hs::launch_status("accept (bonus rows)");
+      if (r != HS_OK) return r;
+    }
   }
   hipLaunchKernelGGL(hs::k_accept_walk, dim3(B), dim3(hs::AC_THREADS), 0, st, target_logits, draft_logits, row_stride,
                      token, parent, node_offsets, NN, V, (int)mode, 1.0f / temperature, uniforms, max_depth, t_arg,

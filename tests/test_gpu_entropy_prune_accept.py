@@ -327,6 +327,40 @@ def test_entropy_rows_picked_by_index(G):
     assert np.array_equal(G.host(one["topk_idx"]), draft_entropy_topk(x[33:34], K, 0.8)["topk_idx"])
 
 
+def _random_accept_case(rs, sizes, V, mode, T, D):
+    """Random trees (a row's parent is one of the five rows before it, siblings carry the draft's best
+    tokens), correlated draft and target rows, uniforms with a margin to every decision.  Returns the
+    arrays and the checker's result, or None when a decision is too close to call."""
+    B, NN = len(sizes), sum(sizes)
+    draft = (rs.normal(size=(NN, V)) * 2.5).astype(np.float32)
+    corr = rs.choice([0.5, 0.8, 0.95])
+    target = (corr * draft + rs.normal(size=draft.shape) * (1.5 * (1 - corr) + 0.3)).astype(np.float32)
+    parent, token, offs, o = np.zeros(NN, np.int32), np.zeros(NN, np.int32), [0], 0
+    for n in sizes:
+        parent[o] = -1
+        kids = {}
+        for i in range(1, n):
+            p = int(rs.randint(max(0, i - 5), i))
+            parent[o + i] = p
+            kids.setdefault(p, []).append(i)
+        for p, ks in kids.items():       # siblings carry the draft's best tokens, distinct
+            for c, tk in zip(ks, np.argsort(-draft[o + p], kind="stable")[:len(ks)]):
+                token[o + c] = tk
+        o += n
+        offs.append(o)
+    offs = np.asarray(offs, np.int32)
+    u = np.concatenate([0.3 + 0.6999 * rs.rand(NN), rs.rand(B)]).astype(np.float32)
+    base = verify_accept(target, draft, token, parent, offs, mode, T, u, D)
+    for sgn in (-1.0, 1.0):
+        un = u.astype(np.float64).copy()
+        un[:NN] *= 1.0 + sgn * 1e-4
+        un[NN:] = np.clip(un[NN:] + sgn * 1e-5, 0.0, 1.0 - 1e-12)
+        alt = verify_accept(target, draft, token, parent, offs, mode, T, un, D)
+        if not all(np.array_equal(alt[k], base[k]) for k in base):
+            return None
+    return target, draft, token, parent, offs, u, base
+
+
 @pytest.mark.parametrize("seed", [1, 2])
 def test_accept_random_trees(G, seed):
     """Forty random cases per seed: both sampling rules, 1 to 3 sequences of up to 25 rows, vocabularies
@@ -341,36 +375,11 @@ def test_accept_random_trees(G, seed):
         B = int(rs.randint(1, 4))
         T = float(rs.choice([0.7, 1.0, 1.3]))
         sizes = [int(rs.randint(1, 26)) for _ in range(B)]
-        NN = sum(sizes)
-        draft = (rs.normal(size=(NN, V)) * 2.5).astype(np.float32)
-        corr = rs.choice([0.5, 0.8, 0.95])
-        target = (corr * draft + rs.normal(size=draft.shape) * (1.5 * (1 - corr) + 0.3)).astype(np.float32)
-        parent, token, offs, o = np.zeros(NN, np.int32), np.zeros(NN, np.int32), [0], 0
-        for n in sizes:
-            parent[o] = -1
-            kids = {}
-            for i in range(1, n):
-                p = int(rs.randint(max(0, i - 5), i))
-                parent[o + i] = p
-                kids.setdefault(p, []).append(i)
-            for p, ks in kids.items():       # siblings carry the draft's best tokens, distinct
-                for c, tk in zip(ks, np.argsort(-draft[o + p], kind="stable")[:len(ks)]):
-                    token[o + c] = tk
-            o += n
-            offs.append(o)
-        offs = np.asarray(offs, np.int32)
-        u = np.concatenate([0.3 + 0.6999 * rs.rand(NN), rs.rand(B)]).astype(np.float32)
         D = int(rs.randint(1, 7))
-        base = verify_accept(target, draft, token, parent, offs, mode, T, u, D)
-        safe = True
-        for sgn in (-1.0, 1.0):
-            un = u.astype(np.float64).copy()
-            un[:NN] *= 1.0 + sgn * 1e-4
-            un[NN:] = np.clip(un[NN:] + sgn * 1e-5, 0.0, 1.0 - 1e-12)
-            alt = verify_accept(target, draft, token, parent, offs, mode, T, un, D)
-            safe = safe and all(np.array_equal(alt[k], base[k]) for k in base)
-        if not safe:
+        case = _random_accept_case(rs, sizes, V, mode, T, D)
+        if case is None:
             continue
+        target, draft, token, parent, offs, u, base = case
         out = hs.hs_verify_accept(G.dev(target), G.dev(draft) if mode == 1 else None, G.dev(token, torch.int32),
                                   G.dev(parent, torch.int32), G.dev(offs, torch.int32), mode, T,
                                   G.dev(u, torch.float32), D)
@@ -380,3 +389,51 @@ def test_accept_random_trees(G, seed):
         if done == 40:
             break
     assert done == 40 and max(lens) >= 2
+
+
+def test_accept_ratio_rule_with_more_rows_than_the_tables_cover(G):
+    """Beyond 4096 tree rows a call has neither the sorted residual nor the row sums prepared ahead of
+    the walk: the chains take plain passes and the walk sums the rows of its stop node itself.  A batch
+    of 4104 rows in 216 sequences; the sequences whose decisions are all clear of their uniforms are
+    compared (a close call in one sequence does not touch the others)."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(11)
+    sizes = [19] * 216
+    V, T, D = 4096, 1.0, 4
+    NN = sum(sizes)
+    assert NN > 4096
+    B = len(sizes)
+    draft = (rs.normal(size=(NN, V)) * 2.5).astype(np.float32)
+    target = (0.8 * draft + rs.normal(size=draft.shape) * 0.6).astype(np.float32)
+    parent, token, offs, o = np.zeros(NN, np.int32), np.zeros(NN, np.int32), [0], 0
+    for n in sizes:
+        parent[o] = -1
+        kids = {}
+        for i in range(1, n):
+            p = int(rs.randint(max(0, i - 5), i))
+            parent[o + i] = p
+            kids.setdefault(p, []).append(i)
+        for p, ks in kids.items():
+            for c, tk in zip(ks, np.argsort(-draft[o + p], kind="stable")[:len(ks)]):
+                token[o + c] = tk
+        o += n
+        offs.append(o)
+    offs = np.asarray(offs, np.int32)
+    u = np.concatenate([0.3 + 0.6999 * rs.rand(NN), rs.rand(B)]).astype(np.float32)
+    base = verify_accept(target, draft, token, parent, offs, 1, T, u, D)
+    safe = np.ones(B, bool)
+    for sgn in (-1.0, 1.0):
+        un = u.astype(np.float64).copy()
+        un[:NN] *= 1.0 + sgn * 1e-4
+        un[NN:] = np.clip(un[NN:] + sgn * 1e-5, 0.0, 1.0 - 1e-12)
+        alt = verify_accept(target, draft, token, parent, offs, 1, T, un, D)
+        safe &= (alt["accept_len"] == base["accept_len"]) & (alt["bonus_token"] == base["bonus_token"])
+        safe &= np.all(alt["accept_path"] == base["accept_path"], axis=1)
+    assert safe.sum() > 150
+    out = hs.hs_verify_accept(G.dev(target), G.dev(draft), G.dev(token, torch.int32), G.dev(parent, torch.int32),
+                              G.dev(offs, torch.int32), 1, T, G.dev(u, torch.float32), D)
+    got = {k: G.host(v) for k, v in out.items()}
+    assert np.array_equal(got["accept_len"][safe], base["accept_len"][safe])
+    assert np.array_equal(got["bonus_token"][safe], base["bonus_token"][safe])
+    assert np.array_equal(got["accept_path"][safe], base["accept_path"][safe])
+    assert base["accept_len"].max() >= 2
