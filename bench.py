@@ -263,6 +263,25 @@ def main():
         del one
     del big, dst
 
+    # The same step under the sampling rule (ratio rule, seeded uniforms): reported beside the headline
+    # line, which keeps the accept rule asked for.
+    sampling = None
+    if mode == 0:
+        st2 = harness.build_step(w, args.seed, layers=layers, accept_mode=1)
+        for _ in range(max(args.warmup, 3)):
+            st2.run()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(K):
+            st2.run()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t2) * 1e3 / K
+        acc2 = st2.t["s4_out"]
+        sampling = {"accept": "stochastic", "ms_per_step": ms2,
+                    "tree_tokens_per_s": st2.host["kept_draft_nodes"] / (ms2 * 1e-3),
+                    "accept_len": [int(x) for x in acc2["accept_len"].cpu().numpy()][:16]}
+        del st2
+
     h = step.host
     tokens = h["kept_draft_nodes"]
     bytes3 = step.bytes_stage3()
@@ -298,6 +317,7 @@ def main():
         "tree_attn_hbm_gbps": achieved, "tree_attn_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "copy_ceiling_gbps": copy_gbps,
         "tree_attn_single_layer": single,
+        "step_with_sampling_accept": sampling,
         "roofline": {"kernel": "hs_tree_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": bytes3, "algorithmic_flops_per_launch": flops3,

@@ -42,3 +42,6 @@ def test_one_json_line_with_the_agreed_keys():
     for k in ("value", "unit", "cores", "kind", "sample"):
         assert k in cb, k
     assert cb["kind"] == "oracle" and cb["value"] > 0
+    # the same step under the sampling rule rides along (not the headline value)
+    sa = d["step_with_sampling_accept"]
+    assert sa["accept"] == "stochastic" and sa["ms_per_step"] > d["ms_per_step"] * 0.9
