@@ -246,3 +246,34 @@ def test_paged_attention_and_commit(G, wid, B):
         assert np.array_equal(_bits(dl), lens)
         raw = lambda x: x.view(np.uint32) if x.dtype == np.float32 else x       # (unused slots hold NaN)
         assert np.array_equal(raw(_bits(dk)), raw(pool_k)) and np.array_equal(raw(_bits(dv)), raw(pool_v))
+
+
+def test_paged_attention_with_several_row_groups(G):
+    """Trees of more than 64 rows on the 8B shape (4 query heads per KV head: more than 256 rows per
+    KV head, i.e. several row groups that read the same pages), next to small trees, over paged caches
+    with a shuffled page order; one sequence long enough to be cut into key splits."""
+    import paper_2505_13254_amd as hs
+    from oracle.kv_commit import gather_pages
+    w = W.small(W.WORKLOADS[2], B=3)
+    rs = np.random.RandomState(77)
+    B = 3
+    lens = np.asarray([300, 2700, 65], np.int64)
+    sizes = [100, 129, 7]
+    max_blocks = int((lens.max() + 63) // 64)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    fill = [W.attention_inputs(w, 1, s, int(lens[s]), 1, "unit") for s in range(B)]
+    dense_k, dense_v = (np.concatenate([p[i] for p in fill], axis=0) for i in (1, 2))
+    pool_k, table = _paginate(np.random.RandomState(5), dense_k, offs, lens, max_blocks)
+    pool_v, _ = _paginate(np.random.RandomState(5), dense_v, offs, lens, max_blocks)
+    parents = [_random_parents(rs, n) for n in sizes]
+    parts = [W.attention_inputs(w, 2, s, 0, sizes[s], "unit", parent=np.asarray(parents[s])) for s in range(B)]
+    q, kt, vt = (np.concatenate([p[i] for p in parts], axis=0) for i in (0, 3, 4))
+    par = np.concatenate([np.asarray(p, np.int32) for p in parents]).astype(np.int32)
+    no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    gk, po = gather_pages(pool_k, table, lens)
+    gv, _ = gather_pages(pool_v, table, lens)
+    want_o, _ = tree_attention(q, gk, gv, kt, vt, par, no, po, 1.0 / np.sqrt(w.D))
+    o, _ = hs.hs_tree_attention_paged(G.dev_store(q), G.dev_store(pool_k), G.dev_store(pool_v), G.dev_store(kt),
+                                      G.dev_store(vt), G.dev(par), G.dev(no), torch.from_numpy(no), G.dev(table),
+                                      G.dev(lens), torch.from_numpy(lens.copy()), 1.0 / float(np.sqrt(w.D)))
+    assert np.abs(G.host(o).astype(np.float64) - want_o).max() <= 2e-2
