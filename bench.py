@@ -176,7 +176,6 @@ def main():
     for k in range(K):
         step.stage1()
         step.stage2()
-        step.stage3_tree()
         hs.hs_time_next_attention(ev[k][0], ev[k][1])
         step.stage3()
         step.stage4()
@@ -187,26 +186,23 @@ def main():
 
     # Per-stage breakdown: a second pass of K steps with an event recorded at every stage boundary
     # (recorded events cost about 5 us a pair, which is why they stay out of the timed region above;
-    # gaps[3] is the attention call bracketed that way, combine kernel included when there is one).
-    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(K)]
+    # gaps[2] is the attention call bracketed that way, combine kernel included when there is one).
+    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
     for k in range(K):
         ev2[k][0].record()
         step.stage1()
         ev2[k][1].record()
         step.stage2()
         ev2[k][2].record()
-        step.stage3_tree()
-        ev2[k][3].record()
         step.stage3()
-        ev2[k][4].record()
+        ev2[k][3].record()
         step.stage4()
-        ev2[k][5].record()
+        ev2[k][4].record()
     torch.cuda.synchronize()
-    gaps = [[ev2[k][i].elapsed_time(ev2[k][i + 1]) for k in range(K)] for i in range(5)]
-    stage_ms = [float(np.mean(gaps[0])), float(np.mean(gaps[1])), float(np.mean(attn)), float(np.mean(gaps[4]))]
-    stage_med = [float(np.median(gaps[0])), float(np.median(gaps[1])), float(np.median(attn)), float(np.median(gaps[4]))]
-    tree_copy_ms = float(np.mean(gaps[2]))
-    attn_bracketed_ms = float(np.mean(gaps[3]))
+    gaps = [[ev2[k][i].elapsed_time(ev2[k][i + 1]) for k in range(K)] for i in range(4)]
+    stage_ms = [float(np.mean(gaps[0])), float(np.mean(gaps[1])), float(np.mean(attn)), float(np.mean(gaps[3]))]
+    stage_med = [float(np.median(gaps[0])), float(np.median(gaps[1])), float(np.median(attn)), float(np.median(gaps[3]))]
+    attn_bracketed_ms = float(np.mean(gaps[2]))
 
     # what a pair of events costs by itself on the busy stream (it is inside every figure above)
     pe = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 20)]
@@ -214,7 +210,7 @@ def main():
     for i in range(20):
         pe[2 * i].record()
         pe[2 * i + 1].record()
-        step.stage3_tree()
+        step.stage2()
     torch.cuda.synchronize()
     event_pair_ms = float(np.median([pe[2 * i].elapsed_time(pe[2 * i + 1]) for i in range(20)]))
 
@@ -309,7 +305,7 @@ def main():
                    "draft_rows_quantified": int(step.t["draft_rows"].shape[0]), "accept": args.accept},
         "stage_ms": {"entropy_topk": stage_ms[0], "prune": stage_ms[1], "attention": stage_ms[2], "accept": stage_ms[3],
                      "attention_call_bracketed_by_events": attn_bracketed_ms,
-                     "tree_to_layers_copy": tree_copy_ms, "empty_event_pair": event_pair_ms},
+                     "empty_event_pair": event_pair_ms},
         "stage_ms_median": {"entropy_topk": stage_med[0], "prune": stage_med[1], "attention": stage_med[2],
                             "accept": stage_med[3]},
         "stage_gbps": {"entropy_topk": step.bytes_stage1() / (stage_ms[0] * 1e-3) / 1e9,

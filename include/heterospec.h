@@ -23,6 +23,7 @@
  *                           resumes behind the last accepted token)
  *   hs_tree_attention_lens  hs_tree_attention on caches stored with spare capacity
  *   hs_tree_attention_paged, hs_kv_commit_paged   the same two on caches made of pages
+ *   hs_tree_attention_shared_tree   hs_tree_attention on batch entries that all verify one tree
  *
  * Conventions that hold for every call
  *   - Pointers are DEVICE pointers unless the parameter name starts with host_.  The caller owns
@@ -191,6 +192,21 @@ hs_status hs_tree_attention_lens(const void* q, const void* k_prefix, const void
                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale,
                                  void* o, float* lse,
                                  void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* hs_tree_attention_shared_tree: hs_tree_attention on B batch entries that verify the same tree, each
+ * with its own Q, K and V: the decoder layers of one verification step (Section 2.2: one tree-mask
+ * pass of the target model over the draft tree), or sequences that were given the same tree.
+ * `parent` holds that one tree (int32 [M], device; e.g. hs_tree_prune's out_parent as it is); every
+ * entry must have M rows (node_offsets[s+1] - node_offsets[s] == M for all s, checked on the host
+ * copy: HS_ERR_SHAPE otherwise).  Everything else as hs_tree_attention. */
+hs_status hs_tree_attention_shared_tree(const void* q, const void* k_prefix, const void* v_prefix,
+                                        const void* k_tree, const void* v_tree,
+                                        const int32_t* parent, const int32_t* node_offsets,
+                                        const int64_t* prefix_offsets,
+                                        const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale,
+                                        void* o, float* lse,
+                                        void* workspace, size_t workspace_bytes, hs_stream stream);
 
 /* hs_tree_attention_paged: hs_tree_attention on paged KV caches.  k_pages / v_pages are pools
  * [n_pages, page_tokens, Hkv, D]; block_table (device, int32 [B, max_blocks]) names the page of each

@@ -41,6 +41,8 @@ _SIGNATURES = {
     "hs_tree_attention_workspace": (_sz, [_i32, _i32, _i64, _i32, _i32, _i32, _c.c_int]),
     "hs_tree_attention": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                      _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "hs_tree_attention_shared_tree": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
+                                                 _i32, _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
     "hs_tree_attention_lens": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
                                           _i32, _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
     "hs_tree_attention_paged": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _i32,
@@ -256,12 +258,15 @@ def hs_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offset
                       host_node_offsets, host_prefix_offsets, scale: float, *, want_lse: bool = False,
                       out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
                       ws: Optional[torch.Tensor] = None, stream=None,
-                      prefix_lens: Optional[torch.Tensor] = None, host_prefix_lens: Optional[torch.Tensor] = None):
+                      prefix_lens: Optional[torch.Tensor] = None, host_prefix_lens: Optional[torch.Tensor] = None,
+                      shared_tree: bool = False):
     """q [NN,Hq,D]; k_prefix, v_prefix [total_prefix,Hkv,D]; k_tree, v_tree [NN,Hkv,D] (float32 or bfloat16, GPU);
     parent int32 [NN], node_offsets int32 [B+1], prefix_offsets int64 [B+1] on the GPU and the same two offset
     arrays on the host (CPU tensors).  Returns (o [NN,Hq,D], lse [NN,Hq] or None).
     With prefix_lens (int64 [B], GPU) and host_prefix_lens (the same on the CPU) the call is
-    hs_tree_attention_lens: prefix_offsets then delimit cache regions with spare capacity."""
+    hs_tree_attention_lens: prefix_offsets then delimit cache regions with spare capacity.
+    shared_tree: the call is hs_tree_attention_shared_tree: parent int32 [M] is one tree that all B entries
+    (of M rows each) use."""
     dt = _dtype_code(q)
     for name, t in (("q", q), ("k_prefix", k_prefix), ("v_prefix", v_prefix), ("k_tree", k_tree), ("v_tree", v_tree)):
         _dev(t, q.dtype, name)
@@ -284,7 +289,11 @@ def hs_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offset
             _ptr(node_offsets), _ptr(prefix_offsets), _vp(hno.data_ptr()), _vp(hpo.data_ptr()))
     tail = (B, Hq, Hkv, D, dt, float(scale), _ptr(out), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(),
             _stream(stream))
-    if prefix_lens is None:
+    if shared_tree:
+        if prefix_lens is not None:
+            raise ValueError("shared_tree and prefix_lens cannot be combined")
+        st = lib().hs_tree_attention_shared_tree(*head, *tail)
+    elif prefix_lens is None:
         st = lib().hs_tree_attention(*head, *tail)
     else:
         _dev(prefix_lens, torch.int64, "prefix_lens")

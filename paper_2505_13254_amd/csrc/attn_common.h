@@ -66,6 +66,7 @@ struct AttnArgs {
   const void* k_tree;
   const void* v_tree;
   const int32_t* parent;
+  int tree_shared;  // 1: `parent` holds one tree that every batch entry uses (all entries have its row count)
   const int32_t* node_offsets;
   const int64_t* prefix_offsets;
   const int64_t* prefix_lens;  // used tokens of each sequence's prefix region; NULL: the whole region

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(GEN_THREADS) void k_attn_generic(AttnArgs a) {
   const T* kt = static_cast<const T*>(a.k_tree) + (int64_t)n0 * Hkv * D;
   const T* vt = static_cast<const T*>(a.v_tree) + (int64_t)n0 * Hkv * D;
 
-  for (int i = tid; i < M; i += GEN_THREADS) par[i] = a.parent[n0 + i];
+  for (int i = tid; i < M; i += GEN_THREADS) par[i] = a.parent[(a.tree_shared ? 0 : n0) + i];
   const int r0 = rb * GEN_ROWS;
   for (int e = tid; e < GEN_ROWS * D; e += GEN_THREADS) {
     const int rr = e / D, d = e - rr * D;
@@ -447,7 +447,8 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
                                 const int64_t* host_prefix_offsets, const int64_t* prefix_lens,
                                 const int64_t* host_prefix_lens, const int32_t* block_table, int32_t max_blocks,
                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
-                                float* lse, void* workspace, size_t workspace_bytes, hs_stream stream) {
+                                float* lse, void* workspace, size_t workspace_bytes, hs_stream stream,
+                                bool tree_shared = false) {
   const bool paged = block_table != nullptr;
   hipEvent_t ev_start = timing_start, ev_stop = timing_stop;  // one-shot, whatever this call comes to
   timing_start = timing_stop = nullptr;
@@ -503,7 +504,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
                     aligned16(o);
   AttnArgs a;
   a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_tree = k_tree; a.v_tree = v_tree;
-  a.parent = parent; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets; a.prefix_lens = prefix_lens;
+  a.parent = parent; a.tree_shared = tree_shared ? 1 : 0; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets; a.prefix_lens = prefix_lens;
   a.block_table = block_table; a.max_blocks = max_blocks;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
   a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
@@ -569,6 +570,26 @@ extern "C" hs_status hs_tree_attention_lens(const void* q, const void* k_prefix,
   return attention_impl(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offsets, prefix_offsets, host_node_offsets,
                         host_prefix_offsets, prefix_lens, host_prefix_lens, nullptr, 0, B, Hq, Hkv, D, dt, scale, o, lse,
                         workspace, workspace_bytes, stream);
+}
+
+extern "C" hs_status hs_tree_attention_shared_tree(const void* q, const void* k_prefix, const void* v_prefix,
+                                                   const void* k_tree, const void* v_tree, const int32_t* parent,
+                                                   const int32_t* node_offsets, const int64_t* prefix_offsets,
+                                                   const int32_t* host_node_offsets,
+                                                   const int64_t* host_prefix_offsets, int32_t B, int32_t Hq,
+                                                   int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o, float* lse,
+                                                   void* workspace, size_t workspace_bytes, hs_stream stream) {
+  clear_error();
+  if (B > 0 && host_node_offsets != nullptr) {
+    const int M = host_node_offsets[1] - host_node_offsets[0];
+    for (int s = 1; s < B; ++s)
+      HS_REQUIRE(host_node_offsets[s + 1] - host_node_offsets[s] == M, HS_ERR_SHAPE,
+                 "hs_tree_attention_shared_tree: entry %d has %d rows, entry 0 has %d", s,
+                 host_node_offsets[s + 1] - host_node_offsets[s], M);
+  }
+  return attention_impl(q, k_prefix, v_prefix, k_tree, v_tree, parent, node_offsets, prefix_offsets, host_node_offsets,
+                        host_prefix_offsets, nullptr, nullptr, nullptr, 0, B, Hq, Hkv, D, dt, scale, o, lse, workspace,
+                        workspace_bytes, stream, true);
 }
 
 extern "C" hs_status hs_tree_attention_paged(const void* q, const void* k_pages, const void* v_pages,

@@ -167,12 +167,12 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   float* const h_lse = a.lse;
   float* const h_part = a.part;
   const float h_scale = a.scale;
-  const int h_sp_max = a.sp_max, h_n_tbl = a.n_tbl;
+  const int h_sp_max = a.sp_max, h_n_tbl = a.n_tbl, h_tree_shared = a.tree_shared;
   const int G = a.G, Hkv = a.Hkv, Hq = a.Hq;
   asm volatile("" : "+v"(t0_lo), "+v"(t0_hi));  // (keeps the request here instead of inside the branch that uses it)
   asm volatile("" ::"s"(h_q), "s"(h_k_prefix), "s"(h_v_prefix), "s"(h_k_tree), "s"(h_v_tree), "s"(h_parent), "s"(h_o),
                "s"(h_lse), "s"(h_part), "s"(h_scale), "s"(h_sp_max), "s"(h_n_tbl), "s"(G), "s"(Hkv), "s"(Hq),
-               "s"(n_rg_max));
+               "s"(n_rg_max), "s"(h_tree_shared));
   int n0, M, g, rg, sp, n_sp, tiles_per_split;
   int64_t p0, L;
   if (h_n_tbl > 0) {
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const float inv_G = 1.0f / (float)G;
   auto div_G = [&](int r) { return (int)(((float)r + 0.5f) * inv_G); };
   int my_parent = -1;
-  if (last_split && tid < M) my_parent = h_parent[n0 + tid];
+  if (last_split && tid < M) my_parent = h_parent[(h_tree_shared ? 0 : n0) + tid];  // (one tree for all entries, or each its own)
   bf16x8 qf[8];
   int tree_row;
   {

@@ -105,8 +105,7 @@ class Step:
     t: Dict[str, torch.Tensor] = field(default_factory=dict)
     host: Dict[str, object] = field(default_factory=dict)
 
-    # ---- the four stages, each one C call (plus, for stage 3, a device copy that hands the pruned
-    # tree to every layer's attention problem)
+    # ---- the four stages, each one C call
     def stage1(self):
         return hs.hs_draft_entropy_topk(self.t["draft_rows"], self.w.topk, self.w.temperature,
                                         out=self.t["s1_out"], ws=self.t["s1_ws"])
@@ -116,15 +115,14 @@ class Step:
                                 self.t["d_max"], self.t["theta"], self.t["max_nodes"],
                                 out=self.t["s2_out"], ws=self.t["s2_ws"])
 
-    def stage3_tree(self):
-        """With several layers: the pruned tree (stage 2's device output) becomes the tree of every
-        layer's batch entry (a small device copy, no host round trip)."""
-        t, h = self.t, self.host
-        if self.layers > 1:
-            t["attn_parent"].view(self.layers, -1).copy_(t["s2_out"]["out_parent"][:h["NNp"]])
-
     def stage3(self):
         t, h = self.t, self.host
+        if self.layers > 1:
+            # every layer verifies the tree that stage 2 has just left on the device
+            return hs.hs_tree_attention(t["q"], t["k_prefix"], t["v_prefix"], t["k_tree"], t["v_tree"],
+                                        t["s2_out"]["out_parent"], t["attn_node_offsets"], t["attn_prefix_offsets"],
+                                        h["attn_node_offsets"], h["attn_prefix_offsets"], h["scale"],
+                                        out=t["o"], ws=t["s3_ws"], shared_tree=True)
         return hs.hs_tree_attention(t["q"], t["k_prefix"], t["v_prefix"], t["k_tree"], t["v_tree"],
                                     t["attn_parent"], t["attn_node_offsets"], t["attn_prefix_offsets"],
                                     h["attn_node_offsets"], h["attn_prefix_offsets"], h["scale"],
@@ -141,7 +139,6 @@ class Step:
     def run(self):
         self.stage1()
         self.stage2()
-        self.stage3_tree()
         self.stage3()
         self.stage4()
 
@@ -349,10 +346,9 @@ class AdaptiveStep:
         a = t["attn"][M]
         src = t["s2_out"]["out_src"][:M]
         par = t["s2_out"]["out_parent"][:M]
-        a["parent"].view(self.layers, M).copy_(par)
-        hs.hs_tree_attention(a["q"], t["k_prefix"], t["v_prefix"], a["k_tree"], a["v_tree"], a["parent"],
+        hs.hs_tree_attention(a["q"], t["k_prefix"], t["v_prefix"], a["k_tree"], a["v_tree"], par,
                              a["node_offsets"], t["prefix_offsets"], a["host_node_offsets"], h["prefix_offsets"],
-                             h["scale"], out=a["o"], ws=a["ws"])
+                             h["scale"], out=a["o"], ws=a["ws"], shared_tree=True)
         # stands in for the target model's output rows of the kept nodes
         torch.index_select(st["token"], 0, src, out=a["token"])
         torch.index_select(t["target_all"], 0, src, out=a["target"])
@@ -463,7 +459,7 @@ def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, e
         a = dict(q=torch.cat([_store(p[0], device) for p in parts], dim=0).contiguous(),
                  k_tree=torch.cat([_store(p[3], device) for p in parts], dim=0).contiguous(),
                  v_tree=torch.cat([_store(p[4], device) for p in parts], dim=0).contiguous(),
-                 parent=torch.empty(layers * M, **i32), node_offsets=_dev(no, torch.int32, device),
+                 node_offsets=_dev(no, torch.int32, device),
                  host_node_offsets=torch.from_numpy(no.copy()), token=torch.empty(M, **i32),
                  target=torch.empty((M, w.V), dtype=torch.float32, device=device))
         a["o"] = torch.empty_like(a["q"])

@@ -225,3 +225,42 @@ def test_random_ragged_batches(G, seed):
         parents = [_random_parents(rs, n) if n else [] for n in sizes]
         variant = ["config", "unit", "peaky"][rs.randint(3)]
         _compare(G, _case(w, 100 * seed + it, parents, Ls, variant), "bf16")
+
+
+@pytest.mark.parametrize("wid,M,B", [(2, 61, 5), (2, 100, 3), (1, 16, 4)])
+def test_entries_that_share_one_tree(G, wid, M, B):
+    """hs_tree_attention_shared_tree: B entries (different Q, K, V and prefix lengths) verify one tree
+    passed once; the result equals the checker's on the tree repeated per entry, and bit for bit the
+    ordinary call's on the repeated tree.  Matrix-core kernel with one and with several row groups,
+    and the float32 kernel."""
+    import paper_2505_13254_amd as hs
+    w = W.WORKLOADS[wid]
+    rs = np.random.RandomState(90 + M)
+    tree = _random_parents(rs, M)
+    Ls = [int(x) for x in rs.randint(0, 700, size=B)]
+    st = _case(w, 8, [tree] * B, Ls, "unit")
+    want_o, want_lse = P.attention_out(st)
+    plain_o, plain_lse = G.run_attention(st)
+    no, po = st["node_offsets"], st["prefix_offsets"]
+    o, lse = hs.hs_tree_attention(G.dev_store(st["q"]), G.dev_store(st["k_prefix"]), G.dev_store(st["v_prefix"]),
+                                  G.dev_store(st["k_tree"]), G.dev_store(st["v_tree"]),
+                                  G.dev(np.asarray(tree, np.int32), torch.int32), G.dev(no), G.dev(po),
+                                  torch.from_numpy(no), torch.from_numpy(po), float(st["scale"]), want_lse=True,
+                                  shared_tree=True)
+    o, lse = G.host(o), G.host(lse)
+    dtype = "f32" if w.dtype == "f32" else "bf16"
+    assert np.abs(o.astype(np.float64) - want_o).max() <= TOL[dtype]
+    assert np.array_equal(o, plain_o) and np.array_equal(lse, plain_lse)
+
+
+def test_shared_tree_needs_entries_of_equal_size(G):
+    import paper_2505_13254_amd as hs
+    w = W.WORKLOADS[2]
+    rs = np.random.RandomState(3)
+    st = _case(w, 8, [_random_parents(rs, 10), _random_parents(rs, 12)], [64, 64], "unit")
+    no, po = st["node_offsets"], st["prefix_offsets"]
+    with pytest.raises(RuntimeError, match="rows"):
+        hs.hs_tree_attention(G.dev_store(st["q"]), G.dev_store(st["k_prefix"]), G.dev_store(st["v_prefix"]),
+                             G.dev_store(st["k_tree"]), G.dev_store(st["v_tree"]),
+                             G.dev(st["parent"][:10], torch.int32), G.dev(no), G.dev(po), torch.from_numpy(no),
+                             torch.from_numpy(po), float(st["scale"]), shared_tree=True)
