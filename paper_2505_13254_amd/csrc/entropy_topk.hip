@@ -52,11 +52,6 @@ static ScanPlan plan_scan(int R, int V) {
   const int n_tiles = (V + tile - 1) / tile;
   // few rows: slice them until the chip is full (measured best)
   int want = SCAN_TARGET_WGS * (SCAN_BIG / p.threads) / (R > 0 ? R : 1);
-  static const int forced = [] {
-    const char* e = getenv("HS_SCAN_SPLITS");  // tuning aid: fixes the slices per row
-    return e ? atoi(e) : 0;
-  }();
-  if (forced > 0) want = forced;
   if (want > n_tiles) want = n_tiles;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
   if (want < 1) want = 1;

@@ -327,13 +327,8 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
   }
   if (n == 0) return false;
   static const int targets[] = {1 << 20, 192, 128, 96, 64, 48, 32, 24, 16, 8};
-  static const int forced = [] {
-    const char* e = getenv("HS_ATTN_SPLIT_TILES");  // tuning aid: fixes the target tiles per item
-    return e ? atoi(e) : 0;
-  }();
   ListPlan best{0.f, 0};
   for (int target : targets) {
-    if (forced > 0) target = forced;
     double total = 0.0, rec_bytes = 0.0;
     float mx = 0.f, mn = 1e30f;
     int64_t items = 0;
@@ -358,7 +353,6 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
     }
     if (rec_bytes > 0.0) est += 4.f + (float)(rec_bytes / 2.5e6);  // the combine launch, ~2.5 TB/s
     if (best.target == 0 || est < best.est_us) best = ListPlan{est, target};
-    if (forced > 0) break;
   }
   // the table: sequences by falling cost of an item
   int order[ATTN_TBL];

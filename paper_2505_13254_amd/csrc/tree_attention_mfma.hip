@@ -127,12 +127,6 @@ __device__ __forceinline__ void wait_lds(int n) {  // n is a constant once the w
   }
 }
 
-#ifdef HS_TS
-__device__ unsigned long long dbg_ts[4096 * 16];
-#define TS(i) do { __builtin_amdgcn_sched_barrier(0); ts_[i] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#else
-#define TS(i)
-#endif
 #define MF_PIN() __builtin_amdgcn_sched_barrier(0)
 
 // PAGED: the prefix K/V live in pages of MF_TILE tokens ([page, token, Hkv, D]); a tile is a page.
@@ -145,11 +139,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   __shared__ int exact_flag;
   __shared__ int page_lds[PAGED ? 256 : 1];
 
-#ifdef HS_TS
-  unsigned long long ts_[16] = {0};
-#endif
-  TS(0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform for the compiler too: scalar branches)
   const int col = lane & 31, half = lane >> 5;
   // The first 64 entries of the work-list table are requested before anything else (the table is
   // part of the kernel arguments, so entry `lane` exists whatever the launch), and every scalar
@@ -300,6 +291,16 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
                  (unsigned)(r1 * (int)tok_stride) + dma_chunk, lds_k_addr + ring, lds_v_addr + ring,
                  lds_k_addr + ring + MF_BLOCK_BYTES, lds_v_addr + ring + MF_BLOCK_BYTES);
   };
+  // waits until at most n (a multiple of four, at most 16) of this wave's loads are pending
+  auto wait_vm = [&](int n) {
+    switch (n) {
+      case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+      case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+      case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+      case 12: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+      default: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+    }
+  };
   // Start of a pass: tiles 0 and 1 are on their way; wait for this wave's part of tile 0, meet the
   // other waves, request tile 2.
   auto first_arrival = [&]() {
@@ -325,26 +326,35 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   // 1 / (2 G) away from an integer, far more than the rounding of the float product
   const float inv_G = 1.0f / (float)G;
   auto div_G = [&](int r) { return (int)(((float)r + 0.5f) * inv_G); };
-  int my_parent = -1;
-  if (last_split && tid < M) my_parent = h_parent[(h_tree_shared ? 0 : n0) + tid];  // (one tree for all entries, or each its own)
-  bf16x8 qf[8];
+  // These loads are inline assembly like the tile loads: the compiler does not see the tile loads, so
+  // a load of its own would be waited for with vmcnt(0), i.e. together with every tile requested
+  // behind it.  Here the waits count the younger loads (wait_vm), and an empty asm statement that
+  // "writes" the registers keeps their uses behind the wait.  Lanes without a row of their own load
+  // a valid row (the last one; tree row 0) and zero it afterwards.
+  int my_parent;
+  {
+    const int32_t* src = h_parent + (h_tree_shared ? 0 : n0) + (tid < M ? tid : 0);  // (one tree for all entries, or each its own)
+    asm volatile("global_load_dword %0, %1, off" : "=v"(my_parent) : "v"(src) : "memory");
+  }
+  uintx4 qraw[8];
   int tree_row;
+  bool row_real;
   {
     const int r = row_base + col;
     const int rc = r < R ? r : R - 1;
     const int i = div_G(rc), gi = rc - i * G;
     tree_row = i;
-    const char* qrow = static_cast<const char*>(h_q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES;
+    row_real = r < R;
+    const char* qrow = static_cast<const char*>(h_q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES + half * 16;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[kk] = (r < R && wave_active) ? *reinterpret_cast<const bf16x8*>(qrow + (2 * kk + half) * 16) : zero8;
-    }
+    for (int kk = 0; kk < 8; ++kk)
+      asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qraw[kk]) : "v"(qrow), "n"(32 * kk) : "memory");
   }
-  TS(1);
   issue(0);
   if (n_tiles > 1) issue(1);
-  TS(2);
+  const int first_tile_loads = 2 * MF_LOADS * (n_tiles < 2 ? n_tiles : 2);
+  wait_vm(8 + first_tile_loads);  // the parent pointers are there (the eight Q loads and the tiles are younger)
+  asm volatile("" : "+v"(my_parent));
 
   // ---- ancestor bit table: bit j of row i's words is set iff tree row j is on the root path of i.
   // The parent pointers are staged in LDS and the paths are walked there.
@@ -365,10 +375,14 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
 
   // ---- Q fragments (B operand of the first product), pre-multiplied by scale * log2(e) so that
   // the scores come out of the MFMA in the log2 domain
-  const float c2 = h_scale * MF_LOG2E;
+  const float c2 = row_real ? h_scale * MF_LOG2E : 0.f;
+  wait_vm(first_tile_loads);  // the Q rows are there (the tiles are younger)
+  asm volatile("" : "+v"(qraw[0]), "+v"(qraw[1]), "+v"(qraw[2]), "+v"(qraw[3]), "+v"(qraw[4]), "+v"(qraw[5]),
+               "+v"(qraw[6]), "+v"(qraw[7]));
+  bf16x8 qf[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
-    const bf16x8 raw = qf[kk];
+    const bf16x8 raw = __builtin_bit_cast(bf16x8, qraw[kk]);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       floatx2 f = {(float)raw[2 * e] * c2, (float)raw[2 * e + 1] * c2};
@@ -552,9 +566,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const std::false_type NO{};
 
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the ancestor table is complete
-  TS(3);
   first_arrival();
-  TS(4);
   const int n_blocks = 2 * n_tiles;
 
   if (wave_active) {
@@ -576,7 +588,6 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     }
 #pragma unroll
     for (int kk = 0; kk < 2 * MF_AHEAD; ++kk) kf[kk] = ldk(blk_off(0, 1), kk);
-    TS(5);
     // ---- one trip per tile t (blocks 2t and 2t + 1, ring slot s = t % 4); the barrier in its
     // middle lets tile t + 1 in
     //   window 1: scores of 2t+1      | second half of 2t
@@ -609,9 +620,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
       trip(t + 2, 2, NO);
       trip(t + 3, 3, NO);
     }
-    TS(6);
     for (; t + 1 < n_tiles; ++t) trip(t, t % MF_NBUF, YES);
-    TS(7);
     {  // last tile: nothing follows its odd block
       const int s = t % MF_NBUF;
       win_qk(blk_off(s, 1), blk_off(s, 0), sB, sA, 1, pb);
@@ -623,7 +632,6 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
       win_pv(blk_off(s, 1), 0, pc, pb, sB, 0, pa, NO, NO);
     }
     l_sum = l0 + l1;
-    TS(8);
   } else {
     // no rows: this wave only moves tiles and meets the barriers
     for (int t = 0; t + 1 < n_tiles; ++t) next_arrival(t);
@@ -739,16 +747,6 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
       }
     }
   }
-#ifdef HS_TS
-  TS(9);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  TS(10);
-  if (tid == 0) {
-    const int wg = blockIdx.y * gridDim.x + blockIdx.x;
-    if (wg < 4096)
-      for (int i = 0; i < 16; ++i) dbg_ts[wg * 16 + i] = ts_[i];
-  }
-#endif
 }
 
 // `ev_start` / `ev_stop` (may be NULL): HIP events attached to this dispatch; the runtime stamps them
@@ -774,8 +772,3 @@ hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t str
 }
 
 }  // namespace hs
-#ifdef HS_TS
-extern "C" int hs_dbg_ts(unsigned long long* host, int n_wg) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(hs::dbg_ts), (size_t)n_wg * 16 * 8);
-}
-#endif
