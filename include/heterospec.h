@@ -140,6 +140,9 @@ hs_status hs_draft_entropy_topk_rows(const float* logits, int64_t row_stride, co
  *   out_offsets [B+1] packs the surviving rows; out_src [NN'] is each surviving row's LOCAL index in
  *   its candidate tree (ascending); out_parent [NN'] its parent as a LOCAL index among the surviving
  *   rows (-1 for the root).  out_src / out_parent must have room for NN entries.
+ *   The entries of out_src / out_parent past the last surviving row (NN' .. NN-1) are set to 0: rows
+ *   that hang off a root and repeat it, so that a consumer sized for a fixed node budget (a captured
+ *   graph, say) reads a valid tree even when fewer nodes survive.
  * logc[i] is the log-confidence of node i (ignored for roots).  An empty sequence (n = 0) emits nothing.
  */
 size_t hs_tree_prune_workspace(int32_t B, int32_t NN);

@@ -59,7 +59,7 @@ __device__ __forceinline__ void prune_sequence(
     bool copy_out, FP lc, int dcap, float th, int budget, int32_t* __restrict__ depth,
     float* __restrict__ cumlogp, uint8_t* __restrict__ keep, int32_t* __restrict__ ws_pos,
     int32_t* __restrict__ ws_count, int s, bool emit, int32_t* __restrict__ out_offsets,
-    int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent) {
+    int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent, int NN) {
   const int tid = threadIdx.x, lane = tid & 63;
   // depth: walk to the root
   int my_max = 0;
@@ -200,6 +200,11 @@ __device__ __forceinline__ void prune_sequence(
         out_parent[p] = (i == 0) ? -1 : nxt[par[i]];
       }
     }
+    // the unused tail of the output arrays: rows that hang off the root and repeat it
+    for (int i = red[0] + tid; i < NN; i += PR_THREADS) {
+      out_src[i] = 0;
+      out_parent[i] = 0;
+    }
   }
 }
 
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
     const int32_t* __restrict__ node_counts, const int32_t* __restrict__ d_max, const float* __restrict__ theta, const int32_t* __restrict__ max_nodes,
     int32_t* __restrict__ depth, float* __restrict__ cumlogp, uint8_t* __restrict__ keep,
     int32_t* __restrict__ ws_pos, int32_t* __restrict__ ws_count, int32_t* __restrict__ ws_flag,
-    int32_t* __restrict__ out_offsets, int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent) {
+    int32_t* __restrict__ out_offsets, int32_t* __restrict__ out_src, int32_t* __restrict__ out_parent, int NN) {
   __shared__ int l_par[PR_LDS_NODES];
   __shared__ int l_dep[PR_LDS_NODES];
   __shared__ float l_sum[PR_LDS_NODES];
@@ -228,6 +233,11 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
       ws_count[s] = 0;
       if (gridDim.x == 1) out_offsets[0] = out_offsets[1] = 0;
     }
+    if (gridDim.x == 1)
+      for (int i = tid; i < NN; i += PR_THREADS) {
+        out_src[i] = 0;
+        out_parent[i] = 0;
+      }
     return;
   }
   if (n <= PR_LDS_NODES) {
@@ -240,13 +250,13 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_select(
     }
     __syncthreads();
     prune_sequence(l_par, l_dep, l_sum, l_ok, l_new, l_keys, digit_hist, red, chunk_sum, n, o, true, l_logc, dcap, th, budget, depth, cumlogp, keep, ws_pos, ws_count, s,
-                   gridDim.x == 1, out_offsets, out_src, out_parent);
+                   gridDim.x == 1, out_offsets, out_src, out_parent, NN);
   } else {
     // very large trees: the output arrays and the workspace are the scratch (ws_pos is not written
     // before the last phase, so it can hold the budget flags meanwhile)
     prune_sequence(const_cast<int32_t*>(parent + o), depth + o, cumlogp + o, ws_flag + o, ws_pos + o, (unsigned long long*)nullptr, digit_hist, red,
                    chunk_sum, n, o, false, const_cast<float*>(logc + o), d_max[s], theta[s], max_nodes[s], depth, cumlogp,
-                   keep, ws_pos, ws_count, s, false, out_offsets, out_src, out_parent);
+                   keep, ws_pos, ws_count, s, false, out_offsets, out_src, out_parent, NN);
   }
 }
 
@@ -257,7 +267,7 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_emit(const int32_t* __rest
                                                            const int32_t* __restrict__ ws_count,
                                                            int32_t* __restrict__ out_offsets,
                                                            int32_t* __restrict__ out_src,
-                                                           int32_t* __restrict__ out_parent) {
+                                                           int32_t* __restrict__ out_parent, int NN) {
   __shared__ int red[PR_THREADS / 64];
   const int s = blockIdx.x, tid = threadIdx.x;
   int mine = 0;
@@ -276,6 +286,12 @@ __global__ __launch_bounds__(PR_THREADS) void k_prune_emit(const int32_t* __rest
       out_parent[base + p] = (i == 0) ? -1 : ws_pos[o + parent[o + i]];
     }
   }
+  // the unused tail of the output arrays (last workgroup): rows that hang off a root and repeat it
+  if (s == B - 1)
+    for (int i = base + ws_count[s] + tid; i < NN; i += PR_THREADS) {
+      out_src[i] = 0;
+      out_parent[i] = 0;
+    }
 }
 
 }  // namespace hs
@@ -286,22 +302,13 @@ extern "C" size_t hs_tree_prune_workspace(int32_t B, int32_t NN) {
          hs::align_up((size_t)B * sizeof(int32_t), 256);
 }
 
-extern "C" hs_status hs_tree_prune_counted(const int32_t* parent, const float* logc, const int32_t* node_offsets,
-                                           const int32_t* node_counts, int32_t B, int32_t NN, const int32_t* d_max,
-                                           const float* theta, const int32_t* max_nodes, int32_t* depth,
-                                           float* cumlogp, uint8_t* keep, int32_t* out_offsets, int32_t* out_src,
-                                           int32_t* out_parent, void* workspace, size_t workspace_bytes,
-                                           hs_stream stream) {
-  hs::clear_error();
-  HS_REQUIRE(B >= 0 && NN >= 0, HS_ERR_SHAPE, "hs_tree_prune: B=%d NN=%d", B, NN);
-  if (B == 0) return HS_OK;
-  HS_REQUIRE(node_offsets && d_max && theta && max_nodes && out_offsets, HS_ERR_NULL, "hs_tree_prune: NULL argument");
-  HS_REQUIRE(NN == 0 || (parent && logc && depth && cumlogp && keep && out_src && out_parent), HS_ERR_NULL,
-             "hs_tree_prune: NULL node array");
-  const size_t need = hs_tree_prune_workspace(B, NN);
-  HS_REQUIRE(workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0,
-             HS_ERR_WORKSPACE, "hs_tree_prune: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
-             workspace_bytes);
+// Validation and the two launches; `workspace` is the caller's buffer or this library's static one.
+static hs_status prune_impl(const char* who, const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                            const int32_t* node_counts, int32_t B, int32_t NN, const int32_t* d_max,
+                            const float* theta, const int32_t* max_nodes, int32_t* depth, float* cumlogp,
+                            uint8_t* keep, int32_t* out_offsets, int32_t* out_src, int32_t* out_parent,
+                            void* workspace, hs_stream stream) {
+  (void)who;
   hs::Carver c(workspace);
   int32_t* ws_pos = c.take<int32_t>(NN > 0 ? NN : 1);
   int32_t* ws_flag = c.take<int32_t>(NN > 0 ? NN : 1);
@@ -309,14 +316,37 @@ extern "C" hs_status hs_tree_prune_counted(const int32_t* parent, const float* l
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(hs::k_prune_select, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, logc, node_offsets, node_counts,
                      d_max, theta, max_nodes, depth, cumlogp, keep, ws_pos, ws_count, ws_flag, out_offsets, out_src,
-                     out_parent);
+                     out_parent, NN);
   hs_status r = hs::launch_status("prune select");
   if (r != HS_OK) return r;
   // a single tree that fits LDS was emitted by the selecting workgroup itself
   if (B == 1 && NN <= hs::PR_LDS_NODES) return r;
   hipLaunchKernelGGL(hs::k_prune_emit, dim3(B), dim3(hs::PR_THREADS), 0, st, parent, node_offsets, node_counts, B,
-                     ws_pos, ws_count, out_offsets, out_src, out_parent);
+                     ws_pos, ws_count, out_offsets, out_src, out_parent, NN);
   return hs::launch_status("prune emit");
+}
+
+#define HS_PRUNE_CHECK_ARGS(who)                                                                                      \
+  HS_REQUIRE(B >= 0 && NN >= 0, HS_ERR_SHAPE, who ": B=%d NN=%d", B, NN);                                             \
+  if (B == 0) return HS_OK;                                                                                           \
+  HS_REQUIRE(node_offsets && d_max && theta && max_nodes && out_offsets, HS_ERR_NULL, who ": NULL argument");         \
+  HS_REQUIRE(NN == 0 || (parent && logc && depth && cumlogp && keep && out_src && out_parent), HS_ERR_NULL,           \
+             who ": NULL node array")
+
+extern "C" hs_status hs_tree_prune_counted(const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                                           const int32_t* node_counts, int32_t B, int32_t NN, const int32_t* d_max,
+                                           const float* theta, const int32_t* max_nodes, int32_t* depth,
+                                           float* cumlogp, uint8_t* keep, int32_t* out_offsets, int32_t* out_src,
+                                           int32_t* out_parent, void* workspace, size_t workspace_bytes,
+                                           hs_stream stream) {
+  hs::clear_error();
+  HS_PRUNE_CHECK_ARGS("hs_tree_prune");
+  const size_t need = hs_tree_prune_workspace(B, NN);
+  HS_REQUIRE(workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0,
+             HS_ERR_WORKSPACE, "hs_tree_prune: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+             workspace_bytes);
+  return prune_impl("hs_tree_prune", parent, logc, node_offsets, node_counts, B, NN, d_max, theta, max_nodes, depth,
+                    cumlogp, keep, out_offsets, out_src, out_parent, workspace, stream);
 }
 
 extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, const int32_t* node_offsets, int32_t B,
@@ -327,3 +357,4 @@ extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, con
   return hs_tree_prune_counted(parent, logc, node_offsets, nullptr, B, NN, d_max, theta, max_nodes, depth, cumlogp,
                                keep, out_offsets, out_src, out_parent, workspace, workspace_bytes, stream);
 }
+

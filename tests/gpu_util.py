@@ -40,6 +40,8 @@ def run_prune(pin):
                            dev(pin["theta"], torch.float32), dev(pin["max_nodes"], torch.int32))
     r = {k: host(v) for k, v in out.items()}
     n = int(r["out_offsets"][-1])
+    # past the surviving rows the two arrays are padded with rows that hang off a root and repeat it
+    r["tail_is_padded"] = bool((r["out_src"][n:] == 0).all() and (r["out_parent"][n:] == 0).all())
     r["out_src"], r["out_parent"] = r["out_src"][:n], r["out_parent"][:n]
     return r
 

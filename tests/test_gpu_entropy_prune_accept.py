@@ -108,6 +108,7 @@ def _prune_equal(got, want):
     for k in ("depth", "keep", "out_offsets", "out_src", "out_parent"):
         assert np.array_equal(got[k], want[k]), k
     assert np.array_equal(got["cumlogp"].view(np.uint32), want["cumlogp"].view(np.uint32))   # bit for bit
+    assert got["tail_is_padded"], "out_src / out_parent past the surviving rows must be zero"
 
 
 def test_prune_workload1_and_sweeps(G):
