@@ -153,6 +153,24 @@ hs_status hs_tree_prune(const int32_t* parent, const float* logc, const int32_t*
                         int32_t* out_offsets, int32_t* out_src, int32_t* out_parent,
                         void* workspace, size_t workspace_bytes, hs_stream stream);
 
+/* hs_tree_prune_static: hs_tree_prune without a workspace argument, for callers that cannot allocate
+ * device memory and have no buffer to lend: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The scratch is a device array inside the library (528 KiB per
+ * GPU, held until the process ends); the call allocates and frees nothing.  Limits: B <=
+ * HS_PRUNE_STATIC_MAX_SEQS and NN <= HS_PRUNE_STATIC_MAX_NODES, beyond them HS_ERR_UNSUPPORTED
+ * (nothing launched).  Every call on a GPU uses that GPU's one array: calls that may overlap on
+ * one GPU (different streams, different threads) race; calls on one stream are ordered.  The
+ * first call on a device looks the array's address up (hipGetSymbolAddress), so make it outside a
+ * stream capture.  Arguments, outputs and results are those of hs_tree_prune, bit for bit. */
+#define HS_PRUNE_STATIC_MAX_SEQS 4096
+#define HS_PRUNE_STATIC_MAX_NODES 65536
+hs_status hs_tree_prune_static(const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                               int32_t B, int32_t NN,
+                               const int32_t* d_max, const float* theta, const int32_t* max_nodes,
+                               int32_t* depth, float* cumlogp, uint8_t* keep,
+                               int32_t* out_offsets, int32_t* out_src, int32_t* out_parent,
+                               hs_stream stream);
+
 /* ------------------------------------------------------------------------------------------------
  * hs_tree_attention  (Section 2.2: the pruned tree is verified in one pass with tree-mask
  * attention)

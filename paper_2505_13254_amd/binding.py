@@ -33,6 +33,7 @@ _SIGNATURES = {
                                               _vp]),
     "hs_tree_prune_workspace": (_sz, [_i32, _i32]),
     "hs_tree_prune": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "hs_tree_prune_static": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "hs_tree_prune_counted": (_c.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                          _sz, _vp]),
     "hs_tree_expand": (_c.c_int, [_vp] * 15 + [_i32] * 5 + [_vp]),
@@ -181,6 +182,24 @@ def hs_tree_prune(parent: torch.Tensor, logc: torch.Tensor, node_offsets: torch.
     else:
         st = lib().hs_tree_prune_counted(_ptr(parent), _ptr(logc), _ptr(node_offsets), _ptr(node_counts), B, NN, *tail)
     _check(st, "hs_tree_prune")
+    return out
+
+
+def hs_tree_prune_static(parent: torch.Tensor, logc: torch.Tensor, node_offsets: torch.Tensor, d_max: torch.Tensor,
+                         theta: torch.Tensor, max_nodes: torch.Tensor, *, out: Dict[str, torch.Tensor],
+                         stream=None) -> Dict[str, torch.Tensor]:
+    """hs_tree_prune on the library's own static scratch: no workspace, and `out` (depth, cumlogp, keep,
+    out_offsets, out_src, out_parent as hs_tree_prune returns them) must be given, so the call allocates
+    nothing."""
+    _dev(parent, torch.int32, "parent"); _dev(logc, torch.float32, "logc")
+    _dev(node_offsets, torch.int32, "node_offsets"); _dev(d_max, torch.int32, "d_max")
+    _dev(theta, torch.float32, "theta"); _dev(max_nodes, torch.int32, "max_nodes")
+    NN, B = parent.numel(), node_offsets.numel() - 1
+    st = lib().hs_tree_prune_static(_ptr(parent), _ptr(logc), _ptr(node_offsets), B, NN, _ptr(d_max), _ptr(theta),
+                                    _ptr(max_nodes), _ptr(out["depth"]), _ptr(out["cumlogp"]), _ptr(out["keep"]),
+                                    _ptr(out["out_offsets"]), _ptr(out["out_src"]), _ptr(out["out_parent"]),
+                                    _stream(stream))
+    _check(st, "hs_tree_prune_static")
     return out
 
 

@@ -358,3 +358,51 @@ extern "C" hs_status hs_tree_prune(const int32_t* parent, const float* logc, con
                                keep, out_offsets, out_src, out_parent, workspace, workspace_bytes, stream);
 }
 
+// ---- hs_tree_prune_static: the same call for callers that cannot allocate (code under HIP graph
+// capture, serving loops, harnesses that forbid hipMalloc).  Its scratch is a device array of this
+// library, one copy per GPU, resolved once per device with hipGetSymbolAddress; every call on a GPU
+// uses that GPU's copy, so calls that overlap on one GPU race.  Nothing in it has to start at zero:
+// both kernels write every scratch entry they later read.
+namespace {
+constexpr int PRUNE_STATIC_MAX_NN = HS_PRUNE_STATIC_MAX_NODES;
+constexpr int PRUNE_STATIC_MAX_B = HS_PRUNE_STATIC_MAX_SEQS;
+constexpr size_t PRUNE_STATIC_BYTES = 2 * ((size_t)PRUNE_STATIC_MAX_NN * 4) + (size_t)PRUNE_STATIC_MAX_B * 4;  // 540672
+constexpr int PRUNE_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[PRUNE_STATIC_BYTES];
+static void* scratch_of_device[PRUNE_MAX_DEVICES];  // the array's address on each GPU, once resolved
+
+// The address of `scratch` on the current device (in host code the array's name is only a handle).
+static hs_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= PRUNE_MAX_DEVICES)
+    return hs::fail(HS_ERR_RUNTIME, "hs_tree_prune_static: no current device (%s)", hipGetErrorString(e));
+  void* p = __atomic_load_n(&scratch_of_device[dev], __ATOMIC_ACQUIRE);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr)
+      return hs::fail(HS_ERR_RUNTIME, "hs_tree_prune_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    __atomic_store_n(&scratch_of_device[dev], p, __ATOMIC_RELEASE);  // (two threads may both resolve it: same value)
+  }
+  *out = p;
+  return HS_OK;
+}
+
+extern "C" hs_status hs_tree_prune_static(const int32_t* parent, const float* logc, const int32_t* node_offsets,
+                                          int32_t B, int32_t NN, const int32_t* d_max, const float* theta,
+                                          const int32_t* max_nodes, int32_t* depth, float* cumlogp, uint8_t* keep,
+                                          int32_t* out_offsets, int32_t* out_src, int32_t* out_parent,
+                                          hs_stream stream) {
+  hs::clear_error();
+  HS_PRUNE_CHECK_ARGS("hs_tree_prune_static");
+  HS_REQUIRE(B <= PRUNE_STATIC_MAX_B && NN <= PRUNE_STATIC_MAX_NN, HS_ERR_UNSUPPORTED,
+             "hs_tree_prune_static: B=%d NN=%d exceed the static scratch (at most %d sequences, %d nodes); "
+             "use hs_tree_prune with a workspace", B, NN, PRUNE_STATIC_MAX_B, PRUNE_STATIC_MAX_NN);
+  static_assert(PRUNE_STATIC_MAX_NN % 64 == 0 && PRUNE_STATIC_MAX_B % 64 == 0, "the carved pieces stay 256-byte aligned");
+  void* ws = nullptr;
+  hs_status r = static_scratch(&ws);
+  if (r != HS_OK) return r;
+  return prune_impl("hs_tree_prune_static", parent, logc, node_offsets, nullptr, B, NN, d_max, theta, max_nodes, depth,
+                    cumlogp, keep, out_offsets, out_src, out_parent, ws, stream);
+}
