@@ -333,8 +333,8 @@ hs_status hs_tree_expand(int32_t* parent, int32_t* token, float* logc, float* cu
 
 /* ------------------------------------------------------------------------------------------------
  * hs_adaptive_control  (Section 4.1, Eq. 1: Phi(P) = sum over the positions of path P of the
- * Top-K entropy of the draft distribution at that position, evaluated on the operational path P*,
- * the candidate path with the highest final-token confidence; Section 4.2: the trained decision
+ * Top-K entropy of the draft distribution at that position, evaluated on the operational path P*
+ * (defined below); Section 4.2: the trained decision
  * tree partitions Phi into entropy bins B_0 .. B_{n-1}, lowest entropy first; Section 4.3:
  * d'(B_i) = d_base + Delta(B_i), N'(B_i) = gamma_i * N_default + Delta(B_i), Delta(B_i) = alpha - i
  * for the low-entropy bins, nothing changes for the others.)
@@ -362,9 +362,16 @@ hs_status hs_adaptive_control(const int32_t* parent, const float* logc, const fl
                               float* phi, int32_t* pstar, int32_t* bin, int32_t* d_prime,
                               int32_t* n_prime, hs_stream stream);
 
+/* hs_adaptive_policy: what hs_adaptive_control decides for entropy bin `bin` (Section 4.3: Delta, d', N'
+ * as defined above), computed on the host with the kernel's own formula and written to the two HOST
+ * integers.  For callers that prepare one set of buffers or one captured graph per bin (Section 4.3,
+ * Dynamic Computational Adaptation) and need each bin's shape beforehand.  No device work. */
+hs_status hs_adaptive_policy(int32_t bin, const float* host_gamma, int32_t n_low, int32_t alpha,
+                             int32_t d_base, int32_t n_default,
+                             int32_t* host_d_prime, int32_t* host_n_prime);
+
 /* ------------------------------------------------------------------------------------------------
- * hs_kv_commit  (Section 2.1: accepted draft tokens become part of the context, later drafts are
- * discarded, and decoding resumes behind the last accepted token)
+ * hs_kv_commit  (Section 2.1: what an accepted path means for the next step's context)
  *
  * For each sequence with a tree, the K/V rows of the tree's root (the last committed token, whose
  * K/V is not in the cache yet) and of the accept_len[s] accepted rows accept_path[s, 0..] (local

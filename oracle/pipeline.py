@@ -215,7 +215,7 @@ def safe_uniforms(step, mode, rel=1e-4, cdf_abs=1e-5, tries=64):
 
 
 # ----------------------------------------------------------------------------- the adaptive step
-def adaptive_step(w, seed, edges, gamma, alpha, logp_dtype=np.float32):
+def adaptive_step(w, seed, edges, gamma, alpha, logp_dtype=np.float32, pstar_mode=0):
     """The whole adaptive step of a single-sequence expansion workload with the checker: base
     drafting to w.max_depth levels, complexity decision, extended drafting, pruning to the decided
     budget, greedy accept walk (Sections 4.1 - 4.3 around the Section 2.2 tree).  Confidences are
@@ -234,7 +234,7 @@ def adaptive_step(w, seed, edges, gamma, alpha, logp_dtype=np.float32):
     for _ in range(d_base):
         level()
     n = len(st["parent"])
-    ctl = adaptive_control(st["parent"], st["logc"], st["ent"], [0, n], edges, gamma, alpha, d_base, w.max_nodes, 0)
+    ctl = adaptive_control(st["parent"], st["logc"], st["ent"], [0, n], edges, gamma, alpha, d_base, w.max_nodes, pstar_mode)
     d_prime, n_prime = int(ctl["d_prime"][0]), int(ctl["n_prime"][0])
     for _ in range(d_prime - d_base):
         level()

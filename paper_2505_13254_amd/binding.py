@@ -39,6 +39,7 @@ _SIGNATURES = {
     "hs_tree_expand": (_c.c_int, [_vp] * 15 + [_i32] * 5 + [_vp]),
     "hs_adaptive_control": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i32, _vp, _i32, _i32, _i32, _i32,
                                        _c.c_int, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "hs_adaptive_policy": (_c.c_int, [_i32, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
     "hs_tree_attention_workspace": (_sz, [_i32, _i32, _i64, _i32, _i32, _i32, _c.c_int]),
     "hs_tree_attention": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                      _c.c_int, _f32, _vp, _vp, _vp, _sz, _vp]),
@@ -263,6 +264,16 @@ def hs_adaptive_control(parent, logc, ent, node_offsets, node_counts, bin_edges,
                                    _ptr(out["bin"]), _ptr(out["d_prime"]), _ptr(out["n_prime"]), _stream(stream))
     _check(st, "hs_adaptive_control")
     return out
+
+
+def hs_adaptive_policy(bin: int, gamma, alpha: int, d_base: int, n_default: int):
+    """(d_prime, n_prime) of entropy bin `bin`, from the library's own formula (host arithmetic only)."""
+    gam = (_f32 * max(1, len(gamma)))(*[float(x) for x in gamma])
+    dp, np_ = _i32(0), _i32(0)
+    st = lib().hs_adaptive_policy(int(bin), _c.cast(gam, _vp), len(gamma), int(alpha), int(d_base), int(n_default),
+                                  _c.byref(dp), _c.byref(np_))
+    _check(st, "hs_adaptive_policy")
+    return int(dp.value), int(np_.value)
 
 
 def _dtype_code(t: torch.Tensor) -> int:

@@ -36,6 +36,19 @@ struct ControlArgs {
   int32_t* n_prime;
 };
 
+// What bin b means (Section 4.3): depth extension and node budget.  One definition for the kernel and
+// for the host query hs_adaptive_policy.
+__host__ __device__ inline void bin_policy(int b, int n_low, int alpha, int d_base, int n_default, const float* gamma,
+                                           int* d_prime, int* n_prime) {
+  int delta = 0, budget = n_default;
+  if (b < n_low) {
+    delta = alpha - b > 0 ? alpha - b : 0;
+    budget = (int)floor((double)gamma[b] * (double)n_default + 0.5) + delta;
+  }
+  *d_prime = d_base + delta;
+  *n_prime = budget;
+}
+
 // (value, row) as one key: larger key = larger value, then lower row; never 0 for a real node.
 __device__ __forceinline__ unsigned long long control_key(float v, int i) {
   unsigned u = __builtin_bit_cast(unsigned, v);
@@ -111,17 +124,13 @@ __device__ __forceinline__ void control_sequence(const ControlArgs& a, int s, in
   if (lane != 0) return;
   int b = 0;
   for (int e = 0; e < a.n_edges; ++e) b += acc >= a.edges[e] ? 1 : 0;
-  const bool low = b < a.n_low;
-  int delta = 0, budget = a.n_default;
-  if (low) {
-    delta = a.alpha - b > 0 ? a.alpha - b : 0;
-    budget = (int)floor((double)a.gamma[b] * (double)a.n_default + 0.5) + delta;
-  }
+  int dp, np_;
+  bin_policy(b, a.n_low, a.alpha, a.d_base, a.n_default, a.gamma, &dp, &np_);
   a.phi[s] = acc;
   a.pstar[s] = p;
   a.bin[s] = b;
-  a.d_prime[s] = a.d_base + delta;
-  a.n_prime[s] = budget;
+  a.d_prime[s] = dp;
+  a.n_prime[s] = np_;
 }
 
 __global__ __launch_bounds__(CTL_THREADS) void k_adaptive_control(ControlArgs a) {
@@ -189,4 +198,18 @@ extern "C" hs_status hs_adaptive_control(const int32_t* parent, const float* log
   a.phi = phi; a.pstar = pstar; a.bin = bin; a.d_prime = d_prime; a.n_prime = n_prime;
   hipLaunchKernelGGL(k_adaptive_control, dim3((unsigned)B), dim3(CTL_THREADS), 0, static_cast<hipStream_t>(stream), a);
   return launch_status("adaptive control");
+}
+
+extern "C" hs_status hs_adaptive_policy(int32_t bin, const float* host_gamma, int32_t n_low, int32_t alpha,
+                                        int32_t d_base, int32_t n_default, int32_t* host_d_prime,
+                                        int32_t* host_n_prime) {
+  clear_error();
+  HS_REQUIRE(bin >= 0 && n_low >= 0 && n_low <= CTL_MAX_LOW && d_base >= 0 && n_default >= 0, HS_ERR_SHAPE,
+             "hs_adaptive_policy: bin=%d n_low=%d d_base=%d n_default=%d", bin, n_low, d_base, n_default);
+  HS_REQUIRE(host_d_prime && host_n_prime && (n_low == 0 || host_gamma), HS_ERR_NULL, "hs_adaptive_policy: NULL argument");
+  int dp, np_;
+  bin_policy(bin, n_low, alpha, d_base, n_default, host_gamma, &dp, &np_);
+  *host_d_prime = dp;
+  *host_n_prime = np_;
+  return HS_OK;
 }

@@ -1,5 +1,5 @@
-// hs_kv_commit: the accepted path joins the KV cache (Section 2.1: accepted tokens become part of
-// the context, later drafts are discarded, decoding resumes behind the last accepted token).
+// hs_kv_commit: the accepted path joins the KV cache (Section 2.1: what an accepted path means for
+// the context of the next step; rows of rejected nodes go nowhere).
 //
 // Per sequence the K/V rows of the tree's root and of the accepted rows, in path order, are copied
 // behind the used part of the sequence's cache region and the used length grows by their number.

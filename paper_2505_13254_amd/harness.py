@@ -299,17 +299,26 @@ class AdaptiveStep:
     n_default: int
     edges: List[float]
     gamma: List[float]
+    pstar_mode: int = 0
     t: Dict[str, object] = field(default_factory=dict)
     host: Dict[str, object] = field(default_factory=dict)
     graphs: Dict[object, object] = field(default_factory=dict)
 
-    # ---- what the bins mean (Section 4.3), on the host: which graph to replay
+    # ---- what a bin means (Section 4.3): asked of the library, which holds the formula
     def decision(self, b: int):
-        low = b < len(self.gamma)
-        delta = max(self.alpha - b, 0) if low else 0
-        n = (int(np.floor(np.float64(np.float32(self.gamma[b])) * self.n_default + 0.5)) + delta) if low \
-            else self.n_default
-        return self.d_base + delta, n
+        return hs.hs_adaptive_policy(b, self.gamma, self.alpha, self.d_base, self.n_default)
+
+    def set_temperature(self, T: float):
+        """Swaps the draft model's output rows for those of draft temperature T (a power of two, so that
+        the scaling is exact): softmax(x / T) of the stored rows is what the drafting calls then see,
+        with their own temperature argument, which a captured graph has baked in, left at the
+        workload's.  Stands in for the next step's draft distributions."""
+        m, e = np.frexp(T)
+        if m != 0.5 or T <= 0:
+            raise ValueError("T must be a power of two")
+        t = self.t
+        torch.mul(t["draft_base"], 1.0 / T, out=t["draft_all"])
+        t["x_root"].copy_(t["draft_all"][:1].expand_as(t["x_root"]))
 
     # ---- pieces, each a few library calls on device-resident data
     def _level(self, first: bool):
@@ -331,7 +340,7 @@ class AdaptiveStep:
             self._level(lvl == 0)
         st = t["state"]
         hs.hs_adaptive_control(st["parent"], st["logc"], st["ent"], st["node_offsets"], st["n_nodes"], self.edges,
-                               self.gamma, self.alpha, self.d_base, self.n_default, 0, out=t["ctl"])
+                               self.gamma, self.alpha, self.d_base, self.n_default, self.pstar_mode, out=t["ctl"])
 
     def run_verify(self, b: int):
         """Extended drafting for bin b, pruning to the decided budget, attention on all layers, accept."""
@@ -393,16 +402,17 @@ class AdaptiveStep:
         return b
 
     def result(self, b: int):
-        d_prime, n_prime = self.decision(b)
-        a = self.t["attn"][n_prime + 1]
         torch.cuda.synchronize()
+        ctl = self.t["ctl"]
+        d_prime, n_prime = int(ctl["d_prime"].cpu()[0]), int(ctl["n_prime"].cpu()[0])   # the device's decision
+        a = self.t["attn"][n_prime + 1]
         return dict(bin=b, d_prime=d_prime, n_prime=n_prime,
                     accept_len=int(a["s4_out"]["accept_len"].cpu()[0]),
                     bonus_token=int(a["s4_out"]["bonus_token"].cpu()[0]))
 
 
 def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, edges=None, gamma=(0.3, 0.6, 1.0),
-                   alpha: Optional[int] = None, device="cuda:0") -> AdaptiveStep:
+                   alpha: Optional[int] = None, device="cuda:0", pstar_mode: int = 0) -> AdaptiveStep:
     """Single-sequence workloads grown by Top-K expansion (the 8B shape).  edges: the seven bin
     boundaries of the eight entropy bins (synthetic: the paper prints none)."""
     if w.B != 1 or w.tree != "expand":
@@ -412,7 +422,7 @@ def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, e
     alpha = alpha if alpha is not None else -(-d_base // 2)          # ceil(depth / 2), Section 5
     edges = list(edges) if edges is not None else [0.5 * d_base * x for x in (0.2, 0.4, 0.6, 0.8, 1.0, 1.3, 1.7)]
     st = AdaptiveStep(w=w, layers=layers, d_base=d_base, alpha=alpha, n_default=w.max_nodes, edges=edges,
-                      gamma=list(gamma))
+                      gamma=list(gamma), pstar_mode=pstar_mode)
     t, h = st.t, st.host
     cap = 1 + K + (d_base + alpha - 1) * F * K
     h.update(cap=cap, scale=1.0 / float(np.sqrt(w.D)))
@@ -424,6 +434,7 @@ def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, e
         ids = range(i0, min(i0 + 64, cap))
         t["draft_all"][i0:i0 + len(ids)] = _dev(W.logits_rows(w, seed, "draft", 0, ids), device=device)
         t["target_all"][i0:i0 + len(ids)] = _dev(W.logits_rows(w, seed, "target", 0, ids), device=device)
+    t["draft_base"] = t["draft_all"].clone()          # the rows as generated (set_temperature rescales from them)
     t["x_root"] = t["draft_all"][:1].repeat(F, 1).contiguous()
     t["s1_out"] = dict(topk_idx=torch.empty((F, K), **i32),
                        topk_logp=torch.empty((F, K), dtype=torch.float32, device=device),

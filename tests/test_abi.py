@@ -116,3 +116,20 @@ def test_accept_workspace_depends_on_the_mode(lib):
     d = ctypes.c_void_p(256)
     assert va(d, d, 128256, d, d, d, 1, 61, 128256, 1, 1.0, d, 6, d, d, d, d, greedy, None) == 4
     assert va(d, d, 128256, d, d, d, 1, 61, 128256, 0, 1.0, d, 6, d, d, d, d, greedy - 256, None) == 4
+
+
+def test_adaptive_policy_on_the_host_matches_the_worked_table(lib):
+    """hs_adaptive_policy (host arithmetic only) against the hand-worked Section 4.3 table of the figure example."""
+    f = lib.hs_adaptive_policy
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_int32] * 4 + [ctypes.c_void_p, ctypes.c_void_p]
+    gamma = (ctypes.c_float * 3)(0.3, 0.6, 1.0)
+    rows = [tuple(int(x) for x in line.split()) for line in
+            open(os.path.join(ROOT, "tests", "golden", "control_figure_example.txt")) if line[0] != "#"]
+    assert len(rows) == 8
+    for b, _delta, dp, npr in rows:
+        got_d, got_n = ctypes.c_int32(-1), ctypes.c_int32(-1)
+        assert f(b, ctypes.cast(gamma, ctypes.c_void_p), 3, 3, 5, 20, ctypes.byref(got_d), ctypes.byref(got_n)) == 0
+        assert (got_d.value, got_n.value) == (dp, npr), b
+    assert f(-1, ctypes.cast(gamma, ctypes.c_void_p), 3, 3, 5, 20, ctypes.byref(got_d), ctypes.byref(got_n)) == 2
+    assert f(0, None, 3, 3, 5, 20, ctypes.byref(got_d), ctypes.byref(got_n)) == 1
