@@ -200,14 +200,20 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
     variant "hot":    "peaky" with planted scores of 120, 135, 150, ... instead of 8: exp() of the
                       gap to the other scores overflows float32, so an implementation must track
                       the running maximum to get these rows right.
+    variants "unit_v", "peaky_v": "unit" / "peaky" with V drawn N(0,1) as well, so that outputs are
+                      of order one and an absolute tolerance of a few hundredths means something.
     """
     D = w.D
+    v_unit = variant.endswith("_v")
+    if v_unit:
+        variant = variant[:-2]
     sc = 1.0 / np.sqrt(D) if variant == "config" else 1.0
+    sv = 1.0 if v_unit else 1.0 / np.sqrt(D)
     q = rng.normal(_key(w, seed, _T_Q, s), M * w.Hq * D).reshape(M, w.Hq, D) * sc
     kp = rng.normal(_key(w, seed, _T_KP, s), L * w.Hkv * D).reshape(L, w.Hkv, D) * sc
-    vp = rng.normal(_key(w, seed, _T_VP, s), L * w.Hkv * D).reshape(L, w.Hkv, D) / np.sqrt(D)
+    vp = rng.normal(_key(w, seed, _T_VP, s), L * w.Hkv * D).reshape(L, w.Hkv, D) * sv
     kt = rng.normal(_key(w, seed, _T_KT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) * sc
-    vt = rng.normal(_key(w, seed, _T_VT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) / np.sqrt(D)
+    vt = rng.normal(_key(w, seed, _T_VT, s), M * w.Hkv * D).reshape(M, w.Hkv, D) * sv
     if variant in ("peaky", "hot") and M > 0:
         G = w.Hq // w.Hkv
         picks = rng.randint(_key(w, seed, _T_PLANT, s), 4 * 8, 0, 1 << 30).reshape(8, 4)

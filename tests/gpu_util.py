@@ -71,3 +71,47 @@ def entropy_err(got, want):
     tolerance with an absolute floor); a value <= 1 passes."""
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
     return float(np.max(np.abs(got - want) / (1e-5 * np.maximum(np.abs(want), 1e-3))))
+
+
+BF16_U = 2.0 ** -8      # unit roundoff of bfloat16 (8 significant bits, round to nearest)
+
+
+def attention_error_bound(step, want_o):
+    """Element-wise bound on |kernel output - exact output| of the bfloat16 attention kernel, derived from
+    its arithmetic (what is rounded where), with u = 2^-8:
+
+      * Q is multiplied by scale * log2(e) and rounded to bfloat16 once more, so a score moves by at most
+        delta = u * scale * max_j sum_d |q_d k_jd| (natural-log units, over the keys the row sees), and every
+        softmax weight by a factor within exp(+-2 delta);
+      * a weight is rounded to bfloat16 for the second product (relative u) while the denominator sums
+        the unrounded weights;
+      * the result is rounded to bfloat16 once (relative u);
+      * float32 accumulation of up to a few 10^4 terms: relative 5e-5 (generous).
+
+    With o the exact output and A = sum_j w_j |v_j| (the exact weights on |V|):
+        |error| <= u |o| + ((1 + u) exp(2 delta) - 1 + 5e-5) A
+    A comes from the checker run on |V|; delta from |Q| |K|^T over the visible keys."""
+    from oracle import tree_attention
+    from oracle.tree_attention import _widen, ancestor_mask
+    q, kp, kt = _widen(step["q"]), _widen(step["k_prefix"]), _widen(step["k_tree"])
+    absv_p, absv_t = np.abs(_widen(step["v_prefix"])), np.abs(_widen(step["v_tree"]))
+    A, _ = tree_attention(step["q"], step["k_prefix"], absv_p, step["k_tree"], absv_t, step["parent"],
+                          step["node_offsets"], step["prefix_offsets"], step["scale"])
+    NN, Hq, D = q.shape
+    G = Hq // kt.shape[1]
+    no, po = step["node_offsets"], step["prefix_offsets"]
+    delta = np.zeros((NN, Hq))
+    for s in range(len(no) - 1):
+        n0, n1, p0, p1 = int(no[s]), int(no[s + 1]), int(po[s]), int(po[s + 1])
+        if n1 == n0:
+            continue
+        anc = ancestor_mask(np.asarray(step["parent"][n0:n1]))
+        for h in range(Hq):
+            g = h // G
+            aq = np.abs(q[n0:n1, h])
+            d = np.where(anc, aq @ np.abs(kt[n0:n1, g]).T, 0.0).max(axis=1)
+            if p1 > p0:
+                d = np.maximum(d, (aq @ np.abs(kp[p0:p1, g]).T).max(axis=1))
+            delta[n0:n1, h] = BF16_U * float(step["scale"]) * d
+    grow = (1.0 + BF16_U) * np.exp(2.0 * delta) - 1.0 + 5e-5
+    return BF16_U * np.abs(want_o) + grow[:, :, None] * A + 1e-7

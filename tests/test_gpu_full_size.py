@@ -19,6 +19,12 @@ def H():
     return harness
 
 
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
 def _np(t):
     torch.cuda.synchronize()
     if t.dtype == torch.bfloat16:
@@ -107,6 +113,38 @@ def test_workload5_ragged_batch(H):
     assert len(sizes) == 16 and sizes.min() >= 2 and sizes.max() <= 129
     res = _check_step(st, np.random.RandomState(3), n_rows=4, n_heads=5)
     assert res["accept_len"].shape == (16,)
+
+
+@pytest.mark.parametrize("variant", ["peaky", "unit"])
+def test_workload5_ragged_launch_with_sharp_scores(H, G, variant):
+    """The batched workload's own launch (16 sequences, prefixes of 512 .. 16384 tokens, ragged trees, key
+    splits merged by the combine kernel, row groups beyond 256 rows) on inputs whose softmax is far from
+    uniform: scores of order one, and planted keys near the end of the prefix and among the ancestors.
+    Every head of three sequences is compared: the longest prefix, the shortest, the largest tree."""
+    w = W.WORKLOADS[5]
+    st = H.build_step(w, 0, layers=1, accept_mode=0)
+    t, h = st.t, st.host
+    no, po = h["attn_node_offsets"].numpy(), h["attn_prefix_offsets"].numpy()
+    par = h["out_parent"]
+    B = len(no) - 1
+    parts = [W.attention_inputs(w, 1, s, int(po[s + 1] - po[s]), int(no[s + 1] - no[s]), variant,
+                                parent=par[no[s]:no[s + 1]]) for s in range(B)]
+    for i, name in enumerate(("q", "k_prefix", "v_prefix", "k_tree", "v_tree")):
+        t[name].copy_(G.dev_store(np.concatenate([p[i] for p in parts], axis=0)))
+    t["o"].zero_()
+    st.stage3()
+    o = G.host(t["o"])
+    Ls, Ms = np.diff(po), np.diff(no)
+    assert Ms.max() * (w.Hq // w.Hkv) > 256 and Ls.max() > 8 * 1024     # several row groups, several key splits
+    for s in sorted({int(np.argmax(Ls)), int(np.argmin(Ls)), int(np.argmax(Ms))}):
+        q, kp, vp, kt, vt = parts[s]
+        sub = dict(q=q, k_prefix=kp, v_prefix=vp, k_tree=kt, v_tree=vt, parent=par[no[s]:no[s + 1]],
+                   node_offsets=np.asarray([0, Ms[s]]), prefix_offsets=np.asarray([0, Ls[s]]), scale=h["scale"])
+        want, _ = tree_attention(q, kp, vp, kt, vt, sub["parent"], sub["node_offsets"], sub["prefix_offsets"], h["scale"])
+        diff = np.abs(o[no[s]:no[s + 1]].astype(np.float64) - want)
+        assert diff.max() <= 2e-2, (s, diff.max())
+        assert diff.max() <= 1e-2 * np.abs(want).max(), (s, diff.max(), np.abs(want).max())
+        assert (diff / G.attention_error_bound(sub, want)).max() <= 1.0, s
 
 
 @pytest.mark.parametrize("wid,mode", [(2, 1), (2, 2), (4, 1)])
