@@ -25,13 +25,13 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 
 
-def cpu_baseline(w, step, layers, seed, budget_s=12.0):
-    """The CPU checker, as it stands, on a bounded sample of the same step (about `budget_s` seconds of CPU
-    work: the sample is repeated until that much time has passed), each stage scaled to the full step."""
+def cpu_baseline(w, step, layers, seed, budget_s=9.0):
+    """The CPU checker, as it stands, on a bounded sample of the same step, each stage scaled to the full step:
+    once with the host's BLAS threads as they are (about `budget_s` seconds of CPU work: the sample is
+    repeated until that much time has passed) and once more limited to one thread."""
     import numpy as np
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import draft_entropy_topk, tree_prune, tree_attention, verify_accept
-    from synth import workloads as W
 
     h = step.host
     rows_total = int(step.t["draft_rows"].shape[0])
@@ -54,39 +54,54 @@ def cpu_baseline(w, step, layers, seed, budget_s=12.0):
     q, kp, vp = np_store(step.t["q"][:n1]), np_store(step.t["k_prefix"][:p1]), np_store(step.t["v_prefix"][:p1])
     kt, vt = np_store(step.t["k_tree"][:n1]), np_store(step.t["v_tree"][:n1])
     par = step.t["attn_parent"][:n1].cpu().numpy()
-    n4 = min(256, h["NNp"])
+    # accept walk: the checker's verify_accept on the step's own inputs; leading sequences of the
+    # batch up to 256 rows of logits, scaled by rows
+    oo = h["out_offsets"]
+    n_seq = 1
+    while n_seq < len(oo) - 1 and int(oo[n_seq + 1]) <= 256:
+        n_seq += 1
+    n4 = int(oo[n_seq])
     tl = step.t["target_logits"][:n4].cpu().numpy()
-    t1 = t2 = t3 = t4 = 0.0
-    reps = 0
-    start = time.perf_counter()
-    while reps == 0 or time.perf_counter() - start < budget_s:
-        t0 = time.perf_counter()
-        draft_entropy_topk(x, w.topk, w.temperature)
-        t1 += time.perf_counter() - t0
-        t0 = time.perf_counter()
-        tree_prune(*prune_in)
-        t2 += time.perf_counter() - t0
-        t0 = time.perf_counter()
-        tree_attention(q, kp, vp, kt, vt, par, no[:n_ent + 1], po[:n_ent + 1], h["scale"])
-        t3 += time.perf_counter() - t0
-        t0 = time.perf_counter()
-        for r in range(n4):
-            np.argmax(tl[r])
-        t4 += time.perf_counter() - t0
-        reps += 1
-    spent = time.perf_counter() - start
-    t1 = t1 / reps * rows_total / n_rows
-    t2 = t2 / reps
-    t3 = t3 / reps * step.bytes_stage3() / bytes_sample
-    t4 = t4 / reps * h["NNp"] / n4
-    total = t1 + t2 + t3 + t4
+    tok = step.t["token"][:n4].cpu().numpy()
+    par4 = step.t["s2_out"]["out_parent"][:n4].cpu().numpy()
+
+    def sample(budget):
+        t1 = t2 = t3 = t4 = 0.0
+        reps = 0
+        start = time.perf_counter()
+        while reps == 0 or time.perf_counter() - start < budget:
+            t0 = time.perf_counter()
+            draft_entropy_topk(x, w.topk, w.temperature)
+            t1 += time.perf_counter() - t0
+            t0 = time.perf_counter()
+            tree_prune(*prune_in)
+            t2 += time.perf_counter() - t0
+            t0 = time.perf_counter()
+            tree_attention(q, kp, vp, kt, vt, par, no[:n_ent + 1], po[:n_ent + 1], h["scale"])
+            t3 += time.perf_counter() - t0
+            t0 = time.perf_counter()
+            verify_accept(tl, None, tok, par4, oo[:n_seq + 1], 0, w.temperature, None, h["max_depth"])
+            t4 += time.perf_counter() - t0
+            reps += 1
+        spent = time.perf_counter() - start
+        st = {"entropy_topk": t1 / reps * rows_total / n_rows, "prune": t2 / reps,
+              "attention": t3 / reps * step.bytes_stage3() / bytes_sample, "accept": t4 / reps * h["NNp"] / n4}
+        return st, reps, spent
+
+    stages, reps, spent = sample(budget_s)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    with threadpool_limits(limits=1):
+        stages1, reps1, spent1 = sample(budget_s)
+    total, total1 = sum(stages.values()), sum(stages1.values())
     return {"value": h["kept_draft_nodes"] / total, "unit": "tree-tokens/s", "cores": threads, "kind": "oracle",
             "sample": "%d repetitions (%.1f s of CPU work) of: stage1 on %d of %d rows, stage2 whole, stage3 on %d of %d "
-                      "batch entries (scaled by bytes), stage4 argmax on %d of %d rows; each scaled to the full step" %
-                      (reps, spent, n_rows, rows_total, n_ent, len(no) - 1, n4, h["NNp"]),
-            "seconds_per_step": total,
-            "stage_seconds": {"entropy_topk": t1, "prune": t2, "attention": t3, "accept": t4}}
+                      "batch entries (scaled by bytes), stage4 = the checker's greedy accept walk on %d of %d rows "
+                      "(%d of %d sequences); each scaled to the full step; then %d repetitions (%.1f s) limited to "
+                      "one thread" % (reps, spent, n_rows, rows_total, n_ent, len(no) - 1, n4, h["NNp"], n_seq,
+                                      len(oo) - 1, reps1, spent1),
+            "seconds_per_step": total, "stage_seconds": stages,
+            "one_thread": {"value": h["kept_draft_nodes"] / total1, "cores": 1, "seconds_per_step": total1,
+                           "stage_seconds": stages1}}
 
 
 def adaptive_main(args, w, layers):
@@ -153,6 +168,9 @@ def main():
     ap.add_argument("--accept", default="greedy", choices=["greedy", "stochastic", "pointmass"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", choices=["", "attention"],
+                    help="attention: nothing but W + K attention launches of the workload (for profiler passes); "
+                         "prints a short line, not the bench line")
     ap.add_argument("--adaptive", action="store_true",
                     help="the device-driven adaptive step (level-by-level expansion, complexity decision, extended "
                          "drafting, per-bin HIP graphs) instead of the four-call step; not the headline line")
@@ -181,6 +199,15 @@ def main():
         return adaptive_main(args, w, layers)
     step = harness.build_step(w, args.seed, layers=layers, accept_mode=mode)
     torch.cuda.synchronize()
+    if args.only == "attention":
+        for _ in range(args.warmup + args.steps):
+            step.stage3()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": "attention", "workload": w.wid, "launches": args.warmup + args.steps,
+                          "algorithmic_bytes_per_launch": step.bytes_stage3(),
+                          "algorithmic_flops_per_launch": step.flops_stage3()}))
+        return
+    n_sets = step.rotate_logits()     # consecutive steps read different copies: the scans stream from HBM
 
     for _ in range(args.warmup):
         step.run()
@@ -201,27 +228,28 @@ def main():
     # (hs_time_next_attention: stamped when that kernel begins and ends on the stream it is launched
     # on): the kernel's duration for the roofline.  Not inside the region above, because a dispatch
     # that carries events costs the stream about 6 us more than one that does not.
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+    KE = max(K, 50)             # at least 50 launches, whatever --steps says
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(KE)]
     for pair in ev:
         for e in pair:
             e.record()          # torch creates the HIP event at the first record
     torch.cuda.synchronize()
     te0 = time.perf_counter()
-    for k in range(K):
+    for k in range(KE):
         step.stage1()
         step.stage2()
         hs.hs_time_next_attention(ev[k][0], ev[k][1])
         step.stage3()
         step.stage4()
     torch.cuda.synchronize()
-    ms_per_step_with_events = (time.perf_counter() - te0) * 1e3 / K
+    ms_per_step_with_events = (time.perf_counter() - te0) * 1e3 / KE
     attn = [a.elapsed_time(b) for a, b in ev]
 
     # Per-stage breakdown: a third pass of K steps with an event recorded at every stage boundary
     # (recorded events cost about 5 us a pair, which is why they stay out of the timed region above;
     # gaps[2] is the attention call bracketed that way, combine kernel included when there is one).
-    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
-    for k in range(K):
+    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(KE)]
+    for k in range(KE):
         ev2[k][0].record()
         step.stage1()
         ev2[k][1].record()
@@ -232,7 +260,7 @@ def main():
         step.stage4()
         ev2[k][4].record()
     torch.cuda.synchronize()
-    gaps = [[ev2[k][i].elapsed_time(ev2[k][i + 1]) for k in range(K)] for i in range(4)]
+    gaps = [[ev2[k][i].elapsed_time(ev2[k][i + 1]) for k in range(KE)] for i in range(4)]
     stage_ms = [float(np.mean(gaps[0])), float(np.mean(gaps[1])), float(np.mean(attn)), float(np.mean(gaps[3]))]
     stage_med = [float(np.median(gaps[0])), float(np.median(gaps[1])), float(np.median(attn)), float(np.median(gaps[3]))]
     attn_bracketed_ms = float(np.mean(gaps[2]))
@@ -336,13 +364,20 @@ def main():
                    "attention_layers_per_step": layers, "candidate_nodes": h["cand_nodes"],
                    "verified_rows": h["NNp"], "verified_draft_nodes": tokens,
                    "draft_rows_quantified": int(step.t["draft_rows"].shape[0]), "accept": args.accept},
-        "stage_ms": {"entropy_topk": stage_ms[0], "prune": stage_ms[1], "attention": stage_ms[2], "accept": stage_ms[3],
+        "stage_ms": {"entropy_topk": stage_med[0], "prune": stage_med[1], "attention": stage_med[2], "accept": stage_med[3],
+                     "statistic": "median of %d steps (attention: the kernel between the events attached to its "
+                                  "dispatch; the other stages between recorded events, which add about one "
+                                  "empty_event_pair each)" % KE,
                      "attention_call_bracketed_by_events": attn_bracketed_ms,
                      "empty_event_pair": event_pair_ms, "step_with_events_on_the_attention_launch": ms_per_step_with_events},
-        "stage_ms_median": {"entropy_topk": stage_med[0], "prune": stage_med[1], "attention": stage_med[2],
-                            "accept": stage_med[3]},
-        "stage_gbps": {"entropy_topk": step.bytes_stage1() / (stage_ms[0] * 1e-3) / 1e9,
-                       "attention": achieved, "accept": step.bytes_stage4() / (stage_ms[3] * 1e-3) / 1e9},
+        "stage_ms_mean": {"entropy_topk": stage_ms[0], "prune": stage_ms[1], "attention": stage_ms[2],
+                          "accept": stage_ms[3]},
+        "stage_gbps": {"entropy_topk": step.bytes_stage1() / (stage_med[0] * 1e-3) / 1e9,
+                       "attention": achieved, "accept": step.bytes_stage4() / (stage_med[3] * 1e-3) / 1e9,
+                       "logits_copies_rotated": n_sets,
+                       "note": "consecutive steps read different copies of the logits (%d copies, %.0f MB in all), so the "
+                               "scans' rates are HBM rates, not last-level-cache rates" %
+                               (n_sets, n_sets * (step.bytes_stage1() + step.bytes_stage4()) / 1e6)},
         "tree_attn_hbm_gbps": achieved, "tree_attn_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "copy_ceiling_gbps": copy_gbps,
         "tree_attn_single_layer": single,
@@ -350,7 +385,7 @@ def main():
         "roofline": {"kernel": "hs_tree_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": bytes3, "algorithmic_flops_per_launch": flops3,
-                     "launch_ms": stage_ms[2], "launches_timed": len(attn)},
+                     "launch_ms": stage_ms[2], "launch_ms_median": stage_med[2], "launches_timed": len(attn)},
     }
     if mfma_bound:
         tf = flops3 / (stage_ms[2] * 1e-3) / 1e12

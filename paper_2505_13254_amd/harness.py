@@ -104,10 +104,25 @@ class Step:
     accept_mode: int
     t: Dict[str, torch.Tensor] = field(default_factory=dict)
     host: Dict[str, object] = field(default_factory=dict)
+    sets: List[Dict[str, torch.Tensor]] = field(default_factory=list)   # rotating copies of the logits (see rotate_logits)
+    k: int = 0                                                          # steps run so far
+
+    def rotate_logits(self, min_bytes: float = 320e6) -> int:
+        """Makes enough copies of the step's logits arrays (draft rows, target rows, draft rows of the kept
+        nodes) that a run of steps, each reading the next copy, streams them from HBM instead of finding
+        the previous step's rows in the 256 MB last-level cache.  Returns the number of copies in use."""
+        names = [n for n in ("draft_rows", "target_logits", "draft_logits") if n in self.t]
+        per_set = sum(self.t[n].numel() * 4 for n in names)
+        n_sets = max(1, min(8, int(-(-min_bytes // per_set))))
+        self.sets = [{n: self.t[n] for n in names}] + [{n: self.t[n].clone() for n in names} for _ in range(n_sets - 1)]
+        return n_sets
+
+    def _logits(self, name):
+        return self.sets[self.k % len(self.sets)][name] if self.sets else self.t[name]
 
     # ---- the four stages, each one C call
     def stage1(self):
-        return hs.hs_draft_entropy_topk(self.t["draft_rows"], self.w.topk, self.w.temperature,
+        return hs.hs_draft_entropy_topk(self._logits("draft_rows"), self.w.topk, self.w.temperature,
                                         out=self.t["s1_out"], ws=self.t["s1_ws"])
 
     def stage2(self):
@@ -130,11 +145,14 @@ class Step:
 
     def stage4(self):
         t, h = self.t, self.host
-        return hs.hs_verify_accept(t["target_logits"], t["draft_logits"] if self.accept_mode == 1 else None,
-                                   t["token"], t["s2_out"]["out_parent"], t["s2_out"]["out_offsets"],
-                                   self.accept_mode, self.w.temperature,
-                                   t["uniforms"] if self.accept_mode != 0 else None, h["max_depth"],
-                                   out=t["s4_out"], ws=t["s4_ws"])
+        r = hs.hs_verify_accept(self._logits("target_logits"),
+                                self._logits("draft_logits") if self.accept_mode == 1 else None,
+                                t["token"], t["s2_out"]["out_parent"], t["s2_out"]["out_offsets"],
+                                self.accept_mode, self.w.temperature,
+                                t["uniforms"] if self.accept_mode != 0 else None, h["max_depth"],
+                                out=t["s4_out"], ws=t["s4_ws"])
+        self.k += 1          # the step is complete: the next one reads the next copy of the logits
+        return r
 
     def run(self):
         self.stage1()
