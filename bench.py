@@ -167,6 +167,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="attention layers per step (0 = the model's)")
     ap.add_argument("--accept", default="greedy", choices=["greedy", "stochastic", "pointmass"])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--pause-ms", type=float, default=0.0,
+                    help="--only attention: host pause after every launch (the chip's clocks recover between launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", choices=["", "attention"],
                     help="attention: nothing but W + K attention launches of the workload (for profiler passes); "
@@ -200,12 +202,36 @@ def main():
     step = harness.build_step(w, args.seed, layers=layers, accept_mode=mode)
     torch.cuda.synchronize()
     if args.only == "attention":
-        for _ in range(args.warmup + args.steps):
-            step.stage3()
+        # W + K attention launches (each carrying events on its dispatch) with a 2 ms pause between them,
+        # and one 1 GiB device copy, whose known size calibrates the profiler's byte counters
+        n = args.warmup + args.steps
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
+        for pair in ev:
+            for e in pair:
+                e.record()
         torch.cuda.synchronize()
-        print(json.dumps({"only": "attention", "workload": w.wid, "launches": args.warmup + args.steps,
+        t0 = time.perf_counter()
+        for a_, b_ in ev:
+            hs.hs_time_next_attention(a_, b_)
+            step.stage3()
+            if args.pause_ms > 0:
+                torch.cuda.synchronize()
+                time.sleep(args.pause_ms * 1e-3)
+        torch.cuda.synchronize()
+        call_ms = (time.perf_counter() - t0) * 1e3 / n
+        big = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(big)
+        dst.copy_(big)
+        torch.cuda.synchronize()
+        ts = np.array([a_.elapsed_time(b_) for a_, b_ in ev][args.warmup:])
+        print(json.dumps({"only": "attention", "workload": w.wid, "layers": layers, "launches": n,
+                          "pause_ms_between_launches": args.pause_ms,
+                          "kernel_ms_median": float(np.median(ts)), "kernel_ms_mean": float(ts.mean()),
+                          "kernel_ms_min": float(ts.min()), "call_to_call_ms": call_ms,
                           "algorithmic_bytes_per_launch": step.bytes_stage3(),
-                          "algorithmic_flops_per_launch": step.flops_stage3()}))
+                          "algorithmic_flops_per_launch": step.flops_stage3(),
+                          "note": "kernel_ms is the attention kernel alone (a combine launch that follows split keys "
+                                  "is not in it)"}))
         return
     n_sets = step.rotate_logits()     # consecutive steps read different copies: the scans stream from HBM
 

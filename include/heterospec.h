@@ -81,6 +81,7 @@ typedef enum {
 typedef void* hs_stream; /* a hipStream_t */
 
 #define HS_MAX_TOPK 64
+#define HS_MAX_CHILDREN 256 /* children of one node that the sampling accept rules try (see hs_verify_accept) */
 
 /* Static description of a status code; never NULL, never freed. */
 const char* hs_status_string(hs_status st);
@@ -103,7 +104,8 @@ const char* hs_version(void);
  *   lse      [R]    float  ln sum_v exp(y_v)                                    (may be NULL)
  * logits: float32, row r starts at logits + r*row_stride (row_stride >= V, in elements).
  * -inf logits are allowed (probability 0).  Natural logarithms.
- * Requires 1 <= K <= min(V, HS_MAX_TOPK), temperature > 0, R >= 0 (R == 0 is a no-op).
+ * Requires 1 <= K <= min(V, HS_MAX_TOPK), temperature > 0, 0 <= R <= 65535 (R == 0 is a no-op;
+ * more rows: HS_ERR_UNSUPPORTED, split the call).
  */
 size_t hs_draft_entropy_topk_workspace(int32_t R, int32_t V, int32_t K);
 hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stride, int32_t R, int32_t V,
@@ -184,7 +186,11 @@ hs_status hs_tree_prune_static(const int32_t* parent, const float* logc, const i
  *   output rounded once; HS_F32: float32 throughout).
  *   parent [NN] int32 local indices; node_offsets [B+1] int32; prefix_offsets [B+1] int64 (token units).
  *   host_node_offsets / host_prefix_offsets: HOST copies of the two offset arrays, read during the
- *   call to size the launch; they must equal the device arrays.
+ *   call to size the launch; they must equal the device arrays.  The host copies (and, in the _lens
+ *   and _paged calls, host_prefix_lens) are what the launch is planned from: row counts, prefix
+ *   lengths and key splits are fixed when the call returns, and a launch that was captured into a HIP
+ *   graph keeps them on every replay.  Replaying it after the lengths have changed on the device (after
+ *   hs_kv_commit, say) attends to the lengths of the capture; capture one graph per shape instead.
  *   lse [NN,Hq] float: ln of the softmax denominator (of the scaled scores); may be NULL.
  * Requires Hq % Hkv == 0, D in {64, 128}, at most 1024 tree rows per sequence.
  */
@@ -267,6 +273,9 @@ hs_status hs_tree_attention_paged(const void* q, const void* k_pages, const void
  * Outputs: accept_len [B] (number of accepted rows), accept_path [B,max_depth] local row indices
  *   padded with -1, bonus_token [B] (-1 for an empty sequence).  The walk stops after max_depth
  *   accepted rows.
+ * Limits: the sampling rules try at most HS_MAX_CHILDREN children of a node, the lowest rows (Top-k
+ *   expansion gives a node k <= HS_MAX_TOPK children; hs_tree_validate reports rows beyond the
+ *   limit); NN <= 65535 rows in greedy mode and 32767 in the sampling modes (HS_ERR_UNSUPPORTED beyond).
  * Workspace: hs_verify_accept_workspace_mode gives what a call in `mode` needs; the query without
  *   a mode gives the largest of the three, that of HS_ACCEPT_STOCHASTIC: besides a few arrays of
  *   NN entries, a pair of floats per row and vocabulary entry, 80 KiB of bucket tables per row
@@ -392,12 +401,13 @@ hs_status hs_kv_commit(const void* k_tree, const void* v_tree, const int32_t* no
  * hs_tree_validate  (debugging aid; the tree conventions above are what every other call trusts)
  *
  * Checks B packed trees: node_offsets [B+1] start at 0, do not decrease and end at NN; in every
- * sequence row 0 has parent -1 and every other row's parent is an earlier row of the sequence; and,
- * when token [NN] is given (may be NULL), no row shares parent and token with an earlier row
- * (siblings are distinct Top-k picks, Section 2.2).
+ * sequence row 0 has parent -1 and every other row's parent is an earlier row of the sequence; no
+ * row has HS_MAX_CHILDREN or more earlier rows of the same parent; and, when token [NN] is given (may
+ * be NULL), no row shares parent and token with an earlier row (siblings are distinct Top-k picks,
+ * Section 2.2).
  * report (device, int32 [2]): the number of offending rows and the global index of the first one
  * (-1 if none); broken offsets count every row.  Valid after the stream is synchronised.
- * Quadratic in the fan-out when token is given: not for the hot path.
+ * Quadratic in the rows of a sequence: not for the hot path.
  */
 hs_status hs_tree_validate(const int32_t* parent, const int32_t* token, const int32_t* node_offsets,
                            int32_t B, int32_t NN, int32_t* report, hs_stream stream);

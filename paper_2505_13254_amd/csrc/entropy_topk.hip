@@ -534,6 +534,8 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
                           void* workspace, hipStream_t stream, ScanSlices* slices, const uint8_t* row_active,
                           const int32_t* row_index, const float* logits2, int rows1) {
+  // (rows are the grid's second dimension)
+  HS_REQUIRE(R <= 65535, HS_ERR_UNSUPPORTED, "row scan: %d rows in one call (at most 65535)", R);
   ScanPlan p = plan_scan(R, V);
   Carver c(workspace);
   size_t n = (size_t)R * p.splits;

@@ -8,6 +8,8 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <functional>
+#include <vector>
 
 #include "attn_common.h"
 
@@ -326,12 +328,18 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
     seqs[n++] = q;
   }
   if (n == 0) return false;
-  static const int targets[] = {1 << 20, 192, 128, 96, 64, 48, 32, 24, 16, 8};
+  // Unequal items (a ragged batch): the makespan of each candidate is found by replaying the
+  // hardware's dispatch, which hands the next workgroup in index order to the first compute unit
+  // that falls free (list scheduling).  Equal items (the layers of one step) run in whole rounds.
+  static const int targets[] = {1 << 20, 192, 160, 128, 112, 96, 80, 72, 64, 56, 48, 40, 32, 24, 16, 8};
   ListPlan best{0.f, 0};
+  static thread_local std::vector<float> item_cost, cu_free;  // (kept between calls: no allocation in the steady state)
   for (int target : targets) {
     double total = 0.0, rec_bytes = 0.0;
     float mx = 0.f, mn = 1e30f;
     int64_t items = 0;
+    int ord[ATTN_TBL];
+    float seq_cost[ATTN_TBL];
     for (int i = 0; i < n; ++i) {
       const Seq& q = seqs[i];
       const int nsp = plan_splits(q.tiles, target, sp_cap, a.block_table != nullptr);
@@ -344,12 +352,46 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
       if (big > mx) mx = big;
       if (one_last < mn) mn = one_last;
       if (nsp > 1) rec_bytes += (double)q.M * a.Hq * nsp * ATTN_REC * 4 * 2;  // written, then read
+      ord[i] = i;
+      seq_cost[i] = (float)per * plan_tile_us(q.waves0);
     }
-    float est = (float)(total / PLAN_CUS) + 0.15f * mx;
-    if (mx > est) est = mx;
-    if (mx - mn <= 0.1f * mx) {  // equal items run in whole rounds
-      const float rounds = (float)((items + PLAN_CUS - 1) / PLAN_CUS) * (float)(total / (double)items);
-      if (rounds > est) est = rounds;
+    float est;
+    if (mx - mn <= 0.1f * mx || items > 8192) {
+      est = (float)(total / PLAN_CUS) + 0.15f * mx;
+      if (mx > est) est = mx;
+      if (mx - mn <= 0.1f * mx) {  // equal items run in whole rounds
+        const float rounds = (float)((items + PLAN_CUS - 1) / PLAN_CUS) * (float)(total / (double)items);
+        if (rounds > est) est = rounds;
+      }
+    } else {
+      // the items in dispatch order (as the table below lists them), then the replay
+      std::stable_sort(ord, ord + n, [&](int x, int y) { return seq_cost[x] > seq_cost[y]; });
+      item_cost.clear();
+      for (int k = 0; k < n; ++k) {
+        const Seq& q = seqs[ord[k]];
+        const int nsp = plan_splits(q.tiles, target, sp_cap, a.block_table != nullptr);
+        const int per = (q.tiles + nsp - 1) / nsp;
+        for (int sp = 0; sp < nsp; ++sp) {
+          int t = q.tiles - sp * per;
+          t = t > per ? per : (t < 0 ? 0 : t);
+          if (sp == nsp - 1) t += q.ttiles;
+          for (int rg = 0; rg < q.rg; ++rg) {
+            const float c = PLAN_ITEM_US + (float)t * plan_tile_us(rg == q.rg - 1 ? q.waves_last : q.waves0);
+            for (int h = 0; h < a.Hkv; ++h) item_cost.push_back(c);
+          }
+        }
+      }
+      cu_free.assign(PLAN_CUS, 0.f);
+      std::make_heap(cu_free.begin(), cu_free.end(), std::greater<float>());
+      float end = 0.f;
+      for (float c : item_cost) {
+        std::pop_heap(cu_free.begin(), cu_free.end(), std::greater<float>());
+        const float done = cu_free.back() + c;
+        cu_free.back() = done;
+        std::push_heap(cu_free.begin(), cu_free.end(), std::greater<float>());
+        if (done > end) end = done;
+      }
+      est = end;
     }
     if (rec_bytes > 0.0) est += 4.f + (float)(rec_bytes / 2.5e6);  // the combine launch, ~2.5 TB/s
     if (best.target == 0 || est < best.est_us) best = ListPlan{est, target};

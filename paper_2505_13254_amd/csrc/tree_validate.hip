@@ -1,6 +1,7 @@
 // hs_tree_validate: structural check of packed draft trees, for debugging.  The other calls trust
 // their callers for what this one tests: root first with parent -1, every other parent an earlier
-// row of the same sequence, sibling tokens distinct, offsets that start at 0 and do not decrease.
+// row of the same sequence, sibling tokens distinct, at most HS_MAX_CHILDREN children per node,
+// offsets that start at 0 and do not decrease.
 #include <limits.h>
 
 #include "hs_common.h"
@@ -34,9 +35,15 @@ __global__ __launch_bounds__(VAL_THREADS) void k_validate(const int32_t* __restr
   for (int i = tid; i < n; i += VAL_THREADS) {
     const int p = parent[o + i];
     bool wrong = i == 0 ? p != -1 : !(p >= 0 && p < i);
-    if (!wrong && i > 0 && token != nullptr) {
-      const int x = token[o + i];
-      for (int j = 1; j < i && !wrong; ++j) wrong = parent[o + j] == p && token[o + j] == x;
+    if (!wrong && i > 0) {
+      const int x = token != nullptr ? token[o + i] : 0;
+      int before = 0;  // earlier children of the same parent
+      for (int j = 1; j < i && !wrong; ++j)
+        if (parent[o + j] == p) {
+          ++before;
+          wrong = token != nullptr && token[o + j] == x;
+        }
+      wrong = wrong || before >= HS_MAX_CHILDREN;
     }
     if (wrong) {
       atomicAdd(&report[0], 1);

@@ -214,7 +214,8 @@ __device__ __forceinline__ double token_weight(const RowView& p, const RowView& 
 }
 
 // Children of local row `cur` of a sequence of n rows, ascending, into kids_sorted; returns their
-// number (at most AC_MAX_KIDS).  Called by all threads; ends with a barrier.
+// number (at most AC_MAX_KIDS: of a node with more children the AC_MAX_KIDS lowest rows are taken,
+// whatever order the threads arrive in).  Called by all threads; ends with a barrier.
 __device__ __forceinline__ int gather_children(const int32_t* __restrict__ parent, int o, int n, int cur, bool any,
                                                int* kids, int* kids_sorted, int* n_kids) {
   const int tid = threadIdx.x;
@@ -227,7 +228,20 @@ __device__ __forceinline__ int gather_children(const int32_t* __restrict__ paren
         if (pos < AC_MAX_KIDS) kids[pos] = i;
       }
   __syncthreads();
-  const int nk = *n_kids < AC_MAX_KIDS ? *n_kids : AC_MAX_KIDS;
+  if (*n_kids > AC_MAX_KIDS) {
+    // more children than the lists hold (never with Top-k expansion): which of them the atomic
+    // counter let in depends on arrival order, so the lists are made again by rank, each child
+    // counting the children before it; the first AC_MAX_KIDS stay
+    for (int i = 1 + tid; i < n; i += AC_THREADS)
+      if (parent[o + i] == cur) {
+        int r = 0;
+        for (int j = 1; j < i && r < AC_MAX_KIDS; ++j) r += parent[o + j] == cur ? 1 : 0;
+        if (r < AC_MAX_KIDS) kids_sorted[r] = i;
+      }
+    __syncthreads();
+    return AC_MAX_KIDS;
+  }
+  const int nk = *n_kids;
   if (tid < nk) {
     int me = kids[tid], r = 0;
     for (int j = 0; j < nk; ++j) r += kids[j] < me ? 1 : 0;

@@ -32,6 +32,17 @@ def _store(x, device):
     return torch.from_numpy(x).to(device)
 
 
+def _in_parallel(fn, items, workers: int = 16):
+    """The seeded input generators are pure functions of their key, and numpy releases the interpreter
+    lock inside its array operations: the layers' / sequences' tensors are generated side by side."""
+    from concurrent.futures import ThreadPoolExecutor
+    items = list(items)
+    if len(items) <= 1:
+        return [fn(x) for x in items]
+    with ThreadPoolExecutor(max_workers=min(workers, len(items))) as ex:
+        return list(ex.map(fn, items))
+
+
 def expand_tree(w: W.Workload, seed: int, s: int, depth: int, device="cuda:0"):
     """Top-K expansion: per depth, the `frontier` nodes with the largest cumulative confidence are
     expanded with their K most likely draft tokens.  Returns the candidate tree (host arrays) and the
@@ -278,13 +289,14 @@ def build_step(w: W.Workload, seed: int = 0, layers: Optional[int] = None, accep
     L = W.prefix_lengths(w, seed)
     if layers > 1:
         M = NNp
-        parts = [W.attention_inputs(w, seed, 1000 + l, int(L[0]), M, "config", parent=par) for l in range(layers)]
+        parts = _in_parallel(lambda l: W.attention_inputs(w, seed, 1000 + l, int(L[0]), M, "config", parent=par),
+                             range(layers))
         no = (np.arange(layers + 1) * M).astype(np.int32)
         po = (np.arange(layers + 1) * int(L[0])).astype(np.int64)
         t["attn_parent"] = _dev(np.tile(par, layers), torch.int32, device)
     else:
-        parts = [W.attention_inputs(w, seed, s, int(L[s]), int(oo[s + 1] - oo[s]), "config",
-                                    parent=par[oo[s]:oo[s + 1]]) for s in range(B)]
+        parts = _in_parallel(lambda s: W.attention_inputs(w, seed, s, int(L[s]), int(oo[s + 1] - oo[s]), "config",
+                                                          parent=par[oo[s]:oo[s + 1]]), range(B))
         no = oo.astype(np.int32)
         po = np.zeros(B + 1, np.int64)
         po[1:] = np.cumsum(L)

@@ -183,7 +183,9 @@ def test_tree_validate_matches_the_checker(G):
              ([-1, 0, -1, 0, 5], None, [0, 2, 5]),
              ([0, 0, 0], None, [0, 3]),
              ([-1, 0], None, [0, 2, 1]),
-             ([-1, 0, 1, -1, 0, 0], [1, 2, 3, 4, 5, 6], [0, 3, 3, 6])]
+             ([-1, 0, 1, -1, 0, 0], [1, 2, 3, 4, 5, 6], [0, 3, 3, 6]),
+             ([-1] + [0] * 300 + [1] * 256, None, [0, 557]),          # a node with more than 256 children
+             ([-1, 0] + [1] * 257, list(range(259)), [0, 259])]
     for _ in range(40):                                            # random forests, some rows damaged
         sizes = [int(x) for x in rs.randint(0, 40, size=int(rs.randint(1, 6)))]
         par, tok = [], []

@@ -281,6 +281,46 @@ def test_accept_long_rejection_chains(G, V, n_kids, T):
     assert done >= 6 and rejected_all >= 2, (done, rejected_all)
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+def test_accept_more_children_than_the_lists_hold(G, mode):
+    """A root with 300 children: the sampling rules try the 256 lowest rows (the documented limit), the
+    same ones on every run.  With an accepting draw placed on child 200 the walk is the checker's;
+    with every draw rejecting, the result is that of the tree cut to its first 256 children."""
+    import paper_2505_13254_amd as hs
+    from oracle import verify_accept
+    rs = np.random.RandomState(5 + mode)
+    V, n_kids = 4096, 300
+    draft = (rs.normal(size=(1 + n_kids, V)) * 1.5).astype(np.float32)
+    target = (0.8 * draft + rs.normal(size=draft.shape)).astype(np.float32)
+    parent = np.asarray([-1] + [0] * n_kids, np.int32)
+    token = np.zeros(1 + n_kids, np.int32)
+    token[1:] = np.argsort(-draft[0], kind="stable")[:n_kids]
+    offs = np.asarray([0, 1 + n_kids], np.int32)
+
+    def gpu(u, par=parent, tok=token, off=offs, tl=target, dl=draft):
+        out = hs.hs_verify_accept(G.dev(tl), G.dev(dl), G.dev(tok, torch.int32), G.dev(par, torch.int32),
+                                  G.dev(off, torch.int32), mode, 1.0, G.dev(u, torch.float32), 1)
+        return {k: G.host(v) for k, v in out.items()}
+    # (a) child 200 accepts for sure (u = 0; the target favours its token far more than the draft does, so
+    # that its residual probability survives the rejections before it), the others reject (u close to 1)
+    target[0, token[200]] += 12.0
+    u = np.concatenate([np.full(1 + n_kids, 0.9999), [0.37]]).astype(np.float32)
+    u[200] = 0.0
+    want = verify_accept(target, draft, token, parent, offs, mode, 1.0, u, 1)
+    assert want["accept_len"][0] == 1 and want["accept_path"][0, 0] == 200
+    _accept_equal(gpu(u), want)
+    target[0, token[200]] -= 12.0
+    # (b) nothing accepts: the first 256 children are tried, twice with the same bits
+    u = np.concatenate([np.full(1 + n_kids, 0.99999), [0.61]]).astype(np.float32)
+    cut = 257
+    uc = np.concatenate([u[:cut], u[-1:]])
+    want = verify_accept(target[:cut], draft[:cut], token[:cut], parent[:cut], np.asarray([0, cut], np.int32), mode, 1.0, uc, 1)
+    if want["accept_len"][0] == 0:        # (with 256 rejections in a row nearly all mass is gone; any outcome must agree)
+        first, second = gpu(u), gpu(u)
+        _accept_equal(first, want)
+        _accept_equal(second, first)
+
+
 def test_accept_draft_rows_of_leaves_are_not_read(G):
     """Only rows that have children carry a draft distribution: the others may hold anything."""
     w = W.small(W.WORKLOADS[2], V=8192)

@@ -17,6 +17,9 @@ def test_known_defects():
     assert tree_validate([-1, 0, -1, 0, 5], None, [0, 2, 5]) == (1, 4)         # parent outside the sequence
     assert tree_validate([], None, [0, 0, 0]) == (0, -1)
     assert tree_validate([-1, 0], None, [0, 2, 1])[0] == 2                     # decreasing offsets
+    star = [-1] + [0] * 300                                                    # the root has 300 children:
+    assert tree_validate(star, None, [0, 301]) == (44, 257)                    # those after the 256th offend
+    assert tree_validate([-1] + [0] * 256, None, [0, 257]) == (0, -1)
 
 
 def test_valid_iff_every_row_reaches_the_root_through_earlier_rows():
