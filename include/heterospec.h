@@ -124,6 +124,27 @@ hs_status hs_draft_entropy_topk_rows(const float* logits, int64_t row_stride, co
                                      float* ent_full, float* lse,
                                      void* workspace, size_t workspace_bytes, hs_stream stream);
 
+/* hs_draft_entropy_topk_fused: hs_draft_entropy_topk / _rows (row_index may be NULL: every row) in ONE
+ * kernel launch whatever the row count.  Few rows are cut into slices so that the whole chip reads
+ * them; the plain calls then merge a row's slices with a second launch, this one lets the workgroup
+ * that finishes a row's last slice do it, found by a counter per row at the start of the workspace.
+ * The counters must be zero when the call starts and are zero again when it has completed, so the
+ * workspace must be PREPARED: cleared once by hs_workspace_prepare and used since then only by
+ * hs_draft_entropy_topk_fused calls that ran to completion (any number of them, of any shape the
+ * workspace is large enough for).  Any other use of the memory, the plain calls included, ends that:
+ * prepare it again.  On an unprepared workspace the results are undefined (no fault, no hang).
+ * Same outputs as the plain calls, bit for bit.  Workspace size: hs_draft_entropy_topk_workspace. */
+hs_status hs_draft_entropy_topk_fused(const float* logits, int64_t row_stride, const int32_t* row_index,
+                                      int32_t R, int32_t V, int32_t K, float temperature,
+                                      int32_t* topk_idx, float* topk_logp, float* ent_topk,
+                                      float* ent_full, float* lse,
+                                      void* workspace, size_t workspace_bytes, hs_stream stream);
+
+/* hs_workspace_prepare: clears `workspace_bytes` bytes (a multiple of 16) of a 256-byte aligned
+ * workspace with a fill kernel on `stream` (no memset: the call may be captured in a HIP graph).
+ * What hs_draft_entropy_topk_fused asks of its workspace. */
+hs_status hs_workspace_prepare(void* workspace, size_t workspace_bytes, hs_stream stream);
+
 /* ------------------------------------------------------------------------------------------------
  * hs_tree_prune  (Section 2.2: the value of node i is the product of the confidences on the path
  * root -> i, and the best nodes by value form the verified subtree; Section 4.3: the node budget

@@ -31,6 +31,9 @@ _SIGNATURES = {
     "hs_draft_entropy_topk": (_c.c_int, [_vp, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "hs_draft_entropy_topk_rows": (_c.c_int, [_vp, _i64, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                               _vp]),
+    "hs_draft_entropy_topk_fused": (_c.c_int, [_vp, _i64, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                               _vp]),
+    "hs_workspace_prepare": (_c.c_int, [_vp, _sz, _vp]),
     "hs_tree_prune_workspace": (_sz, [_i32, _i32]),
     "hs_tree_prune": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "hs_tree_prune_static": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -115,12 +118,22 @@ def workspace(nbytes: int, device) -> Optional[torch.Tensor]:
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
+def hs_workspace_prepare(ws: Optional[torch.Tensor], stream=None) -> None:
+    """Clears a workspace tensor on the GPU (what hs_draft_entropy_topk_fused asks of its workspace)."""
+    if ws is None:
+        return
+    _check(lib().hs_workspace_prepare(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "hs_workspace_prepare")
+
+
 def hs_draft_entropy_topk(logits: torch.Tensor, K: int, temperature: float = 1.0, *, want_full: bool = True,
                           out: Optional[Dict[str, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
-                          row_index: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
+                          row_index: Optional[torch.Tensor] = None, fused: bool = False,
+                          stream=None) -> Dict[str, torch.Tensor]:
     """logits float32 [N, V] (row stride may exceed V).  Returns topk_idx, topk_logp, ent_topk, ent_full, lse
     for its N rows, or, with row_index int32 [R] (GPU), for the R rows that row_index names
-    (hs_draft_entropy_topk_rows; a negative entry leaves that result row untouched)."""
+    (hs_draft_entropy_topk_rows; a negative entry leaves that result row untouched).
+    fused: hs_draft_entropy_topk_fused (one launch); `ws` must then be given and PREPARED
+    (hs_workspace_prepare, and only completed fused calls on it since)."""
     if logits.dim() != 2 or logits.dtype != torch.float32 or not logits.is_cuda or logits.stride(1) != 1:
         raise ValueError("logits must be a float32 [R, V] GPU tensor with unit inner stride")
     N, V = logits.shape
@@ -137,12 +150,16 @@ def hs_draft_entropy_topk(logits: torch.Tensor, K: int, temperature: float = 1.0
             out["ent_full"] = torch.empty(R, dtype=torch.float32, device=dev)
             out["lse"] = torch.empty(R, dtype=torch.float32, device=dev)
     need = lib().hs_draft_entropy_topk_workspace(R, V, K)
-    if ws is None:
+    if ws is None and not fused:
         ws = workspace(need, dev)
     stride = logits.stride(0) if N > 1 else max(V, logits.stride(0))
     tail = (_ptr(out["topk_idx"]), _ptr(out["topk_logp"]), _ptr(out["ent_topk"]), _ptr(out.get("ent_full")),
             _ptr(out.get("lse")), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
-    if row_index is None:
+    if fused:
+        if ws is None or ws.numel() < need:
+            raise ValueError("the fused call needs a prepared workspace of at least %d bytes" % need)
+        st = lib().hs_draft_entropy_topk_fused(_ptr(logits), stride, _ptr(row_index), R, V, K, float(temperature), *tail)
+    elif row_index is None:
         st = lib().hs_draft_entropy_topk(_ptr(logits), stride, R, V, K, float(temperature), *tail)
     else:
         st = lib().hs_draft_entropy_topk_rows(_ptr(logits), stride, _ptr(row_index), R, V, K, float(temperature), *tail)

@@ -164,10 +164,20 @@ __device__ __forceinline__ void rank_candidates(MergeScratch<CAP>& sm, int n, in
   __syncthreads();
 }
 
+// Loads and stores that are coherent across the chip's XCDs (each has an L2 of its own): relaxed
+// atomics of device scope, which go past a stale or private cache line.  What workgroups of one
+// launch use to hand their slices' results to each other: a fence that reaches the other XCDs
+// would write back and invalidate a whole L2, and cost the scan several times its own duration.
+__device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ int ld_dev(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
 // Merges S <= 64 slices of a row: statistics st[s] (m, s1, t) and sorted K-lists pv/pi[s * K + k].
+// COHERENT: the slices were written by other workgroups of the same launch (ld_dev).
 // Leaves the row's statistics in sm.total and its K best pairs, in order, in sm.ov / sm.oi.
 // Called by all `nthreads` threads of the workgroup (tid 0..nthreads-1); ends with a barrier.
-template <int CAP>
+template <bool COHERENT, int CAP>
 __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, const int* pi, int S, int K,
                                              float inv_t, MergeScratch<CAP>& sm, int tid, int nthreads) {
   const int lane = tid & 63;
@@ -177,10 +187,17 @@ __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, 
     float hv = -HS_INF;
     int hi = INT_MAX;
     if (lane < S) {
-      const float4 f = st[lane];
-      a = Stats{f.x, f.y, f.z};
-      hv = pv[lane * K];
-      hi = pi[lane * K];
+      if (COHERENT) {
+        const float* sf = reinterpret_cast<const float*>(st + lane);
+        a = Stats{ld_dev(sf), ld_dev(sf + 1), ld_dev(sf + 2)};
+        hv = ld_dev(pv + lane * K);
+        hi = ld_dev(pi + lane * K);
+      } else {
+        const float4 f = st[lane];
+        a = Stats{f.x, f.y, f.z};
+        hv = pv[lane * K];
+        hi = pi[lane * K];
+      }
     }
     a = stats_wave_sum(a, inv_t);
     // threshold: the K-th best list head when there are at least K lists, else "everything passes"
@@ -207,8 +224,8 @@ __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, 
     const float tv = sm.thr_v;
     const int ti = sm.thr_i;
     for (int e = tid; e < S * K; e += nthreads) {
-      float v = pv[e];
-      int i = pi[e];
+      float v = COHERENT ? ld_dev(pv + e) : pv[e];
+      int i = COHERENT ? ld_dev(pi + e) : pi[e];
       if (i != INT_MAX && !better(tv, ti, v, i)) {  // (INT_MAX: an unused list entry)
         int pos = atomicAdd(&sm.cnt, 1);  // order of arrival does not matter: ranks are computed below
         sm.cv[pos] = v;                   // (at most S * K <= FIN_CAP entries)
@@ -257,8 +274,13 @@ __device__ __forceinline__ void write_row(const MergeScratch<CAP>& sm, int64_t r
 }
 
 // grid (S, R): slice `blockIdx.x` of row `blockIdx.y`.  S == 1: the outputs are written here;
-// S > 1: the slice's statistics and K-list go to part_* for k_scan_finalize.
-template <bool VEC, int SCAN_THREADS>
+// S > 1: the slice's statistics and K-list go to part_* for k_scan_finalize, or, FUSED, for the
+// workgroup that finishes a row's last slice: every workgroup draws a ticket from the row's counter
+// (`tickets`, zero before the launch), the one that draws S - 1 knows that all slices are written,
+// puts the counter back to zero for the next launch, merges the slices and writes the row.
+constexpr int FUSED_CAP = 1024;  // slices x K that the merging workgroup's scratch holds
+constexpr size_t TICKET_BYTES = 65536 * sizeof(unsigned);  // a counter for each of the at most 65535 rows of a call
+template <bool VEC, int SCAN_THREADS, bool FUSED>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restrict__ logits, int64_t row_stride,
                                                             int V, int K, float inv_t, int tiles_per_wg,
                                                             float4* __restrict__ part_stats,
@@ -269,7 +291,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
                                                             float* __restrict__ ent_full, float* __restrict__ lse,
                                                             const uint8_t* __restrict__ row_active,
                                                             const int32_t* __restrict__ row_index,
-                                                            const float* __restrict__ logits2, int rows1) {
+                                                            const float* __restrict__ logits2, int rows1,
+                                                            unsigned* __restrict__ tickets) {
   if (row_active != nullptr && row_active[blockIdx.y] == 0) return;  // (the whole workgroup: a row nobody will read)
   // (both arms as int64: mixed with the unsigned block index a negative entry would turn positive)
   const int64_t src_row = row_index != nullptr ? (int64_t)row_index[blockIdx.y] : (int64_t)blockIdx.y;
@@ -277,7 +300,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
   constexpr int SCAN_WAVES = SCAN_THREADS / 64;
   constexpr int SCAN_GROUPS = SCAN_WAVES * 4 < 64 ? SCAN_WAVES * 4 : 64;  // rows of 16 lanes, at most one per lane
   constexpr int SCAN_TILE = scan_tile(SCAN_THREADS);
-  constexpr int SCAN_CAP = SCAN_WAVES * HS_MAX_TOPK;  // candidates the merge of the waves can face
+  // candidates the merge of the waves can face (and, FUSED, the merge of a row's slices)
+  constexpr int SCAN_CAP = (FUSED && SCAN_WAVES * HS_MAX_TOPK < FUSED_CAP) ? FUSED_CAP : SCAN_WAVES * HS_MAX_TOPK;
   __shared__ float4 wave_st[SCAN_WAVES];
   __shared__ float group_maxima[SCAN_GROUPS];
   __shared__ MergeScratch<SCAN_CAP> sm;
@@ -496,12 +520,45 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
   } else {
     const int64_t slot = (int64_t)row * S + split;
-    if (tid < K) {
-      part_val[slot * K + tid] = sm.ov[tid];
-      part_idx[slot * K + tid] = sm.oi[tid];
+    if (!FUSED) {
+      if (tid < K) {
+        part_val[slot * K + tid] = sm.ov[tid];
+        part_idx[slot * K + tid] = sm.oi[tid];
+      }
+      if (tid == 0) part_stats[slot] = make_float4(sm.total.m, sm.total.s1, sm.total.t, 0.f);
+    } else {
+      __shared__ int is_last;
+      // The slice's results go out by the first wave alone, with stores that the other XCDs see; once
+      // they are acknowledged (vmcnt) the ticket is drawn.  The workgroup that draws the last one
+      // finds every slice of the row written.
+      if (tid < 64) {
+        if (tid < K) {
+          st_dev(part_val + slot * K + tid, sm.ov[tid]);
+          st_dev(part_idx + slot * K + tid, sm.oi[tid]);
+        }
+        if (tid < 3) st_dev(reinterpret_cast<float*>(part_stats + slot) + tid, tid == 0 ? sm.total.m : tid == 1 ? sm.total.s1 : sm.total.t);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (tid == 0) {
+          const unsigned drawn = __hip_atomic_fetch_add(&tickets[row], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          is_last = drawn == (unsigned)(S - 1) ? 1 : 0;
+          // (nobody else touches this row's counter any more: back to zero for the next launch)
+          if (is_last) __hip_atomic_store(&tickets[row], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      __syncthreads();
+      if (is_last) {
+        merge_slices<true>(part_stats + (int64_t)row * S, part_val + (int64_t)row * S * K, part_idx + (int64_t)row * S * K,
+                           S, K, inv_t, sm, tid, SCAN_THREADS);
+        write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
+      }
     }
-    if (tid == 0) part_stats[slot] = make_float4(sm.total.m, sm.total.s1, sm.total.t, 0.f);
   }
+}
+
+// Clears a workspace (hs_workspace_prepare): a fill kernel, not a memset, so that it may be captured.
+__global__ __launch_bounds__(256) void k_fill_zero(uint4* __restrict__ p, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __restrict__ part_stats,
@@ -519,7 +576,7 @@ __global__ __launch_bounds__(FIN_THREADS) void k_scan_finalize(const float4* __r
   const int64_t row = blockIdx.x;
   if (row_active != nullptr && row_active[row] == 0) return;
   if (row_index != nullptr && row_index[row] < 0) return;
-  merge_slices(part_stats + row * S, part_val + row * S * K, part_idx + row * S * K, S, K, inv_t, sm, tid, FIN_THREADS);
+  merge_slices<false>(part_stats + row * S, part_val + row * S * K, part_idx + row * S * K, S, K, inv_t, sm, tid, FIN_THREADS);
   write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
 }
 
@@ -527,18 +584,21 @@ size_t row_topk_workspace(int R, int V, int K) {
   if (R <= 0) return 0;
   ScanPlan p = plan_scan(R, V);
   size_t n = (size_t)R * p.splits;
-  return align_up(n * sizeof(float4), 256) + 2 * align_up(n * K * sizeof(float), 256);
+  return TICKET_BYTES + align_up(n * sizeof(float4), 256) + 2 * align_up(n * K * sizeof(float), 256);
 }
 
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
                           void* workspace, hipStream_t stream, ScanSlices* slices, const uint8_t* row_active,
-                          const int32_t* row_index, const float* logits2, int rows1) {
+                          const int32_t* row_index, const float* logits2, int rows1, bool prepared) {
   // (rows are the grid's second dimension)
   HS_REQUIRE(R <= 65535, HS_ERR_UNSUPPORTED, "row scan: %d rows in one call (at most 65535)", R);
   ScanPlan p = plan_scan(R, V);
   Carver c(workspace);
   size_t n = (size_t)R * p.splits;
+  // one counter per row, zero in a prepared workspace and left at zero; always the same leading part
+  // of the workspace, whatever the shape, so that calls of different shapes can share a prepared one
+  unsigned* tickets = c.take<unsigned>(TICKET_BYTES / sizeof(unsigned));
   float4* part_stats = c.take<float4>(n);
   float* part_val = c.take<float>(n * K);
   int* part_idx = c.take<int>(n * K);
@@ -546,20 +606,30 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   const bool vec = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 4 == 0) &&
                    (reinterpret_cast<uintptr_t>(logits2) % 16 == 0);
   dim3 grid(p.splits, R);
-#define HS_SCAN_LAUNCH(VEC, T)                                                                                      \
-  hipLaunchKernelGGL((k_scan_rows<VEC, T>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
-                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index, logits2, rows1)
-  if (p.threads == SCAN_BIG) {
-    if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG);
-    else HS_SCAN_LAUNCH(false, SCAN_BIG);
+  // one launch: the rows' last slices merge (needs the zeroed counters of a prepared workspace)
+  const bool fused = prepared && slices == nullptr && p.splits > 1 && p.splits * K <= FUSED_CAP;
+#define HS_SCAN_LAUNCH(VEC, T, F)                                                                                      \
+  hipLaunchKernelGGL((k_scan_rows<VEC, T, F>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
+                     part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index, logits2, rows1, tickets)
+  if (fused) {
+    if (p.threads == SCAN_BIG) {
+      if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, true);
+      else HS_SCAN_LAUNCH(false, SCAN_BIG, true);
+    } else {
+      if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, true);
+      else HS_SCAN_LAUNCH(false, SCAN_SMALL, true);
+    }
+  } else if (p.threads == SCAN_BIG) {
+    if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, false);
+    else HS_SCAN_LAUNCH(false, SCAN_BIG, false);
   } else {
-    if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL);
-    else HS_SCAN_LAUNCH(false, SCAN_SMALL);
+    if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, false);
+    else HS_SCAN_LAUNCH(false, SCAN_SMALL, false);
   }
 #undef HS_SCAN_LAUNCH
   hs_status st = launch_status("row scan");
   if (slices != nullptr) *slices = ScanSlices{part_val, part_idx, p.splits};
-  if (st != HS_OK || p.splits == 1 || slices != nullptr) return st;
+  if (st != HS_OK || p.splits == 1 || slices != nullptr || fused) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,
                      p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index);
   return launch_status("row scan merge");
@@ -575,7 +645,7 @@ extern "C" size_t hs_draft_entropy_topk_workspace(int32_t R, int32_t V, int32_t 
 static hs_status entropy_topk_impl(const float* logits, int64_t row_stride, const int32_t* row_index, int32_t R,
                                    int32_t V, int32_t K, float temperature, int32_t* topk_idx, float* topk_logp,
                                    float* ent_topk, float* ent_full, float* lse, void* workspace,
-                                   size_t workspace_bytes, hs_stream stream) {
+                                   size_t workspace_bytes, hs_stream stream, bool prepared = false) {
   hs::clear_error();
   HS_REQUIRE(R >= 0 && V >= 1, HS_ERR_SHAPE, "hs_draft_entropy_topk: R=%d V=%d", R, V);
   HS_REQUIRE(K >= 1 && K <= V, HS_ERR_SHAPE, "hs_draft_entropy_topk: K=%d must be in 1..V=%d", K, V);
@@ -590,7 +660,7 @@ static hs_status entropy_topk_impl(const float* logits, int64_t row_stride, cons
              HS_ERR_WORKSPACE, "hs_draft_entropy_topk: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
              workspace_bytes);
   return hs::row_topk_launch(logits, row_stride, R, V, K, temperature, topk_idx, topk_logp, ent_topk, ent_full, lse,
-                             workspace, static_cast<hipStream_t>(stream), nullptr, nullptr, row_index);
+                             workspace, static_cast<hipStream_t>(stream), nullptr, nullptr, row_index, nullptr, 0, prepared);
 }
 
 extern "C" hs_status hs_draft_entropy_topk(const float* logits, int64_t row_stride, int32_t R, int32_t V, int32_t K,
@@ -609,4 +679,27 @@ extern "C" hs_status hs_draft_entropy_topk_rows(const float* logits, int64_t row
   HS_REQUIRE(R <= 0 || row_index != nullptr, HS_ERR_NULL, "hs_draft_entropy_topk_rows: row_index is NULL");
   return entropy_topk_impl(logits, row_stride, row_index, R, V, K, temperature, topk_idx, topk_logp, ent_topk,
                            ent_full, lse, workspace, workspace_bytes, stream);
+}
+
+extern "C" hs_status hs_draft_entropy_topk_fused(const float* logits, int64_t row_stride, const int32_t* row_index,
+                                                 int32_t R, int32_t V, int32_t K, float temperature,
+                                                 int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full,
+                                                 float* lse, void* workspace, size_t workspace_bytes,
+                                                 hs_stream stream) {
+  return entropy_topk_impl(logits, row_stride, row_index, R, V, K, temperature, topk_idx, topk_logp, ent_topk,
+                           ent_full, lse, workspace, workspace_bytes, stream, true);
+}
+
+extern "C" hs_status hs_workspace_prepare(void* workspace, size_t workspace_bytes, hs_stream stream) {
+  hs::clear_error();
+  if (workspace_bytes == 0) return HS_OK;
+  HS_REQUIRE(workspace != nullptr, HS_ERR_NULL, "hs_workspace_prepare: NULL workspace");
+  HS_REQUIRE(reinterpret_cast<uintptr_t>(workspace) % 256 == 0 && workspace_bytes % 16 == 0, HS_ERR_WORKSPACE,
+             "hs_workspace_prepare: the workspace must be 256-byte aligned and a multiple of 16 bytes long (got %zu)",
+             workspace_bytes);
+  const size_t n16 = workspace_bytes / 16;
+  HS_REQUIRE((n16 + 255) / 256 <= 0x7fffffffull, HS_ERR_UNSUPPORTED, "hs_workspace_prepare: %zu bytes", workspace_bytes);
+  hipLaunchKernelGGL(hs::k_fill_zero, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<uint4*>(workspace), n16);
+  return hs::launch_status("workspace prepare");
 }

@@ -44,6 +44,8 @@ size_t row_topk_workspace(int R, int V, int K);
 // written.  `row_index` (device, may be NULL): result row r is computed from logits row
 // row_index[r]; a negative entry leaves row r's results as they are.  `logits2` (may be NULL):
 // rows rows1, rows1 + 1, ... are rows 0, 1, ... of this second array (same row stride).
+// `prepared`: the workspace was cleared by hs_workspace_prepare and has since been used by completed
+// calls of this kind only; rows cut into slices are then merged by the scan's own launch.
 struct ScanSlices {
   const float* val;
   const int32_t* idx;
@@ -53,7 +55,7 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,
                           void* workspace, hipStream_t stream, ScanSlices* slices = nullptr,
                           const uint8_t* row_active = nullptr, const int32_t* row_index = nullptr,
-                          const float* logits2 = nullptr, int rows1 = 0);
+                          const float* logits2 = nullptr, int rows1 = 0, bool prepared = false);
 
 #define HS_REQUIRE(cond, st, ...) \
   do {                            \

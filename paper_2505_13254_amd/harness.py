@@ -133,8 +133,9 @@ class Step:
 
     # ---- the four stages, each one C call
     def stage1(self):
+        # (one launch: the workspace was prepared when the step was built and only this call uses it)
         return hs.hs_draft_entropy_topk(self._logits("draft_rows"), self.w.topk, self.w.temperature,
-                                        out=self.t["s1_out"], ws=self.t["s1_ws"])
+                                        out=self.t["s1_out"], ws=self.t["s1_ws"], fused=True)
 
     def stage2(self):
         return hs.hs_tree_prune(self.t["cand_parent"], self.t["cand_logc"], self.t["cand_offsets"],
@@ -233,6 +234,7 @@ def build_step(w: W.Workload, seed: int = 0, layers: Optional[int] = None, accep
                        ent_full=torch.empty(R, dtype=torch.float32, device=device),
                        lse=torch.empty(R, dtype=torch.float32, device=device))
     t["s1_ws"] = hs.workspace(hs.lib().hs_draft_entropy_topk_workspace(R, w.V, w.topk), device)
+    hs.hs_workspace_prepare(t["s1_ws"])
     # stage 2
     cand_off = np.zeros(B + 1, np.int32)
     cand_off[1:] = np.cumsum([len(tr["parent"]) for tr in trees])
@@ -356,10 +358,10 @@ class AdaptiveStep:
         # The draft model's pass over the frontier is not part of this build: its logits rows exist for
         # all candidates beforehand, and the scan reads the frontier's rows where they lie.
         if first:
-            r = hs.hs_draft_entropy_topk(t["x_root"], w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"])
+            r = hs.hs_draft_entropy_topk(t["x_root"], w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"], fused=True)
         else:
             r = hs.hs_draft_entropy_topk(t["draft_all"], w.topk, w.temperature, out=t["s1_out"], ws=t["s1_ws"],
-                                         row_index=t["state"]["frontier_rows"])
+                                         row_index=t["state"]["frontier_rows"], fused=True)
         hs.hs_tree_expand(t["state"], r["topk_idx"], r["topk_logp"], r["ent_topk"], None, 1, h["cap"], w.frontier,
                           w.topk, first=first)
 
@@ -470,6 +472,7 @@ def build_adaptive(w: W.Workload, seed: int = 0, layers: Optional[int] = None, e
                        topk_logp=torch.empty((F, K), dtype=torch.float32, device=device),
                        ent_topk=torch.empty(F, dtype=torch.float32, device=device))
     t["s1_ws"] = hs.workspace(hs.lib().hs_draft_entropy_topk_workspace(F, w.V, K), device)
+    hs.hs_workspace_prepare(t["s1_ws"])          # (the level loop's scans run in one launch each from here on)
     t["state"] = hs.new_tree_state(1, cap, F, device)
     t["ctl"] = dict(phi=torch.empty(1, dtype=torch.float32, device=device))
     for k in ("pstar", "bin", "d_prime", "n_prime"):

@@ -104,6 +104,47 @@ def test_entropy_is_deterministic(G):
 
 
 # ------------------------------------------------------------------------------------------ prune
+@pytest.mark.parametrize("R,V,K", [(1, 128256, 10), (10, 128256, 10), (51, 128256, 10), (61, 32000, 1), (7, 5000, 64),
+                                   (40, 100003, 13), (300, 4099, 5)])
+def test_entropy_in_one_launch_on_a_prepared_workspace(G, R, V, K):
+    """hs_draft_entropy_topk_fused: the rows' last slices merge (one counter per row in a prepared
+    workspace, left at zero): against the checker, bit-identical to the two-launch call, on calls in a row
+    on one workspace (larger shape first, then smaller ones, then with a row index list)."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(R + V + K)
+    tau = np.exp(rs.uniform(np.log(0.3), np.log(8.0), size=(R, 1)))
+    x = (rs.normal(size=(R, V)) * tau).astype(np.float32)
+    x[0, : min(V, 3 * K)] = x[0, 0]                                   # ties across slices
+    xd = G.dev(x)
+    sizes = sorted({1, max(1, R // 3), R})
+    # (fewer rows are cut into more slices each: the workspace is sized for the largest need)
+    ws = hs.workspace(max(hs.lib().hs_draft_entropy_topk_workspace(r, V, K) for r in sizes + [4]), G.DEV)
+    ws.fill_(0x5A)                                                    # unknown content first ...
+    hs.hs_workspace_prepare(ws)                                       # ... then prepared, once
+    want = draft_entropy_topk(x, K, 1.0)
+    plain = {k: G.host(v) for k, v in hs.hs_draft_entropy_topk(xd, K, 1.0).items()}
+    for rep in range(3):
+        got = {k: G.host(v) for k, v in hs.hs_draft_entropy_topk(xd, K, 1.0, ws=ws, fused=True).items()}
+        assert np.array_equal(got["topk_idx"], want["topk_idx"])
+        for k in ("ent_topk", "ent_full"):
+            assert G.entropy_err(got[k], want[k]) <= 1.0, k
+        for k in plain:
+            assert got[k].tobytes() == plain[k].tobytes(), k          # same merge arithmetic: same bits
+    # fewer rows on the same workspace (other slice counts, other counters), then rows by index
+    for R2 in sizes:
+        got = {k: G.host(v) for k, v in hs.hs_draft_entropy_topk(xd[:R2], K, 1.0, ws=ws, fused=True).items()}
+        ref = {k: G.host(v) for k, v in hs.hs_draft_entropy_topk(xd[:R2], K, 1.0).items()}
+        for k in ref:
+            assert got[k].tobytes() == ref[k].tobytes(), (R2, k)
+    idx = np.asarray([R - 1, 0, -1, R // 2][: max(1, min(4, R))], np.int32)
+    out = {k: torch.full_like(v[: len(idx)], -3) for k, v in hs.hs_draft_entropy_topk(xd, K, 1.0).items()}
+    ref = {k: v.clone() for k, v in out.items()}
+    hs.hs_draft_entropy_topk(xd, K, 1.0, out=out, ws=ws, row_index=G.dev(idx, torch.int32), fused=True)
+    hs.hs_draft_entropy_topk(xd, K, 1.0, out=ref, row_index=G.dev(idx, torch.int32))
+    for k in ref:
+        assert G.host(out[k]).tobytes() == G.host(ref[k]).tobytes(), k
+
+
 def _prune_equal(got, want):
     for k in ("depth", "keep", "out_offsets", "out_src", "out_parent"):
         assert np.array_equal(got[k], want[k]), k
