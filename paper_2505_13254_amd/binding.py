@@ -57,6 +57,7 @@ _SIGNATURES = {
     "hs_kv_commit": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _vp]),
     "hs_tree_validate": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "hs_time_next_attention": (_c.c_int, [_vp, _vp]),
+    "hs_tree_attention_last_kernel": (_c.c_int32, []),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
     "hs_verify_accept_workspace_mode": (_sz, [_i32, _i32, _i32, _c.c_int]),
     "hs_verify_accept": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _f32, _vp, _i32,
@@ -478,6 +479,11 @@ def hs_time_next_attention(start_event, stop_event) -> None:
     if not h0 or not h1:
         raise ValueError("hs_time_next_attention: record each event once before handing it over")
     _check(lib().hs_time_next_attention(_c.c_void_p(h0), _c.c_void_p(h1)), "hs_time_next_attention")
+
+
+def hs_tree_attention_last_kernel() -> int:
+    """1: this thread's last tree-attention call ran on the matrix cores, 2: on the vector ALUs, 0: it launched nothing."""
+    return int(lib().hs_tree_attention_last_kernel())
 
 
 def hs_tree_validate(parent, token, node_offsets, *, stream=None) -> torch.Tensor:

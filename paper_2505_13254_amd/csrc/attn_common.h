@@ -12,6 +12,8 @@
 // denominator l (relative to m) and two pad floats (records stay 16-byte aligned);
 // slot = (node_global * Hq + h) * sp_max + split.
 #pragma once
+#include <cstddef>
+
 #include "hs_common.h"
 
 namespace hs {
@@ -80,10 +82,12 @@ struct AttnArgs {
   void* o;
   float* lse;
   float* part;
+  const unsigned* anc_tiles;  // ancestor table of large trees (matrix-core kernel), in the workspace; else NULL
   int n_tbl;       // > 0: work-list launch (1-D grid over the items of tbl[0 .. n_tbl)); 0: grid.y = sequence
   int n_items;
-  SeqEntry tbl[ATTN_TBL];
+  alignas(16) SeqEntry tbl[ATTN_TBL];  // (lanes fetch their entry with 16-byte loads)
 };
+static_assert(offsetof(AttnArgs, tbl) % 16 == 0, "16-byte loads of the table entries");
 
 // Prefix length of sequence s (plain launches read it on the device).
 __device__ __forceinline__ int64_t prefix_len_of(const AttnArgs& a, int s) {

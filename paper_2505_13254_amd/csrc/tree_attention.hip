@@ -18,6 +18,7 @@ namespace hs {
 hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t stream, hipEvent_t ev_start,
                            hipEvent_t ev_stop);
 bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale);
+size_t attn_mfma_table_bytes(int max_tree_rows, int64_t NN);
 
 constexpr int GEN_THREADS = 256;
 constexpr int GEN_ROWS = 16;  // rows per workgroup (4 per wave)
@@ -448,7 +449,9 @@ extern "C" size_t hs_tree_attention_workspace(int32_t B, int32_t NN, int64_t tot
   if (B <= 0 || NN <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || total_prefix < 0) return 0;
   // upper bound over every plan the launch may choose: splits are at least 512 tokens long
   const int64_t sp_bound = total_prefix / 512 + 1;
-  return part_bytes(NN, Hq, D, (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound));
+  // (+ the ancestor table that trees of more than 256 rows keep there: such a tree needs NN > 256)
+  return part_bytes(NN, Hq, D, (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound)) +
+         align_up(attn_mfma_table_bytes(NN < MAX_TREE_ROWS ? NN : MAX_TREE_ROWS, NN), 256);
 }
 
 extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
@@ -464,6 +467,10 @@ extern "C" hs_status hs_tree_attention(const void* q, const void* k_prefix, cons
 
 // Events that hs_time_next_attention left for this thread's next attention call.
 static thread_local hipEvent_t timing_start = nullptr, timing_stop = nullptr;
+// Kernel that this thread's last attention call launched (hs_tree_attention_last_kernel).
+static thread_local int last_kernel = 0;
+
+extern "C" int32_t hs_tree_attention_last_kernel(void) { return last_kernel; }
 
 extern "C" hs_status hs_time_next_attention(void* start_event, void* stop_event) {
   clear_error();
@@ -488,6 +495,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   const bool paged = block_table != nullptr;
   hipEvent_t ev_start = timing_start, ev_stop = timing_stop;  // one-shot, whatever this call comes to
   timing_start = timing_stop = nullptr;
+  last_kernel = 0;
   HS_REQUIRE(B >= 0, HS_ERR_SHAPE, "hs_tree_attention: B=%d", B);
   HS_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, HS_ERR_SHAPE, "hs_tree_attention: Hq=%d must be a multiple of Hkv=%d",
              Hq, Hkv);
@@ -535,7 +543,8 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   for (int s = 0; s < B; ++s) max_M = std::max(max_M, host_node_offsets[s + 1] - host_node_offsets[s]);
   auto aligned16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
   // (head-count limits: the matrix-core kernel numbers rows and lane offsets in narrow types)
-  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && Hq / Hkv <= 128 && Hkv <= 4096 && aligned16(q) &&
+  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && Hq / Hkv <= 128 && (int64_t)(Hq / Hkv) * max_M < 65536 &&
+                    Hkv <= 4096 && aligned16(q) &&
                     aligned16(k_prefix) && aligned16(v_prefix) && aligned16(k_tree) && aligned16(v_tree) &&
                     aligned16(o);
   AttnArgs a;
@@ -544,7 +553,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   a.block_table = block_table; a.max_blocks = max_blocks;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
   a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
-  a.n_tbl = 0; a.n_items = 0;
+  a.n_tbl = 0; a.n_items = 0; a.anc_tiles = nullptr;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the workspace query bounds the splits of a sequence the same way
   const int64_t sp_bound = total_prefix / 512 + 1;
@@ -566,7 +575,10 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   } else {
     a.split_len = 0; a.n_rb_max = 1;
   }
-  const size_t need = part_bytes(NN, Hq, D, a.sp_max);
+  const size_t table_bytes = mfma ? align_up(attn_mfma_table_bytes(max_M, NN), 256) : 0;
+  const size_t need = part_bytes(NN, Hq, D, a.sp_max) + table_bytes;
+  if (table_bytes != 0 && workspace != nullptr)
+    a.anc_tiles = reinterpret_cast<const unsigned*>(static_cast<const char*>(workspace) + part_bytes(NN, Hq, D, a.sp_max));
   HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
              HS_ERR_WORKSPACE, "hs_tree_attention: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
              workspace_bytes);
@@ -574,6 +586,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   if (mfma) {
     hs_status r = attn_mfma_launch(a, max_M, st, ev_start, ev_stop);
     if (r != HS_OK) return r;
+    last_kernel = 1;
   } else {
     dim3 grid((unsigned)(Hkv * plan.n_rb_max * plan.sp_max), (unsigned)B);
     if (dt == HS_F32 && D == 64) hipLaunchKernelGGL((k_attn_generic<float, 64>), grid, dim3(GEN_THREADS), 0, st, a);
@@ -582,6 +595,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
     else hipLaunchKernelGGL((k_attn_generic<bf16_t, 128>), grid, dim3(GEN_THREADS), 0, st, a);
     hs_status r = launch_status("tree attention");
     if (r != HS_OK) return r;
+    last_kernel = 2;
   }
   if (a.sp_max > 1) {
     const int64_t n_rows = (int64_t)NN * Hq;

@@ -34,7 +34,10 @@
 // finished) and requests the LDS fragments that the matrix instructions three steps ahead will
 // need, so matrix, vector and LDS pipes of a wave all have independent work at any time.
 //
-// The tree part (ancestor mask) is a bit table built in LDS from the parent pointers.
+// The tree part (ancestor mask) is a bit table built in LDS from the parent pointers (trees of up
+// to 256 rows).  Larger trees (BIG, up to 1024 rows) take the table from global memory, where
+// k_anc_tiles has laid it out per 64-key tile before the launch: the slice of a tree tile (two words
+// for each of the workgroup's 256 rows) travels into a ring in LDS together with the tile.
 //
 // K/V tiles go from HBM straight into LDS (global_load_lds_dwordx4, 16 bytes per lane, no staging
 // registers) through a ring of four tile buffers: one tile is being multiplied, the next one has
@@ -64,7 +67,9 @@ constexpr int MF_ROWS = 256;       // query rows per workgroup
 constexpr int MF_THREADS = 512;    // eight waves of 32 rows, two per SIMD
 constexpr int MF_TILE = 64;        // keys per LDS tile (two 32-key blocks)
 constexpr int MF_NBUF = 4;         // LDS ring: one tile in use, one landed, two on their way from HBM
-constexpr int MF_MAX_M = 256;      // tree rows per sequence (ancestor bit table: M x 8 words)
+constexpr int MF_MAX_M = 256;      // tree rows per sequence whose ancestor bit table (M x 8 words) is built in LDS
+constexpr int MF_BIG_M = 1024;     // tree rows per sequence with the table in global memory
+constexpr int MF_ANC_SLICE = 2 * MF_ROWS;  // words of a tree tile's mask slice: two per row of the workgroup
 constexpr int MF_ROW_BYTES = 256;  // one K or V row of a head: 128 bf16
 constexpr int MF_TILE_BYTES = MF_TILE * MF_ROW_BYTES;
 constexpr int MF_BLOCK_BYTES = 32 * MF_ROW_BYTES;
@@ -75,7 +80,48 @@ constexpr float MF_LN2 = 0.6931471805599453f;
 constexpr float MF_SUM_LIMIT = 0x1p64f;  // a denominator beyond it (or NaN) sends the pass to the exact path
 
 bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale) {
-  return D == 128 && dt == HS_BF16 && max_tree_rows <= MF_MAX_M && scale > 0.f;
+  return D == 128 && dt == HS_BF16 && max_tree_rows <= MF_BIG_M && scale > 0.f;
+}
+
+// Bytes of the ancestor table that launches with more than MF_MAX_M rows in a tree keep in the
+// workspace: 16 tiles x two words for every tree row of the batch (0: no such table is needed).
+size_t attn_mfma_table_bytes(int max_tree_rows, int64_t NN) {
+  return max_tree_rows > MF_MAX_M ? (size_t)NN * (MF_BIG_M / MF_TILE) * 8 : 0;
+}
+
+// Ancestor table of large trees, one slice per 64-key tile: words (2 i, 2 i + 1) of tile tt hold bit
+// j - 64 tt for every tree row j of [64 tt, 64 tt + 64) on the root path of tree row i (itself
+// included).  The table of the sequence whose first row is n0 starts at word 32 n0; tile tt of a
+// tree of M rows lies 2 M tt words further.  grid: (row chunks of 256, sequences).
+__global__ __launch_bounds__(256) void k_anc_tiles(const int32_t* __restrict__ parent, const int32_t* __restrict__ node_offsets,
+                                                   unsigned* __restrict__ table) {
+  __shared__ int par[MF_BIG_M];
+  const int s = blockIdx.y;
+  const int n0 = node_offsets[s];
+  int M = node_offsets[s + 1] - n0;
+  if (M > MF_BIG_M) M = MF_BIG_M;  // (the host has refused larger trees)
+  if ((int)blockIdx.x * 256 >= M) return;
+  for (int i = threadIdx.x; i < M; i += 256) par[i] = parent[n0 + i];
+  __syncthreads();
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M) return;
+  unsigned* out = table + (size_t)n0 * 32;
+  const int n_tt = (M + MF_TILE - 1) / MF_TILE;
+  // the path is walked once, from the row towards the root: row numbers fall, and so do the tiles
+  int j = i;
+  for (int tt = n_tt - 1; tt >= 0; --tt) {
+    const int lo = tt * MF_TILE;
+    unsigned w0 = 0, w1 = 0;
+    while (j >= lo) {
+      const int b = j - lo;
+      if (b < 32) w0 |= 1u << b;
+      else if (b < 64) w1 |= 1u << (b - 32);
+      const int up = par[j];
+      j = up < j ? up : -1;  // (a malformed tree cannot keep the walk from ending)
+    }
+    uint2 w = {w0, w1};
+    *reinterpret_cast<uint2*>(out + ((size_t)tt * M + i) * 2) = w;
+  }
 }
 
 // 16-byte chunk c (0..15) of row r lives at chunk position c ^ swz_key(r).  The key takes 16
@@ -130,8 +176,11 @@ __device__ __forceinline__ void wait_lds(int n) {  // n is a constant once the w
 #define MF_PIN() __builtin_amdgcn_sched_barrier(0)
 
 // PAGED: the prefix K/V live in pages of MF_TILE tokens ([page, token, Hkv, D]); a tile is a page.
-template <bool PAGED, bool ONCE>
+// BIG: trees of more than MF_MAX_M rows may occur; the ancestor table comes from a.anc_tiles.
+template <bool PAGED, bool ONCE, bool BIG>
 __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_max) {
+  static_assert(!(BIG && ONCE), "more than 256 tree rows are several row groups");
+  static_assert(MF_NBUF * MF_ANC_SLICE == MF_MAX_M * 8, "the slice ring of large trees takes the place of the table");
   __shared__ __attribute__((aligned(16))) char lds_k[MF_NBUF][MF_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) char lds_v[MF_NBUF][MF_TILE_BYTES];
   __shared__ unsigned anc[MF_MAX_M * 8];
@@ -155,6 +204,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const void* const h_v_tree = a.v_tree;
   const int32_t* const h_parent = a.parent;
   void* const h_o = a.o;
+  const unsigned* const h_anc = a.anc_tiles;
   float* const h_lse = a.lse;
   float* const h_part = a.part;
   const float h_scale = a.scale;
@@ -234,7 +284,11 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const int64_t k_lo = (int64_t)sp * tiles_per_split * MF_TILE;
   const int64_t k_hi = last_split ? L : k_lo + (int64_t)tiles_per_split * MF_TILE;
   const int n_ptiles = (int)((k_hi - k_lo + MF_TILE - 1) / MF_TILE);
-  const int n_ttiles = last_split ? (M + MF_TILE - 1) / MF_TILE : 0;
+  // (large trees: tree rows behind the last row of this row group are on nobody's root path, their tiles are left out)
+  int tree_keys = M;
+  if constexpr (BIG)
+    if ((rg + 1) * MF_ROWS < R) tree_keys = ((rg + 1) * MF_ROWS - 1) / G + 1;
+  const int n_ttiles = last_split ? (tree_keys + MF_TILE - 1) / MF_TILE : 0;
   const int n_tiles = n_ptiles + n_ttiles;  // >= 1: a split holds prefix keys, or it is the last one
   const int n_full = (int)((k_hi - k_lo) / MF_TILE);  // leading tiles made of 64 prefix keys
   const int n_plain = (int)((k_hi - k_lo) >> 5);      // leading blocks that need no mask
@@ -250,6 +304,17 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   const unsigned dma_chunk = (unsigned)(((tid & 15) ^ swz_key(dma_row)) << 4);         // swz_key(row + 32) == swz_key(row)
   const unsigned lane_off0 = (unsigned)(dma_row * (int)tok_stride) + dma_chunk;        // inside a full tile: fixed
   const unsigned lane_off1 = lane_off0 + (unsigned)(32 * (int)tok_stride);
+  // Large trees: lane l of wave w fetches word l % 2 of the workgroup's row 32 w + l / 2 (rows past
+  // the end: of the last row) from a tile's slice of this sequence's table.
+  const unsigned lds_anc_addr = (unsigned)(uintptr_t)(lds_ptr)&anc[0];
+  const unsigned* anc_tbl = nullptr;
+  unsigned anc_lane_off = 0;
+  if constexpr (BIG) {
+    anc_tbl = h_anc + (size_t)(h_tree_shared ? 0 : n0) * 32;
+    int r = rg * MF_ROWS + wave * 32 + (lane >> 1);
+    r = r < R ? r : R - 1;
+    anc_lane_off = (unsigned)(((r / G) * 2 + (lane & 1)) * 4);
+  }
   // Paged caches: the pages of this split's tiles (at most 256) are staged in LDS; the requests
   // go out here, before the Q rows are asked for, so that waiting for them waits for nothing else.
   // A tile's page is then one LDS read.  (That read is older than every fragment read requested
@@ -287,6 +352,19 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     const int r1 = dma_row + 32 < rows ? dma_row + 32 : rows - 1;
     const unsigned ring = (unsigned)(t % MF_NBUF) * MF_TILE_BYTES + wave_lds;
     const int64_t off = tree ? base * tok_stride : prefix_tile(t);
+    if constexpr (BIG) {
+      // The tile's slice of the ancestor table goes first: one more load of this wave, older than the
+      // tile's four, so a wait that leaves the four youngest loads pending has seen it land.
+      if (tree) {
+        const unsigned* src = anc_tbl + (size_t)(t - n_ptiles) * (2 * (size_t)M);
+        const unsigned dst = lds_anc_addr + (unsigned)(t % MF_NBUF) * (MF_ANC_SLICE * 4) + (unsigned)(wave * 256);
+        unsigned saved;
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved)
+                     : "s"(dst), "v"(anc_lane_off), "s"(src)
+                     : "memory");
+      }
+    }
     lds_dma_tile<ONCE>(ks + off, vs + off, (unsigned)(r0 * (int)tok_stride) + dma_chunk,
                  (unsigned)(r1 * (int)tok_stride) + dma_chunk, lds_k_addr + ring, lds_v_addr + ring,
                  lds_k_addr + ring + MF_BLOCK_BYTES, lds_v_addr + ring + MF_BLOCK_BYTES);
@@ -331,8 +409,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   // behind it.  Here the waits count the younger loads (wait_vm), and an empty asm statement that
   // "writes" the registers keeps their uses behind the wait.  Lanes without a row of their own load
   // a valid row (the last one; tree row 0) and zero it afterwards.
-  int my_parent;
-  {
+  int my_parent = 0;
+  if constexpr (!BIG) {
     const int32_t* src = h_parent + (h_tree_shared ? 0 : n0) + (tid < M ? tid : 0);  // (one tree for all entries, or each its own)
     asm volatile("global_load_dword %0, %1, off" : "=v"(my_parent) : "v"(src) : "memory");
   }
@@ -352,13 +430,17 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   }
   issue(0);
   if (n_tiles > 1) issue(1);
+  // (large trees: a leading tree tile brings one load more; waiting for a multiple of four at most
+  // as large as the count waits for no less)
   const int first_tile_loads = 2 * MF_LOADS * (n_tiles < 2 ? n_tiles : 2);
-  wait_vm(8 + first_tile_loads);  // the parent pointers are there (the eight Q loads and the tiles are younger)
-  asm volatile("" : "+v"(my_parent));
+  if constexpr (!BIG) {
+    wait_vm(8 + first_tile_loads);  // the parent pointers are there (the eight Q loads and the tiles are younger)
+    asm volatile("" : "+v"(my_parent));
+  }
 
   // ---- ancestor bit table: bit j of row i's words is set iff tree row j is on the root path of i.
   // The parent pointers are staged in LDS and the paths are walked there.
-  if (last_split) {
+  if (!BIG && last_split) {
     if (tid < M) par_lds[tid] = my_parent;
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (tid < M) {
@@ -444,7 +526,9 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     const int t = blk >> 1;
     if (t >= n_ptiles) {
       const int bbase = (t - n_ptiles) * MF_TILE + (blk & 1) * 32;
-      const unsigned word = bbase < M ? anc[tree_row * 8 + (bbase >> 5)] : 0u;
+      unsigned word;
+      if constexpr (BIG) word = bbase < M ? anc[(t % MF_NBUF) * MF_ANC_SLICE + (wave * 32 + col) * 2 + (blk & 1)] : 0u;
+      else word = bbase < M ? anc[tree_row * 8 + (bbase >> 5)] : 0u;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int bit = 8 * (v >> 2) + 4 * half + (v & 3);
@@ -757,15 +841,25 @@ hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t str
   dim3 grid((unsigned)(a.Hkv * n_rg_max * a.sp_max), (unsigned)a.B);
   if (a.n_tbl > 0) grid = dim3((unsigned)a.n_items, 1u);
   const bool once = n_rg_max == 1;  // every (sequence, head) is one row group: its keys have one reader
+  const bool big = max_tree_rows > MF_MAX_M;
   const dim3 block(MF_THREADS);
-#define MF_LAUNCH(PAGED, ONCE) \
-  hipExtLaunchKernelGGL((k_attn_mfma<PAGED, ONCE>), grid, block, 0, stream, ev_start, ev_stop, 0, a, n_rg_max)
+  if (big) {
+    if (a.anc_tiles == nullptr) return fail(HS_ERR_WORKSPACE, "tree attention: trees of %d rows need the ancestor table", max_tree_rows);
+    const dim3 tgrid((unsigned)((max_tree_rows + 255) / 256), (unsigned)(a.tree_shared ? 1 : a.B));
+    hipLaunchKernelGGL(k_anc_tiles, tgrid, dim3(256), 0, stream, a.parent, a.node_offsets, const_cast<unsigned*>(a.anc_tiles));
+    hs_status r = launch_status("tree attention (ancestor table)");
+    if (r != HS_OK) return r;
+  }
+#define MF_LAUNCH(PAGED, ONCE, BIG) \
+  hipExtLaunchKernelGGL((k_attn_mfma<PAGED, ONCE, BIG>), grid, block, 0, stream, ev_start, ev_stop, 0, a, n_rg_max)
   if (a.block_table != nullptr) {
-    if (once) MF_LAUNCH(true, true);
-    else MF_LAUNCH(true, false);
+    if (big) MF_LAUNCH(true, false, true);
+    else if (once) MF_LAUNCH(true, true, false);
+    else MF_LAUNCH(true, false, false);
   } else {
-    if (once) MF_LAUNCH(false, true);
-    else MF_LAUNCH(false, false);
+    if (big) MF_LAUNCH(false, false, true);
+    else if (once) MF_LAUNCH(false, true, false);
+    else MF_LAUNCH(false, false, false);
   }
 #undef MF_LAUNCH
   return launch_status("tree attention (mfma)");

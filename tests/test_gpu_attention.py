@@ -209,13 +209,50 @@ def test_events_attached_to_the_attention_kernel(G):
     assert hs.lib().hs_time_next_attention(None, ctypes.c_void_p(e1.cuda_event)) != 0   # half a pair is refused
 
 
-@pytest.mark.parametrize("M,L", [(256, 200), (257, 100), (1024, 70)])
-def test_tree_row_limits(G, M, L):
-    """256 rows per tree is what the matrix-core kernel takes (four row groups per KV head at G = 4);
-    one row more goes to the scalar kernel, whose limit is 1024 rows."""
-    w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2)])
+@pytest.mark.parametrize("M,L", [(256, 200), (257, 100), (1024, 70), (513, 0), (700, 1300)])
+def test_tree_row_limits(G, M, L, hq, hkv):
+    """Trees of up to 256 rows have their ancestor table built inside the attention kernel; larger ones
+    (up to the limit of 1024 rows) take it from a table laid out per key tile by a launch of its own.
+    Both run on the matrix cores.  G = 4, 1 and 8 query heads per KV head: up to 32 row groups; L = 0:
+    the leading tiles are tree tiles."""
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[2], Hq=hq, Hkv=hkv)
     rs = np.random.RandomState(M)
     _compare(G, _case(w, 13, [_random_parents(rs, M, back=12)], [L], "unit"), "bf16")
+    assert hs.hs_tree_attention_last_kernel() == 1
+
+
+@pytest.mark.parametrize("shape", ["chain", "star", "deep_then_wide"])
+def test_large_trees_of_extreme_shape(G, shape):
+    """600 rows as one chain (every earlier row is an ancestor: all mask bits set below the diagonal), as a
+    star (only the root and the row itself) and as a chain of 300 whose last node has 299 children."""
+    import paper_2505_13254_amd as hs
+    M = 600
+    par = {"chain": [-1] + list(range(M - 1)), "star": [-1] + [0] * (M - 1),
+           "deep_then_wide": [-1] + list(range(300)) + [300] * (M - 301)}[shape]
+    w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
+    _compare(G, _case(w, 15, [par], [130], "peaky"), "bf16")
+    assert hs.hs_tree_attention_last_kernel() == 1
+
+
+@pytest.mark.parametrize("seed", [3, 4])
+def test_ragged_batches_with_large_trees(G, seed):
+    """Batches that mix trees of a few rows with trees beyond 256 rows, prefixes from nothing to several key
+    splits, every input variant (planted large scores included)."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(seed)
+    for it in range(8):
+        hq, hkv = [(8, 2), (8, 8), (16, 2), (4, 1)][rs.randint(4)]
+        w = W.small(W.WORKLOADS[2], Hq=hq, Hkv=hkv)
+        B = int(rs.randint(2, 6))
+        sizes = [int(rs.choice([0, 2, 61, 256, 257, 300, 640, 1024])) for _ in range(B)]
+        sizes[int(rs.randint(B))] = int(rs.choice([257, 321, 777]))
+        Ls = [int(rs.choice([0, 1, 63, 64, 500, 1300, 2049, 4100])) for _ in range(B)]
+        parents = [_random_parents(rs, n, back=int(rs.choice([2, 6, 40]))) if n else [] for n in sizes]
+        variant = ["config", "unit", "peaky", "hot"][rs.randint(4)]
+        _compare(G, _case(w, 1000 * seed + it, parents, Ls, variant), "bf16", big_scores=variant == "hot")
+        assert hs.hs_tree_attention_last_kernel() == 1
 
 
 def test_more_tree_rows_than_supported_is_an_error(G):
@@ -246,7 +283,7 @@ def test_random_ragged_batches(G, seed):
         _compare(G, _case(w, 100 * seed + it, parents, Ls, variant), "bf16")
 
 
-@pytest.mark.parametrize("wid,M,B", [(2, 61, 5), (2, 100, 3), (1, 16, 4)])
+@pytest.mark.parametrize("wid,M,B", [(2, 61, 5), (2, 100, 3), (2, 300, 3), (1, 16, 4)])
 def test_entries_that_share_one_tree(G, wid, M, B):
     """hs_tree_attention_shared_tree: B entries (different Q, K, V and prefix lengths) verify one tree
     passed once; the result equals the checker's on the tree repeated per entry, and bit for bit the
