@@ -177,33 +177,63 @@ __device__ __forceinline__ void st_dev(int* p, int v) { __hip_atomic_store(p, v,
 // COHERENT: the slices were written by other workgroups of the same launch (ld_dev).
 // Leaves the row's statistics in sm.total and its K best pairs, in order, in sm.ov / sm.oi.
 // Called by all `nthreads` threads of the workgroup (tid 0..nthreads-1); ends with a barrier.
+// Everything the merge reads from memory is requested at once (one trip, which is most of its
+// time when the slices come from other workgroups): the lists by all threads, the statistics by the
+// last wave.  Then the K-th best list head becomes a threshold (with at least K lists), which only
+// a few entries pass, and those are ranked by counting.
 template <bool COHERENT, int CAP>
 __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, const int* pi, int S, int K,
                                              float inv_t, MergeScratch<CAP>& sm, int tid, int nthreads) {
   const int lane = tid & 63;
-  for (int e = tid; e < S * K; e += nthreads) sm.rank[e] = 0;
-  if (tid < 64) {
-    Stats a = stats_empty();
-    float hv = -HS_INF;
-    int hi = INT_MAX;
-    if (lane < S) {
-      if (COHERENT) {
-        const float* sf = reinterpret_cast<const float*>(st + lane);
-        a = Stats{ld_dev(sf), ld_dev(sf + 1), ld_dev(sf + 2)};
-        hv = ld_dev(pv + lane * K);
-        hi = ld_dev(pi + lane * K);
-      } else {
-        const float4 f = st[lane];
-        a = Stats{f.x, f.y, f.z};
-        hv = pv[lane * K];
-        hi = pi[lane * K];
-      }
+  __shared__ float head_v[MAX_SPLITS];
+  __shared__ int head_i[MAX_SPLITS];
+  constexpr int PER = 4;  // entries a thread keeps in registers (a trip covers PER x nthreads of the S x K)
+  const int n_all = S * K;
+  float ev[PER];
+  int ei[PER];
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const int e = tid + q * nthreads;
+    ev[q] = -HS_INF;
+    ei[q] = INT_MAX;
+    if (e < n_all) {
+      ev[q] = COHERENT ? ld_dev(pv + e) : pv[e];
+      ei[q] = COHERENT ? ld_dev(pi + e) : pi[e];
     }
+  }
+  Stats a = stats_empty();
+  const bool stats_wave = tid >= nthreads - 64;
+  if (stats_wave && lane < S) {
+    if (COHERENT) {
+      const float* sf = reinterpret_cast<const float*>(st + lane);
+      a = Stats{ld_dev(sf), ld_dev(sf + 1), ld_dev(sf + 2)};
+    } else {
+      const float4 f = st[lane];
+      a = Stats{f.x, f.y, f.z};
+    }
+  }
+  for (int e = tid; e < n_all; e += nthreads) sm.rank[e] = 0;
+  if (tid == 0) sm.cnt = 0;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const int e = tid + q * nthreads;
+    if (e < n_all && e % K == 0) {
+      head_v[e / K] = ev[q];
+      head_i[e / K] = ei[q];
+    }
+  }
+  if (stats_wave) {
     a = stats_wave_sum(a, inv_t);
+    if (lane == 0) sm.total = a;
+  }
+  __syncthreads();
+  if (tid < 64) {
     // threshold: the K-th best list head when there are at least K lists, else "everything passes"
     float tv = -HS_INF;
     int ti = INT_MAX;
     if (S >= K) {
+      const float hv = lane < S ? head_v[lane] : -HS_INF;
+      const int hi = lane < S ? head_i[lane] : INT_MAX;
       int r = wave_rank(hv, hi, S);
       unsigned long long who = __ballot(r == K - 1 && lane < S);
       if (who != 0ull) {
@@ -213,22 +243,29 @@ __device__ __forceinline__ void merge_slices(const float4* st, const float* pv, 
       }
     }
     if (lane == 0) {
-      sm.total = a;
       sm.thr_v = tv;
       sm.thr_i = ti;
-      sm.cnt = 0;
     }
   }
   __syncthreads();
   {
     const float tv = sm.thr_v;
     const int ti = sm.thr_i;
-    for (int e = tid; e < S * K; e += nthreads) {
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      if (ei[q] != INT_MAX && !better(tv, ti, ev[q], ei[q])) {  // (INT_MAX: an unused list entry, or none)
+        int pos = atomicAdd(&sm.cnt, 1);  // order of arrival does not matter: ranks are computed below
+        sm.cv[pos] = ev[q];               // (at most S * K <= CAP entries)
+        sm.ci[pos] = ei[q];
+      }
+    }
+    // (more entries than PER x nthreads: the rest in further trips)
+    for (int e = tid + PER * nthreads; e < n_all; e += nthreads) {
       float v = COHERENT ? ld_dev(pv + e) : pv[e];
       int i = COHERENT ? ld_dev(pi + e) : pi[e];
-      if (i != INT_MAX && !better(tv, ti, v, i)) {  // (INT_MAX: an unused list entry)
-        int pos = atomicAdd(&sm.cnt, 1);  // order of arrival does not matter: ranks are computed below
-        sm.cv[pos] = v;                   // (at most S * K <= FIN_CAP entries)
+      if (i != INT_MAX && !better(tv, ti, v, i)) {
+        int pos = atomicAdd(&sm.cnt, 1);
+        sm.cv[pos] = v;
         sm.ci[pos] = i;
       }
     }
@@ -280,7 +317,7 @@ __device__ __forceinline__ void write_row(const MergeScratch<CAP>& sm, int64_t r
 // puts the counter back to zero for the next launch, merges the slices and writes the row.
 constexpr int FUSED_CAP = 1024;  // slices x K that the merging workgroup's scratch holds
 constexpr size_t TICKET_BYTES = 65536 * sizeof(unsigned);  // a counter for each of the at most 65535 rows of a call
-template <bool VEC, int SCAN_THREADS, bool FUSED>
+template <bool VEC, int SCAN_THREADS, bool FUSED, int NBUF>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restrict__ logits, int64_t row_stride,
                                                             int V, int K, float inv_t, int tiles_per_wg,
                                                             float4* __restrict__ part_stats,
@@ -457,35 +494,32 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     }
 #undef HS_IDX
   };
-  // Three register buffers, two tiles in flight: the loads of tile t + 2 are requested before tile
-  // t is processed (one workgroup per compute unit: what is in flight bounds the bandwidth).  The
-  // steady-state loop requests without a condition, so that the wait before a tile's values counts
-  // exactly the two younger tiles; the last tiles run through the guarded copy below.
-  float b0[SCAN_VPT], b1[SCAN_VPT], b2[SCAN_VPT];
+  // NBUF register buffers, NBUF - 1 tiles in flight: the loads of tile t + NBUF - 1 are requested
+  // before tile t is processed (what is in flight bounds the bandwidth).  The steady-state loop
+  // requests without a condition, so that the wait before a tile's values counts exactly the younger
+  // tiles; the last tiles run through the guarded copy below.
+  float buf[NBUF][SCAN_VPT];
   // (whole tiles by the unconditional loads: the guarded ones wait for each other)
-  if (n_full > 0) load_full_tile(0, b0);
-  else if (n_my > 0) load_tile(0, b0);
-  if (n_full > 1) load_full_tile(1, b1);
-  else if (n_my > 1) load_tile(1, b1);
-  int tile = 0;
-  for (; tile + 4 < n_full; tile += 3) {
-    load_full_tile(tile + 2, b2);
-    process(b0, tile);
-    load_full_tile(tile + 3, b0);
-    process(b1, tile + 1);
-    load_full_tile(tile + 4, b1);
-    process(b2, tile + 2);
+#pragma unroll
+  for (int b = 0; b < NBUF - 1; ++b) {
+    if (b < n_full) load_full_tile(b, buf[b]);
+    else if (b < n_my) load_tile(b, buf[b]);
   }
-  for (; tile < n_my; tile += 3) {
-    if (tile + 2 < n_my) load_tile(tile + 2, b2);
-    process(b0, tile);
-    if (tile + 1 < n_my) {
-      if (tile + 3 < n_my) load_tile(tile + 3, b0);
-      process(b1, tile + 1);
+  int tile = 0;
+  for (; tile + 2 * NBUF - 2 < n_full; tile += NBUF) {
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b) {
+      load_full_tile(tile + b + NBUF - 1, buf[(b + NBUF - 1) % NBUF]);
+      process(buf[b], tile + b);
     }
-    if (tile + 2 < n_my) {
-      if (tile + 4 < n_my) load_tile(tile + 4, b1);
-      process(b2, tile + 2);
+  }
+  for (; tile < n_my; tile += NBUF) {
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b) {
+      if (tile + b < n_my) {
+        if (tile + b + NBUF - 1 < n_my) load_tile(tile + b + NBUF - 1, buf[(b + NBUF - 1) % NBUF]);
+        process(buf[b], tile + b);
+      }
     }
   }
 
@@ -609,7 +643,7 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   // one launch: the rows' last slices merge (needs the zeroed counters of a prepared workspace)
   const bool fused = prepared && slices == nullptr && p.splits > 1 && p.splits * K <= FUSED_CAP;
 #define HS_SCAN_LAUNCH(VEC, T, F)                                                                                      \
-  hipLaunchKernelGGL((k_scan_rows<VEC, T, F>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
+  hipLaunchKernelGGL((k_scan_rows<VEC, T, F, 3>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
                      part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index, logits2, rows1, tickets)
   if (fused) {
     if (p.threads == SCAN_BIG) {
