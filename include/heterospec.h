@@ -214,7 +214,8 @@ hs_status hs_tree_prune_static(const int32_t* parent, const float* logc, const i
  *   hs_kv_commit, say) attends to the lengths of the capture; capture one graph per shape instead.
  *   lse [NN,Hq] float: ln of the softmax denominator (of the scaled scores); may be NULL.
  * Requires Hq % Hkv == 0, D in {64, 128}, at most 1024 tree rows per sequence.
- * bfloat16 with D = 128 runs on the matrix cores; when a sequence has more than 256 tree rows, a
+ * bfloat16 runs on the matrix cores (D = 64: with an even number of KV heads, which the kernel takes in
+ * pairs); when a sequence has more than 256 tree rows, a
  * small launch ahead of the attention kernel writes the trees' ancestor table into the workspace
  * (128 bytes per tree row, included in the workspace query).
  */
@@ -464,8 +465,9 @@ hs_status hs_time_next_attention(void* start_event, void* stop_event);
 /* hs_tree_attention_last_kernel  (debugging aid, not a step of the method)
  *
  * Which kernel the calling thread's last hs_tree_attention / _lens / _paged / _shared_tree call
- * launched: 1 = the matrix-core kernel (bfloat16, D = 128, 16-byte aligned tensors, at most 1024 tree
- * rows per sequence with G * rows < 65536), 2 = the vector-ALU kernel (everything else),
+ * launched: 1 = the matrix-core kernel (bfloat16; D = 128, or D = 64 with an even number of KV heads;
+ * 16-byte aligned tensors; G * rows < 65536 for G = Hq / Hkv, twice that at D = 64),
+ * 2 = the vector-ALU kernel (everything else),
  * 0 = none (no such call yet, an empty batch, or the call failed before its launch). */
 int32_t hs_tree_attention_last_kernel(void);
 

@@ -21,7 +21,6 @@ namespace hs {
 typedef unsigned short bf16_t;  // raw bfloat16 bits
 
 constexpr int ATTN_REC_PAD = 4;  // floats after o[D] in a partial record: m, l, pad, pad
-#define ATTN_REC (128 + ATTN_REC_PAD)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __builtin_bit_cast(float, (unsigned)b << 16); }
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest, ties to even
@@ -75,6 +74,7 @@ struct AttnArgs {
   const int32_t* block_table;  // paged caches: page of each 64-token block, row s at s * max_blocks; else NULL
   int max_blocks;
   int B, Hq, Hkv, G;
+  int half;        // 1 (matrix-core kernel, D = 64): Hkv counts pairs of KV heads and G the 2 Hq / Hkv query heads of a pair
   float scale;
   int split_len;   // prefix tokens per split (multiple of 64)
   int sp_max;      // largest split count of any sequence; 1 = results are written directly

@@ -352,7 +352,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
       items += (int64_t)a.Hkv * nsp * q.rg;
       if (big > mx) mx = big;
       if (one_last < mn) mn = one_last;
-      if (nsp > 1) rec_bytes += (double)q.M * a.Hq * nsp * ATTN_REC * 4 * 2;  // written, then read
+      if (nsp > 1) rec_bytes += (double)q.M * a.Hq * nsp * ((a.half ? 64 : 128) + ATTN_REC_PAD) * 4 * 2;  // written, then read
       ord[i] = i;
       seq_cost[i] = (float)per * plan_tile_us(q.waves0);
     }
@@ -543,15 +543,19 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   for (int s = 0; s < B; ++s) max_M = std::max(max_M, host_node_offsets[s + 1] - host_node_offsets[s]);
   auto aligned16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
   // (head-count limits: the matrix-core kernel numbers rows and lane offsets in narrow types)
-  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && Hq / Hkv <= 128 && (int64_t)(Hq / Hkv) * max_M < 65536 &&
-                    Hkv <= 4096 && aligned16(q) &&
+  // D = 64: the matrix-core kernel takes the KV heads in pairs (their number must be even); a pair
+  // then has twice the query heads
+  const bool pairs = D == 64;
+  const int kv_units = pairs ? Hkv / 2 : Hkv, g_unit = pairs ? 2 * (Hq / Hkv) : Hq / Hkv;
+  const bool mfma = attn_mfma_supported(D, dt, max_M, scale) && (!pairs || Hkv % 2 == 0) && g_unit <= 128 &&
+                    (int64_t)g_unit * max_M < 65536 && Hkv <= 4096 && aligned16(q) &&
                     aligned16(k_prefix) && aligned16(v_prefix) && aligned16(k_tree) && aligned16(v_tree) &&
                     aligned16(o);
   AttnArgs a;
   a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_tree = k_tree; a.v_tree = v_tree;
   a.parent = parent; a.tree_shared = tree_shared ? 1 : 0; a.node_offsets = node_offsets; a.prefix_offsets = prefix_offsets; a.prefix_lens = prefix_lens;
   a.block_table = block_table; a.max_blocks = max_blocks;
-  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.scale = scale;
+  a.B = B; a.Hq = Hq; a.Hkv = mfma ? kv_units : Hkv; a.G = mfma ? g_unit : Hq / Hkv; a.half = mfma && pairs ? 1 : 0; a.scale = scale;
   a.o = o; a.lse = lse; a.part = static_cast<float*>(workspace);
   a.n_tbl = 0; a.n_items = 0; a.anc_tiles = nullptr;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -562,7 +566,7 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   AttnPlan plan{};
   if (!(mfma && plan_worklist(a, host_node_offsets, host_prefix_offsets, host_prefix_lens, B, sp_cap))) {
     a.n_tbl = 0;
-    plan = plan_attention(host_node_offsets, host_prefix_offsets, host_prefix_lens, B, Hq, Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
+    plan = plan_attention(host_node_offsets, host_prefix_offsets, host_prefix_lens, B, Hq, a.Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
     while (plan.sp_max > sp_cap) {
       plan.split_len *= 2;
       plan.sp_max = splits_of(plan.max_L, plan.split_len);

@@ -1,4 +1,5 @@
-// bfloat16 tree attention on the matrix cores (head dimension 128).
+// bfloat16 tree attention on the matrix cores (head dimension 128; head dimension 64 by taking
+// the KV heads in pairs, see HALF below).
 //
 // One workgroup = up to 256 query rows of one (sequence, KV head, key split); each of its eight
 // waves owns 32 rows and keeps their output accumulators in registers for the whole pass, so K and
@@ -79,8 +80,9 @@ constexpr float MF_LOG2E = 1.4426950408889634f;
 constexpr float MF_LN2 = 0.6931471805599453f;
 constexpr float MF_SUM_LIMIT = 0x1p64f;  // a denominator beyond it (or NaN) sends the pass to the exact path
 
+// (D = 64: the caller also makes sure that the number of KV heads is even)
 bool attn_mfma_supported(int D, hs_dtype dt, int max_tree_rows, float scale) {
-  return D == 128 && dt == HS_BF16 && max_tree_rows <= MF_BIG_M && scale > 0.f;
+  return (D == 128 || D == 64) && dt == HS_BF16 && max_tree_rows <= MF_BIG_M && scale > 0.f;
 }
 
 // Bytes of the ancestor table that launches with more than MF_MAX_M rows in a tree keep in the
@@ -177,8 +179,15 @@ __device__ __forceinline__ void wait_lds(int n) {  // n is a constant once the w
 
 // PAGED: the prefix K/V live in pages of MF_TILE tokens ([page, token, Hkv, D]); a tile is a page.
 // BIG: trees of more than MF_MAX_M rows may occur; the ancestor table comes from a.anc_tiles.
-template <bool PAGED, bool ONCE, bool BIG>
+// HALF: head dimension 64.  Two neighbouring KV heads of a token are 256 contiguous bytes, i.e. one
+// row of this kernel, and a.Hkv / a.G count such pairs and the 2 G query heads that read them.  A
+// query row is widened to 128 elements with zeros on the other head's side, so its scores see its own
+// KV head only; the second product yields both heads' values and the row's own half is stored.  The
+// matrix cores do twice the arithmetic; K and V are still read once, in whole 256-byte rows.
+template <bool PAGED, bool ONCE, bool BIG, bool HALF>
 __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_max) {
+  constexpr int Q_ROW_BYTES = HALF ? MF_ROW_BYTES / 2 : MF_ROW_BYTES;  // a row of Q and of O
+  constexpr int Q_LOADS = HALF ? 4 : 8;                                 // 16-byte loads of a lane's part of it
   static_assert(!(BIG && ONCE), "more than 256 tree rows are several row groups");
   static_assert(MF_NBUF * MF_ANC_SLICE == MF_MAX_M * 8, "the slice ring of large trees takes the place of the table");
   __shared__ __attribute__((aligned(16))) char lds_k[MF_NBUF][MF_TILE_BYTES];
@@ -417,15 +426,17 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   uintx4 qraw[8];
   int tree_row;
   bool row_real;
+  bool q_upper = false;  // HALF: this row's query head reads the second KV head of the pair
   {
     const int r = row_base + col;
     const int rc = r < R ? r : R - 1;
     const int i = div_G(rc), gi = rc - i * G;
     tree_row = i;
     row_real = r < R;
-    const char* qrow = static_cast<const char*>(h_q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES + half * 16;
+    if constexpr (HALF) q_upper = 2 * gi >= G;
+    const char* qrow = static_cast<const char*>(h_q) + ((int64_t)(n0 + i) * Hq + g * G + gi) * Q_ROW_BYTES + half * 16;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
+    for (int kk = 0; kk < Q_LOADS; ++kk)
       asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qraw[kk]) : "v"(qrow), "n"(32 * kk) : "memory");
   }
   issue(0);
@@ -434,7 +445,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   // as large as the count waits for no less)
   const int first_tile_loads = 2 * MF_LOADS * (n_tiles < 2 ? n_tiles : 2);
   if constexpr (!BIG) {
-    wait_vm(8 + first_tile_loads);  // the parent pointers are there (the eight Q loads and the tiles are younger)
+    wait_vm(Q_LOADS + first_tile_loads);  // the parent pointers are there (the Q loads and the tiles are younger)
     asm volatile("" : "+v"(my_parent));
   }
 
@@ -459,8 +470,18 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
   // the scores come out of the MFMA in the log2 domain
   const float c2 = row_real ? h_scale * MF_LOG2E : 0.f;
   wait_vm(first_tile_loads);  // the Q rows are there (the tiles are younger)
-  asm volatile("" : "+v"(qraw[0]), "+v"(qraw[1]), "+v"(qraw[2]), "+v"(qraw[3]), "+v"(qraw[4]), "+v"(qraw[5]),
-               "+v"(qraw[6]), "+v"(qraw[7]));
+  if constexpr (HALF) {
+    asm volatile("" : "+v"(qraw[0]), "+v"(qraw[1]), "+v"(qraw[2]), "+v"(qraw[3]));
+    const uintx4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {  // the row's 64 elements on its own head's side, zeros on the other
+      qraw[4 + kk] = q_upper ? qraw[kk] : zero;
+      qraw[kk] = q_upper ? zero : qraw[kk];
+    }
+  } else {
+    asm volatile("" : "+v"(qraw[0]), "+v"(qraw[1]), "+v"(qraw[2]), "+v"(qraw[3]), "+v"(qraw[4]), "+v"(qraw[5]),
+                 "+v"(qraw[6]), "+v"(qraw[7]));
+  }
   bf16x8 qf[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
@@ -801,10 +822,11 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     for (int j = 0; j < 8; ++j) {
       const int row_l = 4 * j + (lane >> 4), chunk = lane & 15;
       const int ro = row_base + row_l;
-      if (ro < R) {
-        const int i = div_G(ro), gi = ro - i * G;
+      const int i = div_G(ro < R ? ro : 0), gi = ro - i * G;
+      // (HALF: the eight chunks on the side of the row's own KV head are its 64 output elements)
+      if (ro < R && (!HALF || (chunk >> 3) == (2 * gi >= G ? 1 : 0))) {
         const uint4 val = *reinterpret_cast<const uint4*>(stage + row_l * ST_ROW + chunk * 16);
-        char* dst = static_cast<char*>(h_o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * MF_ROW_BYTES + chunk * 16;
+        char* dst = static_cast<char*>(h_o) + ((int64_t)(n0 + i) * Hq + g * G + gi) * Q_ROW_BYTES + (HALF ? chunk & 7 : chunk) * 16;
         // non-temporal: the rows start their way to memory now instead of waiting in L2 for the
         // write-back at the end of the kernel, when every workgroup's rows would go at once
         __builtin_nontemporal_store(__builtin_bit_cast(uintx4, val), reinterpret_cast<uintx4*>(dst));
@@ -816,18 +838,21 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
     if (r < R) {
       const int i = div_G(r), gi = r - i * G;
       const int64_t row = (int64_t)(n0 + i) * Hq + g * G + gi;
-      float* rec = h_part + (row * h_sp_max + sp) * ATTN_REC;
+      constexpr int REC_D = HALF ? 64 : 128;  // a record: o[REC_D], m, l, two pad floats
+      float* rec = h_part + (row * h_sp_max + sp) * (REC_D + ATTN_REC_PAD);
+      const int own = 2 * gi >= G ? 1 : 0;  // HALF: the side of the row's own KV head
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           const int d0 = 32 * tt + 8 * b + 4 * half;
           float4 f = {acc[tt][4 * b], acc[tt][4 * b + 1], acc[tt][4 * b + 2], acc[tt][4 * b + 3]};
-          *reinterpret_cast<float4*>(rec + d0) = f;
+          if (!HALF) *reinterpret_cast<float4*>(rec + d0) = f;
+          else if ((tt >> 1) == own) *reinterpret_cast<float4*>(rec + (d0 & 63)) = f;
         }
       if (half == 0) {
-        rec[128] = m_ref * MF_LN2;
-        rec[129] = l_tot;
+        rec[REC_D] = m_ref * MF_LN2;
+        rec[REC_D + 1] = l_tot;
       }
     }
   }
@@ -850,8 +875,13 @@ hs_status attn_mfma_launch(const AttnArgs& a, int max_tree_rows, hipStream_t str
     hs_status r = launch_status("tree attention (ancestor table)");
     if (r != HS_OK) return r;
   }
-#define MF_LAUNCH(PAGED, ONCE, BIG) \
-  hipExtLaunchKernelGGL((k_attn_mfma<PAGED, ONCE, BIG>), grid, block, 0, stream, ev_start, ev_stop, 0, a, n_rg_max)
+#define MF_LAUNCH(PAGED, ONCE, BIG)                                                                                        \
+  do {                                                                                                                     \
+    if (a.half)                                                                                                            \
+      hipExtLaunchKernelGGL((k_attn_mfma<PAGED, ONCE, BIG, true>), grid, block, 0, stream, ev_start, ev_stop, 0, a, n_rg_max);  \
+    else                                                                                                                   \
+      hipExtLaunchKernelGGL((k_attn_mfma<PAGED, ONCE, BIG, false>), grid, block, 0, stream, ev_start, ev_stop, 0, a, n_rg_max); \
+  } while (0)
   if (a.block_table != nullptr) {
     if (big) MF_LAUNCH(true, false, true);
     else if (once) MF_LAUNCH(true, true, false);

@@ -255,6 +255,38 @@ def test_ragged_batches_with_large_trees(G, seed):
         assert hs.hs_tree_attention_last_kernel() == 1
 
 
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2), (12, 6)])
+@pytest.mark.parametrize("M,L", [(61, 300), (129, 1000), (300, 70), (9, 0), (64, 2100)])
+def test_head_dimension_64_in_bfloat16(G, M, L, hq, hkv):
+    """bfloat16 with D = 64 runs on the matrix cores too: the kernel takes the KV heads in pairs (two heads of
+    a token are one 256-byte row) and widens each query row with zeros on the other head's side.  One and
+    several row groups, large trees, an empty prefix, a prefix cut into splits."""
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[2], Hq=hq, Hkv=hkv, D=64)
+    rs = np.random.RandomState(M + hq)
+    _compare(G, _case(w, 21, [_random_parents(rs, M, back=9)], [L], "unit"), "bf16")
+    assert hs.hs_tree_attention_last_kernel() == 1
+
+
+def test_head_dimension_64_ragged_batches(G):
+    """D = 64 through the ragged work-list launch: several sequences, splits, all input variants; an odd
+    number of KV heads cannot be paired and runs on the vector ALUs."""
+    import paper_2505_13254_amd as hs
+    rs = np.random.RandomState(64)
+    for it in range(10):
+        hq, hkv = [(8, 2), (8, 8), (16, 4), (4, 2), (3, 3)][rs.randint(5)]
+        w = W.small(W.WORKLOADS[2], Hq=hq, Hkv=hkv, D=64)
+        B = int(rs.randint(1, 6))
+        sizes = [int(rs.choice([0, 1, 9, 33, 61, 64, 65, 129, 300])) for _ in range(B)]
+        if sum(sizes) == 0:
+            sizes[0] = 5
+        Ls = [int(rs.choice([0, 1, 63, 64, 65, 500, 1300, 2049, 4100])) for _ in range(B)]
+        parents = [_random_parents(rs, n) if n else [] for n in sizes]
+        variant = ["config", "unit", "peaky", "hot", "unit_v"][rs.randint(5)]
+        _compare(G, _case(w, 6400 + it, parents, Ls, variant), "bf16", big_scores=variant == "hot")
+        assert hs.hs_tree_attention_last_kernel() == (2 if hkv % 2 else 1)
+
+
 def test_more_tree_rows_than_supported_is_an_error(G):
     import paper_2505_13254_amd as hs
     w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)

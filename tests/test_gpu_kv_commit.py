@@ -248,13 +248,15 @@ def test_paged_attention_and_commit(G, wid, B):
         assert np.array_equal(raw(_bits(dk)), raw(pool_k)) and np.array_equal(raw(_bits(dv)), raw(pool_v))
 
 
-def test_paged_attention_with_several_row_groups(G):
+@pytest.mark.parametrize("D", [128, 64])
+def test_paged_attention_with_several_row_groups(G, D):
     """Trees of more than 64 rows on the 8B shape (4 query heads per KV head: more than 256 rows per
     KV head, i.e. several row groups that read the same pages), next to small trees, over paged caches
-    with a shuffled page order; one sequence long enough to be cut into key splits."""
+    with a shuffled page order; one sequence long enough to be cut into key splits.  Also with head
+    dimension 64 (KV heads taken in pairs by the matrix-core kernel)."""
     import paper_2505_13254_amd as hs
     from oracle.kv_commit import gather_pages
-    w = W.small(W.WORKLOADS[2], B=3)
+    w = W.small(W.WORKLOADS[2], B=3, D=D)
     rs = np.random.RandomState(77)
     B = 3
     lens = np.asarray([300, 2700, 65], np.int64)
@@ -277,3 +279,4 @@ def test_paged_attention_with_several_row_groups(G):
                                       G.dev_store(vt), G.dev(par), G.dev(no), torch.from_numpy(no), G.dev(table),
                                       G.dev(lens), torch.from_numpy(lens.copy()), 1.0 / float(np.sqrt(w.D)))
     assert np.abs(G.host(o).astype(np.float64) - want_o).max() <= 2e-2
+    assert hs.hs_tree_attention_last_kernel() == 1
