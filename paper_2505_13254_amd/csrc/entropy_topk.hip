@@ -317,7 +317,9 @@ __device__ __forceinline__ void write_row(const MergeScratch<CAP>& sm, int64_t r
 // puts the counter back to zero for the next launch, merges the slices and writes the row.
 constexpr int FUSED_CAP = 1024;  // slices x K that the merging workgroup's scratch holds
 constexpr size_t TICKET_BYTES = 65536 * sizeof(unsigned);  // a counter for each of the at most 65535 rows of a call
-template <bool VEC, int SCAN_THREADS, bool FUSED, int NBUF>
+// STATS false: only the K best pairs are wanted (the greedy accept walk's argmax scan); the softmax
+// statistics, most of the arithmetic of a tile, are left out and part_stats is not written.
+template <bool VEC, int SCAN_THREADS, bool FUSED, int NBUF, bool STATS>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restrict__ logits, int64_t row_stride,
                                                             int V, int K, float inv_t, int tiles_per_wg,
                                                             float4* __restrict__ part_stats,
@@ -411,7 +413,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     float tm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
     tm = fmaxf(tm, fmaxf(fmaxf(fmaxf(v[8], v[9]), fmaxf(v[10], v[11])), fmaxf(fmaxf(v[12], v[13]), fmaxf(v[14], v[15]))));
     int skip = -1;
-    if (tm > m) {
+    if (STATS && tm > m) {
 #pragma unroll
       for (int jj = SCAN_VPT - 1; jj >= 0; --jj) skip = (v[jj] == tm) ? jj : skip;  // first instance of the max
       if (m != -HS_INF) {
@@ -423,7 +425,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
       }
       m = tm;
     }
-    if (tm != -HS_INF) {
+    if (STATS && tm != -HS_INF) {
 #pragma unroll
       for (int jj = 0; jj < SCAN_VPT; ++jj) {
         // x - m first: exact near the maximum (an fma with a rounded m * c would leave the maximum's
@@ -524,9 +526,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
   }
 
   // ---- the waves' statistics and the real entries of their lists meet in LDS
-  Stats st{m, s1, t2 * 0.6931471805599453f};  // back to natural-log units
-  st = stats_wave_sum(st, inv_t);
-  if (lane == 0) wave_st[wave] = make_float4(st.m, st.s1, st.t, 0.f);
+  if (STATS) {
+    Stats st{m, s1, t2 * 0.6931471805599453f};  // back to natural-log units
+    st = stats_wave_sum(st, inv_t);
+    if (lane == 0) wave_st[wave] = make_float4(st.m, st.s1, st.t, 0.f);
+  }
   {
     const bool real = lane < K && li != INT_MAX;  // a list's real entries come first
     const int n_w = __popcll(__ballot(real));
@@ -540,7 +544,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     }
   }
   __syncthreads();
-  if (tid < 64) {
+  if (STATS && tid < 64) {
     Stats a = stats_empty();
     if (lane < SCAN_WAVES) {
       const float4 f = wave_st[lane];
@@ -550,8 +554,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
     if (lane == 0) sm.total = a;
   }
   rank_candidates(sm, sm.cnt, K, tid, SCAN_THREADS);  // (its first barrier also publishes sm.total)
+  static_assert(STATS || !FUSED, "rows are finished by the caller of a scan without statistics");
   if (S == 1) {
-    write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
+    if (STATS) write_row(sm, row, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, tid);
+    else if (tid < K) topk_idx[row * K + tid] = sm.oi[tid];
   } else {
     const int64_t slot = (int64_t)row * S + split;
     if (!FUSED) {
@@ -559,7 +565,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_rows(const float* __restr
         part_val[slot * K + tid] = sm.ov[tid];
         part_idx[slot * K + tid] = sm.oi[tid];
       }
-      if (tid == 0) part_stats[slot] = make_float4(sm.total.m, sm.total.s1, sm.total.t, 0.f);
+      if (STATS && tid == 0) part_stats[slot] = make_float4(sm.total.m, sm.total.s1, sm.total.t, 0.f);
     } else {
       __shared__ int is_last;
       // The slice's results go out by the first wave alone, with stores that the other XCDs see; once
@@ -642,27 +648,39 @@ hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V,
   dim3 grid(p.splits, R);
   // one launch: the rows' last slices merge (needs the zeroed counters of a prepared workspace)
   const bool fused = prepared && slices == nullptr && p.splits > 1 && p.splits * K <= FUSED_CAP;
-#define HS_SCAN_LAUNCH(VEC, T, F)                                                                                      \
-  hipLaunchKernelGGL((k_scan_rows<VEC, T, F, 3>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
+#define HS_SCAN_LAUNCH(VEC, T, F, ST)                                                                                     \
+  hipLaunchKernelGGL((k_scan_rows<VEC, T, F, 3, ST>), grid, dim3(T), 0, stream, logits, row_stride, V, K, inv_t, p.tiles_per_wg, \
                      part_stats, part_val, part_idx, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index, logits2, rows1, tickets)
-  if (fused) {
+  if (slices != nullptr && slices->pairs_only) {
     if (p.threads == SCAN_BIG) {
-      if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, true);
-      else HS_SCAN_LAUNCH(false, SCAN_BIG, true);
+      if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, false, false);
+      else HS_SCAN_LAUNCH(false, SCAN_BIG, false, false);
     } else {
-      if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, true);
-      else HS_SCAN_LAUNCH(false, SCAN_SMALL, true);
+      if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, false, false);
+      else HS_SCAN_LAUNCH(false, SCAN_SMALL, false, false);
+    }
+  } else if (fused) {
+    if (p.threads == SCAN_BIG) {
+      if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, true, true);
+      else HS_SCAN_LAUNCH(false, SCAN_BIG, true, true);
+    } else {
+      if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, true, true);
+      else HS_SCAN_LAUNCH(false, SCAN_SMALL, true, true);
     }
   } else if (p.threads == SCAN_BIG) {
-    if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, false);
-    else HS_SCAN_LAUNCH(false, SCAN_BIG, false);
+    if (vec) HS_SCAN_LAUNCH(true, SCAN_BIG, false, true);
+    else HS_SCAN_LAUNCH(false, SCAN_BIG, false, true);
   } else {
-    if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, false);
-    else HS_SCAN_LAUNCH(false, SCAN_SMALL, false);
+    if (vec) HS_SCAN_LAUNCH(true, SCAN_SMALL, false, true);
+    else HS_SCAN_LAUNCH(false, SCAN_SMALL, false, true);
   }
 #undef HS_SCAN_LAUNCH
   hs_status st = launch_status("row scan");
-  if (slices != nullptr) *slices = ScanSlices{part_val, part_idx, p.splits};
+  if (slices != nullptr) {
+    slices->val = part_val;
+    slices->idx = part_idx;
+    slices->count = p.splits;
+  }
   if (st != HS_OK || p.splits == 1 || slices != nullptr || fused) return st;
   hipLaunchKernelGGL(k_scan_finalize, dim3(R), dim3(FIN_THREADS), 0, stream, part_stats, part_val, part_idx,
                      p.splits, K, inv_t, topk_idx, topk_logp, ent_topk, ent_full, lse, row_active, row_index);

@@ -50,6 +50,7 @@ struct ScanSlices {
   const float* val;
   const int32_t* idx;
   int count;
+  bool pairs_only = false;  // in: the caller wants the slices' best pairs only, no softmax statistics
 };
 hs_status row_topk_launch(const float* logits, int64_t row_stride, int R, int V, int K, float temperature,
                           int32_t* topk_idx, float* topk_logp, float* ent_topk, float* ent_full, float* lse,

@@ -981,6 +981,7 @@ extern "C" hs_status hs_verify_accept(const float* target_logits, const float* d
   int32_t *t_arg = nullptr, *d_arg = nullptr;
   float *t_lz = nullptr, *d_lz = nullptr;
   hs::ScanSlices slices{nullptr, nullptr, 1};
+  slices.pairs_only = true;  // (the greedy walk needs the rows' argmax and nothing else)
   hs::ChainOut chain{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   hs::BucketWs bk{};  // (all NULL: no sorted residual)
   if (NN > 0) {
