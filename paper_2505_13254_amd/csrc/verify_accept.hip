@@ -29,6 +29,7 @@
 namespace hs {
 
 constexpr int GR_THREADS = 256;
+constexpr int GR_LDS_ROWS = 1024;  // tree rows that the greedy walk stages in LDS
 constexpr int AC_THREADS = 1024;
 constexpr int AC_WAVES = AC_THREADS / 64;
 constexpr int AC_MAX_KIDS = 256;    // children tried per node
@@ -69,6 +70,16 @@ __global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(int32_t* __restric
     }
     return;
   }
+  // Trees of up to GR_LDS_ROWS rows are staged in LDS (parents, tokens, the rows' argmax), all of their
+  // global reads in one trip: the walks below are chains of dependent reads, one per tree level.
+  __shared__ int l_par[GR_LDS_ROWS], l_tok[GR_LDS_ROWS], l_arg[GR_LDS_ROWS];
+  const bool staged = n <= GR_LDS_ROWS;
+  if (staged) {
+    for (int i = tid; i < n; i += GR_THREADS) {
+      l_par[i] = parent[o + i];
+      l_tok[i] = token[o + i];
+    }
+  }
   if (n_slices > 1) {
     for (int i = tid; i < n; i += GR_THREADS) {
       const int64_t base = (int64_t)(o + i) * n_slices;
@@ -83,19 +94,31 @@ __global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(int32_t* __restric
         }
       }
       arg[o + i] = bi;
+      if (staged) l_arg[i] = bi;
     }
-    __syncthreads();  // every row's argmax is visible to the workgroup
+  } else if (staged) {
+    for (int i = tid; i < n; i += GR_THREADS) l_arg[i] = arg[o + i];
   }
+  __syncthreads();  // every row's argmax is visible to the workgroup
   // key = depth of a fully confirmed node (higher wins), then lower index
   long long best = ((long long)0 << 32) | (unsigned)(INT_MAX - 0);  // the root: depth 0
   for (int i = tid; i < n; i += GR_THREADS) {
     bool ok = true;
     int d = 0;
-    for (int j = i; j > 0;) {
-      const int p = parent[o + j];
-      ok = ok && (token[o + j] == arg[o + p]);
-      j = p;
-      ++d;
+    if (staged) {
+      for (int j = i; j > 0;) {
+        const int p = l_par[j];
+        ok = ok && (l_tok[j] == l_arg[p]);
+        j = p;
+        ++d;
+      }
+    } else {
+      for (int j = i; j > 0;) {
+        const int p = parent[o + j];
+        ok = ok && (token[o + j] == arg[o + p]);
+        j = p;
+        ++d;
+      }
     }
     if (ok && d <= max_depth) {
       long long key = ((long long)d << 32) | (unsigned)(INT_MAX - i);
@@ -114,10 +137,10 @@ __global__ __launch_bounds__(GR_THREADS) void k_accept_greedy(int32_t* __restric
     const int d = (int)(best >> 32);
     int node = INT_MAX - (int)(best & 0xffffffffll);
     accept_len[s] = d;
-    bonus_token[s] = arg[o + node];
+    bonus_token[s] = staged ? l_arg[node] : arg[o + node];
     for (int k = d - 1; k >= 0; --k) {
       path[k] = node;
-      node = parent[o + node];
+      node = staged ? l_par[node] : parent[o + node];
     }
   }
 }
