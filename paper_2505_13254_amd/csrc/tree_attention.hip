@@ -218,18 +218,32 @@ __global__ __launch_bounds__(64 * CMB_ROWS) void k_attn_combine(AttnArgs a, int6
   if (n_sp == 1) return;  // written directly by the attention kernel
   constexpr int REC = D + ATTN_REC_PAD;
   const float* rec = a.part + row * a.sp_max * REC;
-  float m = -HS_INF;
-  for (int sp = 0; sp < n_sp; ++sp) m = fmaxf(m, rec[sp * REC + D]);
+  // lane sp holds split sp's reference maximum and denominator (at most 64 splits): one trip to memory
+  // for all of them, then the splits' rows four at a time
+  float mv = -HS_INF, lv = 0.f;
+  if (lane < n_sp) {
+    mv = rec[lane * REC + D];
+    lv = rec[lane * REC + D + 1];
+  }
+  const float m = wave_max(mv);
+  const float w = lane < n_sp ? __expf(mv - m) : 0.f;
+  const float l = wave_sum(lv * w);
   constexpr int DPL = D / 64;
-  float l = 0.f, o[DPL];
+  float o[DPL];
 #pragma unroll
   for (int dd = 0; dd < DPL; ++dd) o[dd] = 0.f;
-  for (int sp = 0; sp < n_sp; ++sp) {
-    const float* r = rec + sp * REC;
-    const float w = __expf(r[D] - m);
-    l = fmaf(r[D + 1], w, l);
+  for (int sp0 = 0; sp0 < n_sp; sp0 += 4) {
+    float v[4][DPL];
 #pragma unroll
-    for (int dd = 0; dd < DPL; ++dd) o[dd] = fmaf(r[lane * DPL + dd], w, o[dd]);
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) v[u][dd] = sp0 + u < n_sp ? rec[(sp0 + u) * REC + lane * DPL + dd] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wu = __shfl(w, (sp0 + u) & 63);  // (0 beyond the last split)
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) o[dd] = fmaf(v[u][dd], wu, o[dd]);
+    }
   }
   const float inv = 1.f / l;
 #pragma unroll
