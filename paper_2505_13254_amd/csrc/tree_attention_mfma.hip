@@ -587,6 +587,13 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tt][v] *= alpha;
   };
+  // the first reference of a pass (denominator and accumulators are still zero: nothing to rescale,
+  // and no 0 x 2^(-m) = 0 x inf for a first block whose scores are all hugely negative)
+  auto set_reference = [&](float mx) {
+    m_ref = mx;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negm[v] = -mx;
+  };
   // the pieces of a window: two exponentials (keys 2j, 2j + 1 of half h of a block), and, one step
   // later, their bf16 pair; the two values also go into two running denominators
   float l0 = 0.f, l1 = 0.f;
@@ -688,7 +695,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
       const float mx = row_max(sA);
 #pragma unroll
       for (int v = 0; v < 16; ++v) sA[v] -= mx;
-      move_reference(mx);
+      set_reference(mx);
       exp_half(sA, 0, pa);
     }
 #pragma unroll
@@ -775,7 +782,8 @@ __global__ __launch_bounds__(MF_THREADS) void k_attn_mfma(AttnArgs a, int n_rg_m
         const float delta = (blk == 0 || mx > 0.f) ? mx : 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) S[v] -= delta;
-        move_reference(delta);
+        if (blk == 0) set_reference(delta);
+        else move_reference(delta);
       }
       uintx4 P0, P1;
       l0 = 0.f;

@@ -200,6 +200,9 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
     variant "hot":    "peaky" with planted scores of 120, 135, 150, ... instead of 8: exp() of the
                       gap to the other scores overflows float32, so an implementation must track
                       the running maximum to get these rows right.
+    variant "cold":   "unit", with the first keys of the prefix (up to 64) pointing away from two chosen
+                      queries: scores of -150 there, so a running maximum that starts from those keys
+                      starts hugely negative and every later score towers above it.
     variants "unit_v", "peaky_v": "unit" / "peaky" with V drawn N(0,1) as well, so that outputs are
                       of order one and an absolute tolerance of a few hundredths means something.
     """
@@ -232,7 +235,15 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
                 while parent is not None and steps > 0 and parent[j] >= 0:
                     j = int(parent[j]); steps -= 1
                 kt[j, g] = unit * amp                               # an ancestor (or the row itself)
-    elif variant not in ("config", "unit", "peaky", "hot"):
+    elif variant == "cold" and M > 0 and L > 0:
+        G = w.Hq // w.Hkv
+        picks = rng.randint(_key(w, seed, _T_PLANT, s), 2 * 2, 0, 1 << 30).reshape(2, 2)
+        for a, b in picks:
+            i, h = int(a) % M, int(b) % w.Hq
+            unit = q[i, h] / np.linalg.norm(q[i, h])
+            amp = 150.0 * np.sqrt(D) / np.linalg.norm(q[i, h])
+            kp[:min(L, 64), h // G] = -unit * amp
+    elif variant not in ("config", "unit", "peaky", "hot", "cold"):
         raise ValueError(variant)
     return tuple(_quantise(w, t) for t in (q, kp, vp, kt, vt))
 

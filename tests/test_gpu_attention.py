@@ -287,6 +287,15 @@ def test_head_dimension_64_ragged_batches(G):
         assert hs.hs_tree_attention_last_kernel() == (2 if hkv % 2 else 1)
 
 
+@pytest.mark.parametrize("hq,hkv,M,L", [(8, 2, 61, 300), (4, 2, 40, 700), (8, 2, 129, 64), (8, 8, 9, 2100)])
+def test_first_keys_with_hugely_negative_scores(G, hq, hkv, M, L):
+    """Two query rows score -150 on the first 64 prefix keys: the maximum of their first block is far below
+    the range in which 2^(-m) is finite, and every later score is 150 above it (the exact pass)."""
+    w = W.small(W.WORKLOADS[2], Hq=hq, Hkv=hkv)
+    rs = np.random.RandomState(M)
+    _compare(G, _case(w, 31, [_random_parents(rs, M)], [L], "cold"), "bf16", big_scores=True)
+
+
 def test_more_tree_rows_than_supported_is_an_error(G):
     import paper_2505_13254_amd as hs
     w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
