@@ -471,6 +471,25 @@ hs_status hs_time_next_attention(void* start_event, void* stop_event);
  * 0 = none (no such call yet, an empty batch, or the call failed before its launch). */
 int32_t hs_tree_attention_last_kernel(void);
 
+/* hs_tree_attention_plan  (diagnostic, host only: no GPU is touched, nothing is launched)
+ *
+ * How hs_tree_attention / _lens (host_prefix_lens given) / _paged (paged != 0: host_prefix_offsets is
+ * ignored, host_prefix_lens and max_blocks are required) would cut a batch of this shape into
+ * workgroups, assuming 16-byte aligned tensors.  The host arrays are checked as in the real call
+ * (same status codes).
+ *   totals [6] (host, written): [0] kernel as in hs_tree_attention_last_kernel (0: nothing to launch),
+ *     [1] workgroups of the attention launch, [2] largest number of key splits of a sequence,
+ *     [3] tokens per split when all sequences are cut alike (0: each sequence has its own cut, see
+ *     per_seq), [4] workspace bytes the call needs, [5] 1 if a combine launch follows.
+ *   per_seq [B][4] (host, written; may be NULL): key splits, 64-key tiles per split, row groups
+ *     (workgroups per KV head and split), number of the sequence's first workgroup in dispatch order
+ *     (-1: the launch is a plain grid).
+ */
+hs_status hs_tree_attention_plan(const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                                 const int64_t* host_prefix_lens, int32_t paged, int32_t max_blocks,
+                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt,
+                                 int64_t* totals, int32_t* per_seq);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,7 @@ _SIGNATURES = {
     "hs_tree_validate": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "hs_time_next_attention": (_c.c_int, [_vp, _vp]),
     "hs_tree_attention_last_kernel": (_c.c_int32, []),
+    "hs_tree_attention_plan": (_c.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _c.c_int, _vp, _vp]),
     "hs_verify_accept_workspace": (_sz, [_i32, _i32, _i32]),
     "hs_verify_accept_workspace_mode": (_sz, [_i32, _i32, _i32, _c.c_int]),
     "hs_verify_accept": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _c.c_int, _f32, _vp, _i32,
@@ -479,6 +480,22 @@ def hs_time_next_attention(start_event, stop_event) -> None:
     if not h0 or not h1:
         raise ValueError("hs_time_next_attention: record each event once before handing it over")
     _check(lib().hs_time_next_attention(_c.c_void_p(h0), _c.c_void_p(h1)), "hs_time_next_attention")
+
+
+def hs_tree_attention_plan(host_node_offsets, host_prefix_offsets, Hq, Hkv, D, dtype, *, host_prefix_lens=None,
+                           paged=False, max_blocks=0):
+    """Host only.  host_node_offsets int32 [B+1], host_prefix_offsets int64 [B+1] (None when paged),
+    host_prefix_lens int64 [B] or None: CPU tensors.  Returns (totals int64 [6], per_seq int32 [B,4]) as the
+    header describes them."""
+    B = host_node_offsets.numel() - 1
+    totals = torch.zeros(6, dtype=torch.int64)
+    per_seq = torch.zeros(max(B, 1), 4, dtype=torch.int32)
+    hp = None if host_prefix_offsets is None else host_prefix_offsets.data_ptr()
+    hl = None if host_prefix_lens is None else host_prefix_lens.data_ptr()
+    _check(lib().hs_tree_attention_plan(host_node_offsets.data_ptr(), hp, hl, 1 if paged else 0, int(max_blocks), B,
+                                        int(Hq), int(Hkv), int(D), int(dtype), totals.data_ptr(), per_seq.data_ptr()),
+           "hs_tree_attention_plan")
+    return totals, per_seq[:B]
 
 
 def hs_tree_attention_last_kernel() -> int:

@@ -318,6 +318,17 @@ static inline int plan_splits(int tiles, int target, int sp_cap, bool paged = fa
   return n < 1 ? 1 : n;
 }
 
+// The cut itself: `per` tiles to a split, and as many splits as that takes (rounding `per` up can make
+// the last of the splits asked for empty: they are dropped, every split starts inside the prefix).
+static inline void plan_cut(int tiles, int target, int sp_cap, bool paged, int* nsp, int* per) {
+  int n = plan_splits(tiles, target, sp_cap, paged);
+  int p = (tiles + n - 1) / n;
+  if (p < 1) p = 1;
+  n = (tiles + p - 1) / p;
+  *nsp = n < 1 ? 1 : n;
+  *per = p;
+}
+
 // Fills a.tbl / a.n_tbl / a.n_items / a.sp_max.  Returns false when the batch does not fit the table.
 static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, const int64_t* hlens, int B,
                           int sp_cap) {
@@ -357,8 +368,8 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
     float seq_cost[ATTN_TBL];
     for (int i = 0; i < n; ++i) {
       const Seq& q = seqs[i];
-      const int nsp = plan_splits(q.tiles, target, sp_cap, a.block_table != nullptr);
-      const int per = (q.tiles + nsp - 1) / nsp;
+      int nsp, per;
+      plan_cut(q.tiles, target, sp_cap, a.block_table != nullptr, &nsp, &per);
       const float big = PLAN_ITEM_US + (float)(per + q.ttiles) * plan_tile_us(q.waves0);
       const float one = PLAN_ITEM_US + (float)per * plan_tile_us(q.waves0);
       const float one_last = PLAN_ITEM_US + (float)per * plan_tile_us(q.waves_last);
@@ -384,8 +395,8 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
       item_cost.clear();
       for (int k = 0; k < n; ++k) {
         const Seq& q = seqs[ord[k]];
-        const int nsp = plan_splits(q.tiles, target, sp_cap, a.block_table != nullptr);
-        const int per = (q.tiles + nsp - 1) / nsp;
+        int nsp, per;
+        plan_cut(q.tiles, target, sp_cap, a.block_table != nullptr, &nsp, &per);
         for (int sp = 0; sp < nsp; ++sp) {
           int t = q.tiles - sp * per;
           t = t > per ? per : (t < 0 ? 0 : t);
@@ -417,9 +428,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
   int nsp_of[ATTN_TBL], per_of[ATTN_TBL];
   for (int i = 0; i < n; ++i) {
     const Seq& q = seqs[i];
-    nsp_of[i] = plan_splits(q.tiles, best.target, sp_cap, a.block_table != nullptr);
-    per_of[i] = (q.tiles + nsp_of[i] - 1) / nsp_of[i];
-    if (per_of[i] < 1) per_of[i] = 1;
+    plan_cut(q.tiles, best.target, sp_cap, a.block_table != nullptr, &nsp_of[i], &per_of[i]);
     cost[i] = (float)per_of[i] * plan_tile_us(q.waves0);
     order[i] = i;
   }
@@ -495,6 +504,12 @@ extern "C" hs_status hs_time_next_attention(void* start_event, void* stop_event)
   return HS_OK;
 }
 
+// What hs_tree_attention_plan reports (host memory; per_seq may be NULL).
+struct PlanReport {
+  int64_t* totals;   // [6]
+  int32_t* per_seq;  // [B][4]
+};
+
 // The three entry points in one: dense prefix regions (prefix_lens NULL), regions with spare
 // capacity (prefix_lens given), pages (block_table given: k_prefix / v_prefix are the page pools,
 // the offset arrays are absent).
@@ -505,22 +520,32 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
                                 const int64_t* host_prefix_lens, const int32_t* block_table, int32_t max_blocks,
                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt, float scale, void* o,
                                 float* lse, void* workspace, size_t workspace_bytes, hs_stream stream,
-                                bool tree_shared = false) {
+                                bool tree_shared = false, const PlanReport* report = nullptr) {
+  // report != NULL: plan only.  The host arrays are read and checked as in a real call, the device
+  // pointers may be NULL, nothing is launched; the report says how the launch would be cut.
+  const bool plan_only = report != nullptr;
+  if (plan_only)
+    for (int k = 0; k < 6; ++k) report->totals[k] = 0;
   const bool paged = block_table != nullptr;
-  hipEvent_t ev_start = timing_start, ev_stop = timing_stop;  // one-shot, whatever this call comes to
-  timing_start = timing_stop = nullptr;
-  last_kernel = 0;
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  if (!plan_only) {
+    ev_start = timing_start;  // one-shot, whatever this call comes to
+    ev_stop = timing_stop;
+    timing_start = timing_stop = nullptr;
+    last_kernel = 0;
+  }
   HS_REQUIRE(B >= 0, HS_ERR_SHAPE, "hs_tree_attention: B=%d", B);
   HS_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, HS_ERR_SHAPE, "hs_tree_attention: Hq=%d must be a multiple of Hkv=%d",
              Hq, Hkv);
   HS_REQUIRE(D == 64 || D == 128, HS_ERR_UNSUPPORTED, "hs_tree_attention: head dimension %d (64 and 128 are built)", D);
   HS_REQUIRE(dt == HS_F32 || dt == HS_BF16, HS_ERR_SHAPE, "hs_tree_attention: unknown dtype %d", (int)dt);
   if (B == 0) return HS_OK;
-  HS_REQUIRE(host_node_offsets && node_offsets && (paged || (host_prefix_offsets && prefix_offsets)), HS_ERR_NULL,
-             "hs_tree_attention: offset arrays (device and host copies) are required");
+  HS_REQUIRE(host_node_offsets && (paged || host_prefix_offsets) &&
+                 (plan_only || (node_offsets && (paged || prefix_offsets))),
+             HS_ERR_NULL, "hs_tree_attention: offset arrays (device and host copies) are required");
   HS_REQUIRE(host_node_offsets[0] == 0 && (paged || host_prefix_offsets[0] == 0), HS_ERR_SHAPE,
              "hs_tree_attention: offsets must start at 0");
-  HS_REQUIRE(!paged || (prefix_lens && host_prefix_lens && max_blocks >= 0), HS_ERR_NULL,
+  HS_REQUIRE(!paged || ((plan_only || prefix_lens) && host_prefix_lens && max_blocks >= 0), HS_ERR_NULL,
              "hs_tree_attention_paged: prefix lengths (device and host) are required");
   int64_t total_used = 0;
   for (int s = 0; s < B; ++s) {
@@ -545,13 +570,13 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
                    (host_prefix_lens[s] >= 0 && host_prefix_lens[s] <= host_prefix_offsets[s + 1] - host_prefix_offsets[s]),
                HS_ERR_SHAPE, "hs_tree_attention: prefix length of sequence %d exceeds its region", s);
   }
-  HS_REQUIRE((prefix_lens == nullptr) == (host_prefix_lens == nullptr), HS_ERR_NULL,
+  HS_REQUIRE(plan_only || (prefix_lens == nullptr) == (host_prefix_lens == nullptr), HS_ERR_NULL,
              "hs_tree_attention: prefix_lens and host_prefix_lens go together");
   const int NN = host_node_offsets[B];
   const int64_t total_prefix = paged ? total_used : host_prefix_offsets[B];
   if (NN == 0) return HS_OK;
-  HS_REQUIRE(q && k_tree && v_tree && parent && o, HS_ERR_NULL, "hs_tree_attention: NULL tensor");
-  HS_REQUIRE(total_prefix == 0 || (k_prefix && v_prefix), HS_ERR_NULL, "hs_tree_attention: NULL prefix cache");
+  HS_REQUIRE(plan_only || (q && k_tree && v_tree && parent && o), HS_ERR_NULL, "hs_tree_attention: NULL tensor");
+  HS_REQUIRE(plan_only || total_prefix == 0 || (k_prefix && v_prefix), HS_ERR_NULL, "hs_tree_attention: NULL prefix cache");
 
   int max_M = 0;
   for (int s = 0; s < B; ++s) max_M = std::max(max_M, host_node_offsets[s + 1] - host_node_offsets[s]);
@@ -597,6 +622,36 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   const size_t need = part_bytes(NN, Hq, D, a.sp_max) + table_bytes;
   if (table_bytes != 0 && workspace != nullptr)
     a.anc_tiles = reinterpret_cast<const unsigned*>(static_cast<const char*>(workspace) + part_bytes(NN, Hq, D, a.sp_max));
+  if (plan_only) {
+    const int n_rg_max = mfma ? (a.G * max_M + 255) / 256 : plan.n_rb_max;
+    report->totals[0] = mfma ? 1 : 2;
+    report->totals[1] = a.n_tbl > 0 ? a.n_items : (int64_t)a.Hkv * n_rg_max * a.sp_max * B;
+    report->totals[2] = a.sp_max;
+    report->totals[3] = a.split_len;
+    report->totals[4] = (int64_t)need;
+    report->totals[5] = a.sp_max > 1 ? 1 : 0;
+    if (report->per_seq != nullptr) {
+      for (int s = 0; s < B; ++s) {
+        int32_t* r = report->per_seq + 4 * s;
+        const int M = host_node_offsets[s + 1] - host_node_offsets[s];
+        const int64_t L = host_prefix_lens != nullptr ? host_prefix_lens[s] : host_prefix_offsets[s + 1] - host_prefix_offsets[s];
+        r[0] = M > 0 ? splits_of(L, a.split_len > 0 ? a.split_len : 1 << 30) : 0;
+        r[1] = a.split_len / 64;
+        r[2] = M > 0 ? (mfma ? (a.G * M + 255) / 256 : (a.G * M + GEN_ROWS - 1) / GEN_ROWS) : 0;
+        r[3] = -1;
+      }
+      for (int k = 0; k < a.n_tbl; ++k) {  // work lists: the table's entries, found back by their first tree row
+        const SeqEntry& e = a.tbl[k];
+        for (int s = 0; s < B; ++s)
+          if (host_node_offsets[s] == e.n0 && host_node_offsets[s + 1] - e.n0 == e.M && report->per_seq[4 * s + 3] < 0) {
+            int32_t* r = report->per_seq + 4 * s;
+            r[0] = e.n_sp; r[1] = e.tiles_per_split; r[2] = e.n_rg; r[3] = e.first_item;
+            break;
+          }
+      }
+    }
+    return HS_OK;
+  }
   HS_REQUIRE(need == 0 || (workspace && workspace_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 256 == 0),
              HS_ERR_WORKSPACE, "hs_tree_attention: workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
              workspace_bytes);
@@ -674,4 +729,17 @@ extern "C" hs_status hs_tree_attention_paged(const void* q, const void* k_pages,
   return attention_impl(q, k_pages, v_pages, k_tree, v_tree, parent, node_offsets, nullptr, host_node_offsets, nullptr,
                         prefix_lens, host_prefix_lens, block_table, max_blocks, B, Hq, Hkv, D, dt, scale, o, lse,
                         workspace, workspace_bytes, stream);
+}
+
+extern "C" hs_status hs_tree_attention_plan(const int32_t* host_node_offsets, const int64_t* host_prefix_offsets,
+                                            const int64_t* host_prefix_lens, int32_t paged, int32_t max_blocks,
+                                            int32_t B, int32_t Hq, int32_t Hkv, int32_t D, hs_dtype dt,
+                                            int64_t* totals, int32_t* per_seq) {
+  clear_error();
+  HS_REQUIRE(totals != nullptr, HS_ERR_NULL, "hs_tree_attention_plan: NULL totals");
+  const PlanReport report{totals, per_seq};
+  static const int32_t no_table = 0;  // (paged calls are told apart by their block table; none is read on the host)
+  return attention_impl(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, host_node_offsets,
+                        paged ? nullptr : host_prefix_offsets, nullptr, host_prefix_lens, paged ? &no_table : nullptr,
+                        max_blocks, B, Hq, Hkv, D, dt, 1.0f, nullptr, nullptr, nullptr, 0, nullptr, false, &report);
 }

@@ -296,6 +296,20 @@ def test_first_keys_with_hugely_negative_scores(G, hq, hkv, M, L):
     _compare(G, _case(w, 31, [_random_parents(rs, M)], [L], "cold"), "bf16", big_scores=True)
 
 
+def test_a_long_prefix_cut_into_the_most_splits(G):
+    """70 000 prefix tokens on two KV heads: the planner asks for the largest number of key splits (64); with
+    18 tiles to a split 61 splits hold all 1094 tiles, and no split may start behind the prefix."""
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
+    rs = np.random.RandomState(7)
+    st = _case(w, 41, [_random_parents(rs, 33)], [70000], "unit")
+    totals, per = hs.hs_tree_attention_plan(torch.from_numpy(st["node_offsets"]), torch.from_numpy(st["prefix_offsets"]),
+                                            8, 2, 128, hs.HS_BF16)
+    n_sp, per_split = int(per[0][0]), int(per[0][1])
+    assert n_sp > 32 and (n_sp - 1) * per_split < 1094 <= n_sp * per_split
+    _compare(G, st, "bf16")
+
+
 def test_more_tree_rows_than_supported_is_an_error(G):
     import paper_2505_13254_amd as hs
     w = W.small(W.WORKLOADS[2], Hq=8, Hkv=2)
