@@ -155,3 +155,39 @@ def test_stochastic_accept_at_full_vocabulary(H, wid, mode):
     st = H.build_step(w, 0, layers=1, accept_mode=mode)
     res = _check_step(st, np.random.RandomState(10 + wid + mode), n_rows=2, n_heads=1, accept_mode=mode)
     assert res["bonus_token"].min() >= 0
+
+
+@pytest.mark.parametrize("name,D,sizes,Ls,variant", [
+    ("a tree of 1024 rows on the 8B shape", 128, [1024], [4096], "peaky"),
+    ("large and small trees, long and short prefixes", 128, [700, 61, 300], [9000, 100, 3000], "unit"),
+    ("head dimension 64 on the 8B head layout", 64, [61, 129], [8192, 2048], "unit_v"),
+])
+def test_large_trees_and_head_dimension_64_at_full_head_count(G, name, D, sizes, Ls, variant):
+    """32 query heads on 8 KV heads as in the 8B workload, with what the matrix-core kernel takes beyond that
+    workload's own shape: trees past 256 rows (the ancestor table comes from its own launch) and head
+    dimension 64 (KV heads in pairs).  The launch covers all heads; two KV heads' query heads are compared
+    with the checker, which gets those heads alone."""
+    import paper_2505_13254_amd as hs
+    w = W.small(W.WORKLOADS[2], D=D)
+    rs = np.random.RandomState(len(name))
+    parents = [[-1] + [int(rs.randint(max(0, i - 9), i)) for i in range(1, n)] for n in sizes]
+    parts = [W.attention_inputs(w, 51, s, int(L), len(p), variant, parent=np.asarray(p))
+             for s, (p, L) in enumerate(zip(parents, Ls))]
+    q, kp, vp, kt, vt = (np.concatenate([x[i] for x in parts], axis=0) for i in range(5))
+    no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    po = np.concatenate([[0], np.cumsum(Ls)]).astype(np.int64)
+    par = np.concatenate([np.asarray(p, np.int32) for p in parents])
+    scale = 1.0 / np.sqrt(D)
+    st = dict(w=w, q=q, k_prefix=kp, v_prefix=vp, k_tree=kt, v_tree=vt, parent=par, node_offsets=no,
+              prefix_offsets=po, scale=scale)
+    got, _ = G.run_attention(st)
+    assert hs.hs_tree_attention_last_kernel() == 1
+    grp = w.Hq // w.Hkv
+    for g in (1, 6):
+        hq = slice(g * grp, (g + 1) * grp)
+        sub = dict(st, q=q[:, hq], k_prefix=kp[:, g:g + 1], v_prefix=vp[:, g:g + 1], k_tree=kt[:, g:g + 1],
+                   v_tree=vt[:, g:g + 1])
+        want, _ = tree_attention(sub["q"], sub["k_prefix"], sub["v_prefix"], sub["k_tree"], sub["v_tree"], par, no, po, scale)
+        diff = np.abs(got[:, hq].astype(np.float64) - want)
+        assert diff.max() <= 2e-2, (g, diff.max())
+        assert (diff / G.attention_error_bound(sub, want)).max() <= 1.0, g
