@@ -173,6 +173,9 @@ def main():
     ap.add_argument("--pause-ms", type=float, default=0.0,
                     help="--only attention: host pause after every launch (the chip's clocks recover between launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--head-dim", type=int, default=0,
+                    help="--only attention: the workload's attention shape with this head dimension (64: the "
+                         "matrix-core kernel's paired-head path); not a bench line")
     ap.add_argument("--only", default="", choices=["", "attention"],
                     help="attention: nothing but W + K attention launches of the workload (for profiler passes); "
                          "prints a short line, not the bench line")
@@ -198,6 +201,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = W.WORKLOADS[args.workload]
+    if args.head_dim:
+        assert args.only == "attention", "--head-dim goes with --only attention"
+        w = W.small(w, D=args.head_dim)
     layers = args.layers or (w.layers if w.B == 1 else 1)
     mode = {"greedy": 0, "stochastic": 1, "pointmass": 2}[args.accept]
     if args.adaptive:
@@ -227,7 +233,8 @@ def main():
         dst.copy_(big)
         torch.cuda.synchronize()
         ts = np.array([a_.elapsed_time(b_) for a_, b_ in ev][args.warmup:])
-        print(json.dumps({"only": "attention", "workload": w.wid, "layers": layers, "launches": n,
+        print(json.dumps({"only": "attention", "workload": w.wid, "head_dim": w.D, "layers": layers, "launches": n,
+                          "kernel": {0: "none", 1: "matrix cores", 2: "vector ALUs"}[hs.hs_tree_attention_last_kernel()],
                           "verified_rows": step.host["NNp"],
                           "pause_ms_between_launches": args.pause_ms,
                           "kernel_ms_median": float(np.median(ts)), "kernel_ms_mean": float(ts.mean()),
