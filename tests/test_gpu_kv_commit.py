@@ -248,19 +248,19 @@ def test_paged_attention_and_commit(G, wid, B):
         assert np.array_equal(raw(_bits(dk)), raw(pool_k)) and np.array_equal(raw(_bits(dv)), raw(pool_v))
 
 
-@pytest.mark.parametrize("D", [128, 64])
-def test_paged_attention_with_several_row_groups(G, D):
+@pytest.mark.parametrize("D,sizes", [(128, [100, 129, 7]), (64, [100, 129, 7]), (128, [100, 300, 7]), (64, [9, 700, 61])])
+def test_paged_attention_with_several_row_groups(G, D, sizes):
     """Trees of more than 64 rows on the 8B shape (4 query heads per KV head: more than 256 rows per
     KV head, i.e. several row groups that read the same pages), next to small trees, over paged caches
     with a shuffled page order; one sequence long enough to be cut into key splits.  Also with head
-    dimension 64 (KV heads taken in pairs by the matrix-core kernel)."""
+    dimension 64 (KV heads taken in pairs by the matrix-core kernel) and with trees past 256 rows (ancestor
+    table from its own launch)."""
     import paper_2505_13254_amd as hs
     from oracle.kv_commit import gather_pages
     w = W.small(W.WORKLOADS[2], B=3, D=D)
     rs = np.random.RandomState(77)
     B = 3
     lens = np.asarray([300, 2700, 65], np.int64)
-    sizes = [100, 129, 7]
     max_blocks = int((lens.max() + 63) // 64)
     offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
     fill = [W.attention_inputs(w, 1, s, int(lens[s]), 1, "unit") for s in range(B)]
