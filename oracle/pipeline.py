@@ -60,16 +60,7 @@ def fixed_tree(w, seed, s, quantify=draft_entropy_topk):
     M = len(parent)
     x = W.logits_rows(w, seed, "draft", s, range(M))
     r = quantify(x, w.topk, w.temperature)
-    token = np.full(M, -1, np.int32)
-    logc = np.zeros(M, np.float64)
-    rank = {}
-    for i in range(1, M):
-        p = int(parent[i])
-        k = rank.get(p, 0)
-        rank[p] = k + 1
-        assert k < w.topk, "fan-out exceeds K"
-        token[i] = r["topk_idx"][p, k]
-        logc[i] = r["topk_logp"][p, k]
+    token, logc = W.label_children(parent, r["topk_idx"], np.asarray(r["topk_logp"], np.float64), w.topk)
     return dict(parent=parent, token=token, logc=logc, draft_ids=np.arange(M), rows=x, stage1=r)
 
 
@@ -81,13 +72,7 @@ def sequence_budget(w, seed, B):
     for s in range(B):
         x = W.logits_rows(w, seed, "draft", s, [0])
         ent.append(float(draft_entropy_topk(x, w.topk, w.temperature)["ent_topk"][0]))
-    order = sorted(range(B), key=lambda s: (ent[s], s))
-    depth, budget = [0] * B, [0] * B
-    for rank, s in enumerate(order):
-        b = rank * 8 // B
-        depth[s] = max(2, w.max_depth - b)
-        budget[s] = int(round(8 + (w.max_nodes - 8) * b / 7.0))
-    return depth, budget
+    return W.batch_budgets(w, ent)
 
 
 def build_step(w, seed, theta=None, with_attention=True, variant="config", depth_budget=None):

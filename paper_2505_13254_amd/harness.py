@@ -44,67 +44,52 @@ def _in_parallel(fn, items, workers: int = 16):
 
 
 def expand_tree(w: W.Workload, seed: int, s: int, depth: int, device="cuda:0"):
-    """Top-K expansion: per depth, the `frontier` nodes with the largest cumulative confidence are
-    expanded with their K most likely draft tokens.  Returns the candidate tree (host arrays) and the
-    expanded rows' logits (device, in expansion order)."""
+    """Top-K expansion with the library's own calls: per level the frontier's draft rows are quantified
+    (hs_draft_entropy_topk) and the tree grows on the device (hs_tree_expand: children of the frontier,
+    next frontier = the `frontier` new rows with the largest cumulative confidence).  The host only
+    fetches the rows the next level asks for.  Returns the candidate tree (host arrays) and the expanded
+    rows' logits (device, in expansion order)."""
     K, F = w.topk, w.frontier
-    parent, token, logc, cum = [-1], [-1], [0.0], [0.0]
+    cap = 1 + K + max(0, depth - 1) * F * K
+    state = hs.new_tree_state(1, cap, F, device)
+    idx = torch.zeros((F, K), dtype=torch.int32, device=device)
+    lp = torch.zeros((F, K), dtype=torch.float32, device=device)
+    ent = torch.zeros(F, dtype=torch.float32, device=device)
     draft_ids: List[int] = []
     rows = []
-    level = [0]
+    chosen = [0]
     for d in range(depth):
-        chosen = sorted(sorted(level, key=lambda i: (-cum[i], i))[:F])
         x = _dev(W.logits_rows(w, seed, "draft", s, chosen), device=device)
         r = hs.hs_draft_entropy_topk(x, K, w.temperature, want_full=False)
-        idx = r["topk_idx"].cpu().numpy()
-        lp = r["topk_logp"].cpu().numpy()
-        nxt = []
-        for j, i in enumerate(chosen):
-            draft_ids.append(i)
-            for k in range(K):
-                parent.append(i)
-                token.append(int(idx[j, k]))
-                logc.append(float(lp[j, k]))
-                cum.append(cum[i] + min(float(lp[j, k]), 0.0))
-                nxt.append(len(parent) - 1)
+        n = len(chosen)                       # the frontier's slots, in row order; the rest is unused
+        idx[:n], lp[:n], ent[:n] = r["topk_idx"], r["topk_logp"], r["ent_topk"]
+        hs.hs_tree_expand(state, idx, lp, ent, None, 1, cap, F, K, first=(d == 0))
+        draft_ids += chosen
         rows.append(x)
-        level = nxt
-    return dict(parent=np.asarray(parent, np.int32), token=np.asarray(token, np.int32),
-                logc=np.asarray(logc, np.float32), draft_ids=np.asarray(draft_ids, np.int64),
+        chosen = state["frontier"][:int(state["n_frontier"][0])].cpu().tolist()
+    n = int(state["n_nodes"][0])
+    return dict(parent=state["parent"][:n].cpu().numpy(), token=state["token"][:n].cpu().numpy(),
+                logc=state["logc"][:n].cpu().numpy(), draft_ids=np.asarray(draft_ids, np.int64),
                 rows=torch.cat(rows, dim=0))
 
 
 def fixed_tree(w: W.Workload, seed: int, s: int, device="cuda:0"):
-    """Random-shape tree: every node's draft row is quantified; child number r of a node carries the
-    node's r-th most likely draft token and its log-probability."""
+    """Random-shape tree: every node's draft row is quantified; the workload's recipe labels the nodes
+    with their parents' Top-K tokens."""
     parent = W.tree_parents(w, seed, s)
     M = len(parent)
     x = _dev(W.logits_rows(w, seed, "draft", s, range(M)), device=device)
     r = hs.hs_draft_entropy_topk(x, w.topk, w.temperature, want_full=False)
-    idx, lp = r["topk_idx"].cpu().numpy(), r["topk_logp"].cpu().numpy()
-    token = np.full(M, -1, np.int32)
-    logc = np.zeros(M, np.float32)
-    rank: Dict[int, int] = {}
-    for i in range(1, M):
-        p = int(parent[i])
-        k = rank.get(p, 0)
-        rank[p] = k + 1
-        token[i], logc[i] = idx[p, k], lp[p, k]
+    token, logc = W.label_children(parent, r["topk_idx"].cpu().numpy(), r["topk_logp"].cpu().numpy(), w.topk)
     return dict(parent=parent, token=token, logc=logc, draft_ids=np.arange(M), rows=x)
 
 
 def sequence_budget(w: W.Workload, seed: int, device="cuda:0"):
-    """(depth, node budget) per sequence of the batched workload from the Top-K entropy of each root
-    row (first term of Eq. 1): eight equal-count bins, low entropy -> deeper draft, fewer nodes."""
+    """(depth, node budget) per sequence of the batched workload, by the workload's recipe from the Top-K
+    entropy of each root row (first term of Eq. 1)."""
     x = _dev(np.concatenate([W.logits_rows(w, seed, "draft", s, [0]) for s in range(w.B)]), device=device)
     ent = hs.hs_draft_entropy_topk(x, w.topk, w.temperature, want_full=False)["ent_topk"].cpu().numpy()
-    order = sorted(range(w.B), key=lambda s: (float(ent[s]), s))
-    depth, budget = [0] * w.B, [0] * w.B
-    for rank, s in enumerate(order):
-        b = rank * 8 // w.B
-        depth[s] = max(2, w.max_depth - b)
-        budget[s] = int(round(8 + (w.max_nodes - 8) * b / 7.0))
-    return depth, budget
+    return W.batch_budgets(w, ent)
 
 
 @dataclass

@@ -248,6 +248,39 @@ def attention_inputs(w: Workload, seed: int, s: int, L: int, M: int, variant: st
     return tuple(_quantise(w, t) for t in (q, kp, vp, kt, vt))
 
 
+# ----------------------------------------------------------------------------- tree recipes
+def label_children(parent: np.ndarray, topk_idx: np.ndarray, topk_logp: np.ndarray, topk: int):
+    """Tokens and log-confidences of a random-shape tree (workloads 1, 3, 4): child number r of a node (in
+    row order) carries that node's r-th most likely draft token and its log-probability, as the Top-K
+    results of every node's draft row list them.  Returns (token int32 [M], logc [M] in topk_logp's dtype)."""
+    M = len(parent)
+    token = np.full(M, -1, np.int32)
+    logc = np.zeros(M, np.asarray(topk_logp).dtype)
+    rank = {}
+    for i in range(1, M):
+        p = int(parent[i])
+        k = rank.get(p, 0)
+        rank[p] = k + 1
+        assert k < topk, "fan-out exceeds K"
+        token[i] = topk_idx[p, k]
+        logc[i] = topk_logp[p, k]
+    return token, logc
+
+
+def batch_budgets(w: Workload, root_entropy):
+    """(depth, node budget) per sequence of the batched workload from the Top-K entropies of the root
+    rows: sequences are ranked by entropy (ties: lower sequence first); the lower the entropy, the deeper
+    the draft and the smaller the verified set, in eight equal-count bins."""
+    B = len(root_entropy)
+    order = sorted(range(B), key=lambda s: (float(root_entropy[s]), s))
+    depth, budget = [0] * B, [0] * B
+    for rank, s in enumerate(order):
+        b = rank * 8 // B
+        depth[s] = max(2, w.max_depth - b)
+        budget[s] = int(round(8 + (w.max_nodes - 8) * b / 7.0))
+    return depth, budget
+
+
 # ----------------------------------------------------------------------------- uniforms
 def uniforms(w: Workload, seed: int, n: int, redraw: int = 0) -> np.ndarray:
     """n float32 uniforms in [0, 1) for the stochastic accept rule (node draws, then one per sequence)."""
