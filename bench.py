@@ -392,7 +392,7 @@ def main():
     mfma_bound = w.dtype == "bf16" and flops3 / bytes3 > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_tree_attention_w%d.json" % w.wid)
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.theta is None and not args.layers:   # (measured on the configured launch only)
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
     out = {
         "metric": "verified tree-tokens/sec per step + tree-attn HBM GB/s (% of peak), 1 GPU",
