@@ -138,16 +138,17 @@ def test_split_and_unsplit_sequences_in_one_launch(G):
     _compare(G, _case(w, 8, [_random_parents(rs, n) for n in sizes], Ls, "peaky"), "bf16")
 
 
-@pytest.mark.parametrize("B", [70, 96, 100])
-def test_batches_around_the_work_list_capacity(G, B):
+@pytest.mark.parametrize("B,D,big", [(70, 128, 40), (96, 128, 40), (100, 128, 40), (100, 128, 300), (100, 64, 40), (100, 64, 300)])
+def test_batches_around_the_work_list_capacity(G, B, D, big):
     """More than 64 sequences need the second half of the kernel-argument table; more than 96 do
-    not fit it and take the launch with one grid row per sequence."""
-    w = W.small(W.WORKLOADS[5])
+    not fit it and take the launch with one grid row per sequence: also with a tree past 256 rows in
+    the batch and with head dimension 64."""
+    w = W.small(W.WORKLOADS[5], D=D)
     rs = np.random.RandomState(B)
     sizes = [int(x) for x in rs.randint(0, 20, size=B)]
     Ls = [int(x) for x in rs.randint(0, 300, size=B)]
     Ls[B // 2] = 2500                                        # one sequence long enough to be split
-    sizes[B // 2] = 40
+    sizes[B // 2] = big
     parents = [_random_parents(rs, n) if n else [] for n in sizes]
     _compare(G, _case(w, 9, parents, Ls, "unit"), "bf16")
 
