@@ -6,6 +6,7 @@
 // split combine (k_attn_combine).  bfloat16 with head dimension 128 goes to the MFMA kernel in
 // tree_attention_mfma.hip.
 #include <stdlib.h>
+#include <string.h>
 
 #include <algorithm>
 #include <functional>
@@ -300,7 +301,11 @@ static AttnPlan plan_attention(const int32_t* hno, const int64_t* hpo, const int
 // per-tile part that grows with the number of waves that have rows.
 constexpr int PLAN_CUS = 256;
 constexpr float PLAN_ITEM_US = 10.f;
-constexpr int PLAN_MIN_SPLIT_TILES = 8;  // splits of at least 512 tokens (the workspace bound relies on it)
+// Splits of at least 128 tokens (the workspace bound relies on it).  A launch of few workgroups is mostly an
+// item's fixed cost: one layer of the 8B shape (32 tiles a head) takes 25.9 us cut into 4 x 8 tiles, 23.5 us
+// into 8 x 4 or 16 x 2, combine launch included.
+constexpr int PLAN_MIN_SPLIT_TILES = 2;
+constexpr int PLAN_MIN_SPLIT_TOKENS = PLAN_MIN_SPLIT_TILES * 64;
 static inline float plan_tile_us(int waves) { return 1.25f + 0.04f * (float)waves; }
 
 struct ListPlan {
@@ -357,10 +362,16 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
   // Unequal items (a ragged batch): the makespan of each candidate is found by replaying the
   // hardware's dispatch, which hands the next workgroup in index order to the first compute unit
   // that falls free (list scheduling).  Equal items (the layers of one step) run in whole rounds.
-  static const int targets[] = {1 << 20, 192, 160, 128, 112, 96, 80, 72, 64, 56, 48, 40, 32, 24, 16, 8};
+  static const int targets[] = {1 << 20, 192, 160, 128, 112, 96, 80, 72, 64, 56, 48, 40, 32, 24, 16, 8, 4, 2};
+  // Cuts finer than eight tiles are candidates only while eight-tile items would leave compute units idle
+  // (a launch of one or two layers): such an item is mostly its fixed cost.
+  int64_t coarse_items = 0;
+  for (int i = 0; i < n; ++i) coarse_items += (int64_t)a.Hkv * seqs[i].rg * (seqs[i].tiles / 8 > 0 ? seqs[i].tiles / 8 : 1);
+  const int n_targets = (int)(sizeof(targets) / sizeof(targets[0])) - (coarse_items < PLAN_CUS ? 0 : 2);
   ListPlan best{0.f, 0};
   static thread_local std::vector<float> item_cost, cu_free;  // (kept between calls: no allocation in the steady state)
-  for (int target : targets) {
+  for (int ti = 0; ti < n_targets; ++ti) {
+    const int target = targets[ti];
     double total = 0.0, rec_bytes = 0.0;
     float mx = 0.f, mn = 1e30f;
     int64_t items = 0;
@@ -380,6 +391,13 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
       if (nsp > 1) rec_bytes += (double)q.M * a.Hq * nsp * ((a.half ? 64 : 128) + ATTN_REC_PAD) * 4 * 2;  // written, then read
       ord[i] = i;
       seq_cost[i] = (float)per * plan_tile_us(q.waves0);
+    }
+    // (no schedule ends before the work divided by the compute units, nor before its longest item: a
+    // candidate whose bound is no better than the best estimate so far needs no replay)
+    const float combine_us = rec_bytes > 0.0 ? 4.f + (float)(rec_bytes / 2.5e6) : 0.f;  // the combine launch, ~2.5 TB/s
+    {
+      const float floor_us = (float)(total / PLAN_CUS) > mx ? (float)(total / PLAN_CUS) : mx;
+      if (best.target != 0 && floor_us + combine_us >= best.est_us) continue;
     }
     float est;
     if (mx - mn <= 0.1f * mx || items > 8192) {
@@ -419,7 +437,7 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
       }
       est = end;
     }
-    if (rec_bytes > 0.0) est += 4.f + (float)(rec_bytes / 2.5e6);  // the combine launch, ~2.5 TB/s
+    est += combine_us;
     if (best.target == 0 || est < best.est_us) best = ListPlan{est, target};
   }
   // the table: sequences by falling cost of an item
@@ -457,6 +475,60 @@ static bool plan_worklist(AttnArgs& a, const int32_t* hno, const int64_t* hpo, c
   return true;
 }
 
+// The plan depends on the host arrays and the head layout alone, and a model calls the attention of all its
+// layers with the same ones: the last few plans are kept per thread.  (Planning a ragged batch of 16 sequences
+// replays some twenty candidate cuts over hundreds of items each, a few hundred microseconds on the host:
+// more than the launch itself takes on the GPU.)
+struct PlanMemo {
+  std::vector<int64_t> key;  // everything the plan is a function of; empty: unused slot
+  bool ok;
+  int n_tbl, n_items, sp_max;
+  SeqEntry tbl[ATTN_TBL];
+};
+constexpr int PLAN_MEMO_SLOTS = 4;
+constexpr int PLAN_MEMO_MAX_B = 1024;  // larger batches (at most 96 of their entries non-empty) are planned every time
+
+static bool plan_worklist_memo(AttnArgs& a, const int32_t* hno, const int64_t* hpo, const int64_t* hlens, int B,
+                               int sp_cap) {
+  if (B > PLAN_MEMO_MAX_B) return plan_worklist(a, hno, hpo, hlens, B, sp_cap);
+  static thread_local PlanMemo memo[PLAN_MEMO_SLOTS];
+  static thread_local unsigned next_slot = 0;
+  static thread_local std::vector<int64_t> key;
+  key.clear();
+  key.push_back(B);
+  key.push_back(sp_cap);
+  key.push_back(a.G);
+  key.push_back(a.Hkv);
+  key.push_back(a.half);
+  key.push_back(a.block_table != nullptr ? 1 + (int64_t)a.max_blocks : 0);  // (paged: an entry's p0 is s * max_blocks)
+  key.push_back((hpo != nullptr ? 1 : 0) + (hlens != nullptr ? 2 : 0));
+  for (int s = 0; s <= B; ++s) key.push_back(hno[s]);
+  if (hpo != nullptr)
+    for (int s = 0; s <= B; ++s) key.push_back(hpo[s]);
+  if (hlens != nullptr)
+    for (int s = 0; s < B; ++s) key.push_back(hlens[s]);
+  for (PlanMemo& m : memo)
+    if (m.key == key) {
+      if (m.ok) {
+        a.n_tbl = m.n_tbl;
+        a.n_items = m.n_items;
+        a.sp_max = m.sp_max;
+        memcpy(a.tbl, m.tbl, sizeof(SeqEntry) * (size_t)m.n_tbl);
+      }
+      return m.ok;
+    }
+  PlanMemo& m = memo[next_slot++ % PLAN_MEMO_SLOTS];
+  m.ok = plan_worklist(a, hno, hpo, hlens, B, sp_cap);
+  m.key = key;
+  if (m.ok) {
+    m.n_tbl = a.n_tbl;
+    m.n_items = a.n_items;
+    m.sp_max = a.sp_max;
+    memcpy(m.tbl, a.tbl, sizeof(SeqEntry) * (size_t)a.n_tbl);
+  }
+  return m.ok;
+}
+
 }  // namespace hs
 
 using namespace hs;
@@ -470,8 +542,8 @@ extern "C" size_t hs_tree_attention_workspace(int32_t B, int32_t NN, int64_t tot
                                               int32_t D, hs_dtype dt) {
   (void)dt;
   if (B <= 0 || NN <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || total_prefix < 0) return 0;
-  // upper bound over every plan the launch may choose: splits are at least 512 tokens long
-  const int64_t sp_bound = total_prefix / 512 + 1;
+  // upper bound over every plan the launch may choose: splits are at least PLAN_MIN_SPLIT_TOKENS long
+  const int64_t sp_bound = total_prefix / PLAN_MIN_SPLIT_TOKENS + 1;
   // (+ the ancestor table that trees of more than 256 rows keep there: such a tree needs NN > 256)
   return part_bytes(NN, Hq, D, (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound)) +
          align_up(attn_mfma_table_bytes(NN < MAX_TREE_ROWS ? NN : MAX_TREE_ROWS, NN), 256);
@@ -599,11 +671,11 @@ static hs_status attention_impl(const void* q, const void* k_prefix, const void*
   a.n_tbl = 0; a.n_items = 0; a.anc_tiles = nullptr;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the workspace query bounds the splits of a sequence the same way
-  const int64_t sp_bound = total_prefix / 512 + 1;
+  const int64_t sp_bound = total_prefix / PLAN_MIN_SPLIT_TOKENS + 1;
   const int sp_cap = (int)(sp_bound < 2 ? 2 : sp_bound > 64 ? 64 : sp_bound);
 
   AttnPlan plan{};
-  if (!(mfma && plan_worklist(a, host_node_offsets, host_prefix_offsets, host_prefix_lens, B, sp_cap))) {
+  if (!(mfma && plan_worklist_memo(a, host_node_offsets, host_prefix_offsets, host_prefix_lens, B, sp_cap))) {
     a.n_tbl = 0;
     plan = plan_attention(host_node_offsets, host_prefix_offsets, host_prefix_lens, B, Hq, a.Hkv, mfma ? 0 : GEN_ROWS, mfma ? 256 : 1024);
     while (plan.sp_max > sp_cap) {

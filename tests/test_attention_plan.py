@@ -27,7 +27,7 @@ def _plan(Ms, Ls, Hq, Hkv, D=128, dt=None, lens=None, paged=False, max_blocks=0)
 
 def _check_work_list(Ms, Ls, Hq, Hkv, D, totals, per):
     """A work-list plan: every sequence with rows has its items, items are numbered without gaps in
-    dispatch order, a sequence's splits cover its prefix tiles once, no split is shorter than 8 tiles."""
+    dispatch order, a sequence's splits cover its prefix tiles once, no split is shorter than 2 tiles."""
     kernel, n_items, sp_max, split_len, ws_bytes, combine = (int(x) for x in totals)
     units = Hkv // 2 if D == 64 else Hkv
     G = (Hq // Hkv) * (2 if D == 64 else 1)
@@ -43,7 +43,7 @@ def _check_work_list(Ms, Ls, Hq, Hkv, D, totals, per):
         assert 1 <= n_sp <= sp_max <= 64
         assert n_sp * per_split >= tiles and (n_sp - 1) * per_split < max(tiles, 1)
         if n_sp > 1:
-            assert per_split >= 8
+            assert per_split >= 2
         nxt += units * n_sp * n_rg
     assert nxt == n_items
     for s in range(len(Ms)):
@@ -63,6 +63,45 @@ def test_the_bench_launch_is_one_workgroup_per_layer_and_head():
     assert tuple(totals) == (1, 256, 1, 0, 0, 0)
     assert all(tuple(r[:3]) == (1, 32, 1) for r in per)
     _check_work_list([61] * 32, [2048] * 32, 32, 8, 128, totals, per)
+
+
+def test_a_single_layer_is_cut_finer_than_a_launch_that_fills_the_chip():
+    """One layer of the 8B shape is 8 (sequence, head) pairs for 256 compute units: its keys are cut into
+    items of fewer than 8 tiles; four layers already take 8-tile items."""
+    totals, per = _plan([61], [2048], 32, 8)
+    _check_work_list([61], [2048], 32, 8, 128, totals, per)
+    assert 2 <= per[0][1] < 8 and totals[1] == 8 * per[0][0] and totals[5] == 1
+    totals4, per4 = _plan([61] * 4, [2048] * 4, 32, 8)
+    _check_work_list([61] * 4, [2048] * 4, 32, 8, 128, totals4, per4)
+    assert all(r[1] >= 8 for r in per4)
+
+
+def test_plans_are_remembered_per_input_not_per_call_order():
+    """The library keeps its last few plans: the same inputs give the same plan whatever was planned in
+    between (more shapes than it keeps), and inputs that differ in one length, one tree size, the head layout,
+    the used lengths or the offsets alone are not taken for each other."""
+    base = ([61, 129, 9], [3000, 20000, 700], 32, 8)
+    variants = [base,
+                ([61, 129, 9], [3000, 20001, 700], 32, 8),
+                ([61, 130, 9], [3000, 20000, 700], 32, 8),
+                ([61, 129, 9], [3000, 20000, 700], 64, 8),
+                ([61, 129, 9], [3000, 20000, 700], 32, 4),
+                ([61, 129, 9], [3000, 20000, 764], 32, 8),
+                ([61, 129, 9, 0], [3000, 20000, 700, 0], 32, 8)]
+    first = [_plan(*v) for v in variants]
+    for v, (t, p) in zip(variants, first):
+        _check_work_list(v[0], v[1], v[2], v[3], 128, t, p)
+    for rnd in range(3):
+        for k in np.random.RandomState(rnd).permutation(len(variants)):
+            t, p = _plan(*variants[k])
+            assert np.array_equal(t, first[k][0]) and np.array_equal(p, first[k][1]), (rnd, k)
+    # used lengths: same offsets, different lens; and the same lens behind different offsets
+    t_a, p_a = _plan([61, 61], [20000, 20000], 32, 8, lens=[300, 20000])
+    t_b, p_b = _plan([61, 61], [20000, 20000], 32, 8, lens=[20000, 300])
+    t_c, p_c = _plan([61, 61], [20000, 20000], 32, 8)
+    assert p_a[0][0] == 1 and p_b[1][0] == 1 and p_c[0][0] > 1 and p_c[1][0] > 1
+    t_a2, p_a2 = _plan([61, 61], [20000, 20000], 32, 8, lens=[300, 20000])
+    assert np.array_equal(t_a, t_a2) and np.array_equal(p_a, p_a2)
 
 
 def test_the_ragged_batch_is_cut_into_comparable_items():

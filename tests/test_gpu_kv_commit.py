@@ -116,6 +116,39 @@ def test_decoding_loop_on_caches_with_spare_capacity(G, wid, B):
         assert np.array_equal(_bits(dl), lens) and np.array_equal(_bits(dk), kc) and np.array_equal(_bits(dv), vc)
 
 
+def test_equal_lengths_in_regions_at_different_offsets(G):
+    """Two cache layouts with the same tree sizes and the same used lengths, whose regions start at different
+    offsets, called in turns: a call's plan (the library remembers its last few) holds each region's own
+    offset, so every call must read its own keys."""
+    import paper_2505_13254_amd as hs
+    B = 3
+    w = W.small(W.WORKLOADS[2], B=B)
+    rs = np.random.RandomState(77)
+    sizes, lens = [9, 20, 5], np.asarray([700, 130, 64], np.int64)
+    parents = [_random_parents(rs, n) for n in sizes]
+    par = np.concatenate([np.asarray(p, np.int32) for p in parents]).astype(np.int32)
+    no = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    po = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    parts = [W.attention_inputs(w, 3, s, 0, sizes[s], "unit", parent=np.asarray(parents[s])) for s in range(B)]
+    q, kt, vt = (np.concatenate([p[i] for p in parts], axis=0) for i in (0, 3, 4))
+    dq, dkt, dvt, dpar, dno, dl = G.dev_store(q), G.dev_store(kt), G.dev_store(vt), G.dev(par), G.dev(no), G.dev(lens)
+    layouts = []
+    for k, caps in enumerate(([800, 200, 64], [1500, 130, 900])):
+        co = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+        fill = [W.attention_inputs(w, 10 + k, s, caps[s], 1, "unit") for s in range(B)]
+        kc, vc = (np.concatenate([p[i] for p in fill], axis=0) for i in (1, 2))
+        used_k = np.concatenate([kc[co[s]:co[s] + lens[s]] for s in range(B)], axis=0)
+        used_v = np.concatenate([vc[co[s]:co[s] + lens[s]] for s in range(B)], axis=0)
+        want, _ = tree_attention(q, used_k, used_v, kt, vt, par, no, po, 1.0 / np.sqrt(w.D))
+        layouts.append((G.dev_store(kc), G.dev_store(vc), G.dev(co), co, want))
+    assert np.abs(layouts[0][4] - layouts[1][4]).max() > 0.05     # (the two layouts hold different keys)
+    for turn in range(4):
+        dk, dv, dco, co, want = layouts[turn % 2]
+        o, _ = hs.hs_tree_attention(dq, dk, dv, dkt, dvt, dpar, dno, dco, torch.from_numpy(no), torch.from_numpy(co),
+                                    1.0 / float(np.sqrt(w.D)), prefix_lens=dl, host_prefix_lens=torch.from_numpy(lens.copy()))
+        assert np.abs(G.host(o).astype(np.float64) - want).max() <= 2e-2, turn
+
+
 def test_verify_commit_loop_over_layers(G):
     """Three decoding steps of a two-layer model slice, each: tree attention of every layer over its
     own cache, greedy accept walk on target logits, commit of the accepted path into every layer's
