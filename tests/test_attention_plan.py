@@ -104,6 +104,36 @@ def test_plans_are_remembered_per_input_not_per_call_order():
     assert np.array_equal(t_a, t_a2) and np.array_equal(p_a, p_a2)
 
 
+def test_plans_from_several_threads_at_once():
+    """Planning state is per calling thread: four threads planning different batches at the same time (the
+    foreign calls run without the interpreter lock) get what a single thread gets."""
+    import threading
+    rs = np.random.RandomState(5)
+    shapes = []
+    for _ in range(24):
+        B = int(rs.randint(1, 30))
+        shapes.append(([int(x) for x in rs.choice([1, 9, 61, 129, 300], size=B)],
+                       [int(x) for x in rs.choice([0, 64, 700, 2048, 9000, 40000], size=B)], 32, 8))
+    want = [_plan(*sh) for sh in shapes]
+    errors = []
+
+    def work(tid):
+        try:
+            for rep in range(6):
+                for k in range(tid, len(shapes), 4):
+                    t, p = _plan(*shapes[k])
+                    assert np.array_equal(t, want[k][0]) and np.array_equal(p, want[k][1]), (tid, rep, k)
+        except Exception as e:          # noqa: BLE001 (reported below, in the main thread)
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+
+
 def test_the_ragged_batch_is_cut_into_comparable_items():
     totals, per = _plan(W5_M, W5_L, 32, 8)
     _check_work_list(W5_M, W5_L, 32, 8, 128, totals, per)
