@@ -220,7 +220,7 @@ hs_status hs_tree_prune_static(const int32_t* parent, const float* logc, const i
  * (128 bytes per tree row, included in the workspace query).
  * Workspace: one partial record of D + 4 floats per (tree row, query head, key split); the query
  * returns the bound for min(64, total_prefix / 128 + 1) splits, more than any plan of that batch
- * uses.  The host keeps the last few plans per calling thread (a model's layers share theirs); the
+ * uses (a batch whose keys are not cut needs none; hs_tree_attention_plan tells what a given batch needs).  The host keeps the last few plans per calling thread (a model's layers share theirs); the
  * calls stay re-entrant across threads and hold no device state.
  */
 size_t hs_tree_attention_workspace(int32_t B, int32_t NN, int64_t total_prefix,
